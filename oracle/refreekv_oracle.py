@@ -1,0 +1,275 @@
+"""Float64 CPU oracle for the ReFreeKV post-prefill compression pass.
+
+TEST INFRASTRUCTURE ONLY.  This module is the yardstick the HIP path is judged
+against; it is imported by the tests, by the smoke check and by the benchmark's
+CPU-baseline leg, and by nothing else.  It shares no code with the GPU path and
+must never be used as a fallback for it.
+
+Everything here is written from the paper's definitions, slowly and plainly:
+
+* window attention rows  -- causal softmax(Q K^T / sqrt(d)) for the last k query
+  positions (Sec. 3.2 "Reducing Overhead"; Alg. 1, the `Attention(Q[-1], K^T)` step);
+* the reduced vector A'  -- column mean of those rows over the rows that can see
+  the column (Eq. 2);
+* GQA reduction          -- mean of A' over the query heads sharing a KV head
+  (the paper is silent; any positive rescaling leaves the budget rule unchanged);
+* initial ranking        -- position based, first m then the rest reversed
+  (Sec. 3.2 "Initial Ranking"), or by descending score (Sec. 4.4 ablation);
+* Uni-Metric budget rule -- leftmost ranked prefix whose Frobenius norm is
+  within T of the full norm (Eq. 1), in the masked-norm *definition* form and in
+  the cumulative square-sum form (Eq. 3);
+* compaction             -- gather of the retained K/V rows (Alg. 1, last steps),
+  emitted in ascending original position.
+
+All floating point is float64.  Inputs arrive already upcast (bf16/fp32 -> fp64
+is exact), so the oracle sees the same values the GPU sees.
+
+Pinned by tests/test_oracle_*.py: softmax row sums, the k = 1 special case
+against a library softmax, the full n x n attention matrix on tiny inputs,
+closed forms of the budget rule (uniform / one-hot / geometric / two-level),
+definition-form == cumsum-form, exhaustive subset search for the score ranking,
+literal prefix enumeration for the position ranking, T = 0 / T >= 1 limits,
+and attention over the compacted cache == masked full attention.  The paper
+prints no worked numeric example of the rule, so there is no paper-value pin;
+results on the paper's real datasets/models are parity-unpinned.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+RANK_POSITION = 0   # Sec. 3.2 "Initial Ranking" (paper default)
+RANK_SCORE = 1      # Sec. 4.4 "Initial Ranking Strategies" (ablation)
+
+# above this length the O(n^2) definition form is skipped in favour of Eq. 3
+DEFINITION_FORM_MAX_N = 4096
+
+
+# ----------------------------------------------------------------------------
+# scoring  (Sec. 3.2 "Reducing Overhead", Eq. 2)
+# ----------------------------------------------------------------------------
+def window_attention(q_rows: np.ndarray, k_rows: np.ndarray, scale: float) -> np.ndarray:
+    """Causal softmax attention of the last w' query positions over all n keys.
+
+    q_rows [w', d], k_rows [n, d] (float64).  Row t is the query at absolute
+    position n - w' + t; it sees keys 0 .. n - w' + t.  Returns P [w', n] with
+    exact zeros at the causally hidden entries.
+    """
+    q_rows = np.asarray(q_rows, dtype=np.float64)
+    k_rows = np.asarray(k_rows, dtype=np.float64)
+    wp, n = q_rows.shape[0], k_rows.shape[0]
+    assert wp <= n
+    logits = (q_rows @ k_rows.T) * scale
+    P = np.zeros((wp, n), dtype=np.float64)
+    for t in range(wp):
+        last = n - wp + t                      # last visible key of this row
+        row = logits[t, : last + 1]
+        e = np.exp(row - row.max())
+        P[t, : last + 1] = e / e.sum()
+    return P
+
+
+def causal_counts(n: int, wp: int) -> np.ndarray:
+    """Number of window rows that can see key i (denominator of Eq. 2)."""
+    i = np.arange(n)
+    return np.minimum(wp, n - i).astype(np.float64)
+
+
+def reduced_attention_vector(P: np.ndarray) -> np.ndarray:
+    """Eq. 2: per-column mean of the window rows over the rows that see the column."""
+    wp, n = P.shape
+    return P.sum(axis=0) / causal_counts(n, wp)
+
+
+def score_unit(q_unit: np.ndarray, k_unit: np.ndarray, scale: float) -> np.ndarray:
+    """A' for one (sequence, KV head).  q_unit [w', G, d], k_unit [n, d]."""
+    wp, G, _ = q_unit.shape
+    n = k_unit.shape[0]
+    acc = np.zeros(n, dtype=np.float64)
+    for g in range(G):
+        acc += reduced_attention_vector(window_attention(q_unit[:, g, :], k_unit, scale))
+    return acc / G
+
+
+def oracle_score(q_win, k, cu_seqlens, n_q_heads, n_kv_heads, window, scale=None):
+    """Scores [Hkv, N] for a packed ragged batch.
+
+    q_win [sum_b min(window, n_b), Hq, d] holds, per sequence, the queries of its
+    last min(window, n_b) positions; k [N, Hkv, d]; cu_seqlens [B+1].
+    """
+    q_win = np.asarray(q_win, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    N, Hkv, d = k.shape
+    assert Hkv == n_kv_heads and n_q_heads % n_kv_heads == 0
+    G = n_q_heads // n_kv_heads
+    if scale is None or scale == 0:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((Hkv, N), dtype=np.float64)
+    q0 = 0
+    for b in range(len(cu_seqlens) - 1):
+        s, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        n = e - s
+        wp = min(window, n)
+        for h in range(Hkv):
+            if n > 0:
+                out[h, s:e] = score_unit(q_win[q0:q0 + wp, h * G:(h + 1) * G, :], k[s:e, h, :], scale)
+        q0 += wp
+    return out
+
+
+# ----------------------------------------------------------------------------
+# ranking  (Sec. 3.2 "Initial Ranking"; Sec. 4.4 ablation)
+# ----------------------------------------------------------------------------
+def rank_positions(scores_unit: np.ndarray, rank_mode: int, n_sink: int) -> np.ndarray:
+    """Permutation: rank r (0-based) -> position (0-based)."""
+    n = len(scores_unit)
+    if rank_mode == RANK_POSITION:
+        if n <= n_sink:
+            return np.arange(n)
+        return np.concatenate([np.arange(n_sink), np.arange(n - 1, n_sink - 1, -1)])
+    if rank_mode == RANK_SCORE:
+        # descending score, equal scores keep ascending position
+        return np.argsort(-np.asarray(scores_unit, dtype=np.float64), kind="stable")
+    raise ValueError("rank_mode")
+
+
+# ----------------------------------------------------------------------------
+# Uni-Metric budget rule  (Eq. 1, Eq. 3)
+# ----------------------------------------------------------------------------
+def budget_definition(s_ranked: np.ndarray, T: float) -> int:
+    """Eq. 1 literally: for each i build the vector with ranks > i masked out, take
+    its norm afresh, stop at the first i with 1 - norm_i / norm_full < T.
+    Returns i* in 1..n (n if no i qualifies or the full norm is zero)."""
+    s = np.asarray(s_ranked, dtype=np.float64)
+    n = len(s)
+    F = np.sqrt(np.sum(s * s))
+    if n == 0 or F == 0.0:
+        return n
+    for i in range(1, n + 1):
+        masked = s.copy()
+        masked[i:] = 0.0
+        if 1.0 - np.sqrt(np.sum(masked * masked)) / F < T:
+            return i
+    return n
+
+
+def budget_cumsum(s_ranked: np.ndarray, T: float) -> int:
+    """Eq. 3: the same rule through the cumulative square-sum."""
+    s = np.asarray(s_ranked, dtype=np.float64)
+    n = len(s)
+    if n == 0:
+        return 0
+    C = np.sqrt(np.cumsum(s * s))
+    F = C[-1]
+    if F == 0.0:
+        return n
+    hit = np.nonzero(1.0 - C / F < T)[0]
+    return int(hit[0]) + 1 if len(hit) else n
+
+
+def select_unit(scores_unit, rank_mode, n_sink, T, min_keep=0, form="auto"):
+    """(kept, idx): number of retained positions and their indices, ascending."""
+    n = len(scores_unit)
+    if n == 0:
+        return 0, np.zeros(0, dtype=np.int64)
+    rank = rank_positions(scores_unit, rank_mode, n_sink)
+    s_ranked = np.asarray(scores_unit, dtype=np.float64)[rank]
+    if form == "auto":
+        form = "definition" if n <= DEFINITION_FORM_MAX_N else "cumsum"
+    i_star = budget_definition(s_ranked, T) if form == "definition" else budget_cumsum(s_ranked, T)
+    kept = min(n, max(i_star, int(min_keep)))
+    return kept, np.sort(rank[:kept])
+
+
+def oracle_select(scores, cu_seqlens, rank_mode, n_sink, T, min_keep=0, form="auto"):
+    """Per unit u = b*Hkv + h: kept[u]; out_offsets = exclusive scan of kept;
+    idx = retained positions (relative to the sequence start), ascending,
+    packed unit after unit."""
+    Hkv = scores.shape[0]
+    B = len(cu_seqlens) - 1
+    kept = np.zeros(B * Hkv, dtype=np.int64)
+    chunks = []
+    for b in range(B):
+        s, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        for h in range(Hkv):
+            c, idx = select_unit(scores[h, s:e], rank_mode, n_sink, T, min_keep, form)
+            kept[b * Hkv + h] = c
+            chunks.append(idx)
+    offs = np.concatenate([[0], np.cumsum(kept)]).astype(np.int64)
+    idx = np.concatenate(chunks) if chunks else np.zeros(0, dtype=np.int64)
+    return kept, offs, idx
+
+
+# ----------------------------------------------------------------------------
+# compaction  (Alg. 1, "Compress K / V by R")
+# ----------------------------------------------------------------------------
+def oracle_compact(k, v, cu_seqlens, kept, out_offsets, idx):
+    """Gather rows.  k, v [N, Hkv, d] in any storage dtype (moved bit for bit).
+    Returns k_out, v_out [sum kept, d]."""
+    N, Hkv, d = k.shape
+    total = int(out_offsets[-1])
+    k_out = np.zeros((total, d), dtype=k.dtype)
+    v_out = np.zeros((total, d), dtype=v.dtype)
+    B = len(cu_seqlens) - 1
+    for b in range(B):
+        s = int(cu_seqlens[b])
+        for h in range(Hkv):
+            u = b * Hkv + h
+            o = int(out_offsets[u])
+            for t in range(int(kept[u])):
+                p = s + int(idx[o + t])
+                k_out[o + t] = k[p, h]
+                v_out[o + t] = v[p, h]
+    return k_out, v_out
+
+
+def oracle_compress_layer(q_win_f64, k_f64, k_raw, v_raw, cu_seqlens, n_q_heads, n_kv_heads,
+                          window, n_sink=4, T=0.01, rank_mode=RANK_POSITION, min_keep=0,
+                          scale=None, form="auto"):
+    """One layer: score -> rank -> budget rule -> compact (Alg. 1 loop body)."""
+    scores = oracle_score(q_win_f64, k_f64, cu_seqlens, n_q_heads, n_kv_heads, window, scale)
+    kept, offs, idx = oracle_select(scores, cu_seqlens, rank_mode, n_sink, T, min_keep, form)
+    k_out, v_out = oracle_compact(k_raw, v_raw, cu_seqlens, kept, offs, idx)
+    return dict(scores=scores, kept=kept, out_offsets=offs, idx=idx, k_out=k_out, v_out=v_out)
+
+
+# ----------------------------------------------------------------------------
+# helpers for the invariants the tests use
+# ----------------------------------------------------------------------------
+def attention_output(q_new, k_rows, v_rows, scale, keep_mask=None):
+    """softmax(q K^T * scale) V for queries that see every key; positions with
+    keep_mask == False get logit -inf.  Used for the compaction invariant."""
+    logits = (np.asarray(q_new, np.float64) @ np.asarray(k_rows, np.float64).T) * scale
+    if keep_mask is not None:
+        logits = np.where(keep_mask[None, :], logits, -np.inf)
+    logits = logits - logits.max(axis=1, keepdims=True)
+    e = np.exp(logits)
+    return (e / e.sum(axis=1, keepdims=True)) @ np.asarray(v_rows, np.float64)
+
+
+def cut_robustness(scores_unit, rank_mode, n_sink, T, rel=1e-3):
+    """Is the oracle's cut far enough from a rounding edge that a correct fp32
+    implementation must reproduce it exactly?  Returns (robust, i_star).
+
+    With g(i) = P_i / F^2 and tau = (1 - T)^2 the rule picks the step of g that
+    straddles tau.  The unit is robust when tau sits more than `rel` of that
+    step's height away from both of its edges and, in score ranking, the scores
+    on the two sides of the cut differ by more than `rel` relative.
+    """
+    n = len(scores_unit)
+    rank = rank_positions(scores_unit, rank_mode, n_sink)
+    s = np.asarray(scores_unit, np.float64)[rank]
+    i_star = budget_cumsum(s, T)
+    if n == 0:
+        return True, 0
+    P = np.cumsum(s * s)
+    F2 = P[-1]
+    if F2 == 0.0 or T <= 0.0 or T >= 1.0:
+        return True, i_star          # keep-all / keep-one limits do not depend on rounding
+    tau = (1.0 - T) ** 2
+    g_hi = P[i_star - 1] / F2
+    g_lo = P[i_star - 2] / F2 if i_star >= 2 else 0.0
+    step = g_hi - g_lo
+    robust = step > 0 and min(g_hi - tau, tau - g_lo) > rel * step
+    if rank_mode == RANK_SCORE and i_star < n:
+        robust = robust and abs(s[i_star - 1] - s[i_star]) > rel * abs(s[i_star - 1])
+    return bool(robust), i_star
