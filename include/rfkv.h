@@ -1,0 +1,168 @@
+/*
+ * rfkv -- threshold-free KV-cache compression (ReFreeKV) for AMD MI355X (gfx950).
+ *
+ * C ABI of the post-prefill compression pass: for one transformer layer and a
+ * packed ragged batch of prefilled sequences, score every cached position by
+ * the causal softmax attention a window of the most recent queries pays to it,
+ * rank the positions, apply the paper's norm-ratio budget rule and gather the
+ * retained K/V rows into a ragged per-(sequence, KV head) cache.
+ *
+ * Conventions shared by every entry point
+ *   - A *unit* is one (sequence b, KV head h), numbered u = b * n_kv_heads + h.
+ *   - B = batch, n_b = tokens of sequence b, N = sum n_b, w'_b = min(window, n_b),
+ *     G = n_q_heads / n_kv_heads.
+ *   - "device" pointers are HIP device memory owned by the caller and must be
+ *     16-byte aligned; "host" pointers are ordinary host memory.  The library
+ *     never allocates, frees or retains memory and never synchronises: all work
+ *     is enqueued on the HIP stream passed as `stream` (a hipStream_t; NULL is
+ *     the default stream).  Buffers must stay alive until that work has run.
+ *   - cu_seqlens (int32, B + 1 entries, cu[0] = 0, non-decreasing, cu[B] = N) is
+ *     passed twice: a host copy, used for validation and launch geometry, and a
+ *     device copy with the same contents, read by the kernels.
+ *   - Every call validates its arguments on the host before touching the GPU
+ *     and returns a status; nothing is enqueued unless the status is RFKV_OK.
+ *     Results that depend on device data (kept counts) are never read back.
+ *   - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef RFKV_H
+#define RFKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define RFKV_API __attribute__((visibility("default")))
+#else
+#define RFKV_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rfkv_status {
+  RFKV_OK = 0,
+  RFKV_INVALID_ARG = 1,          /* null / misaligned pointer, inconsistent sizes or cu_seqlens   */
+  RFKV_UNSUPPORTED = 2,          /* dtype, head_dim or window * G outside what the kernels cover  */
+  RFKV_WORKSPACE_TOO_SMALL = 3,  /* ws_bytes < rfkv_workspace_bytes(...)                          */
+  RFKV_OUTPUT_TOO_SMALL = 4,     /* a capacity the host can check is too small                    */
+  RFKV_DEVICE_ERROR = 5          /* a HIP call failed; see rfkv_last_device_error()               */
+} rfkv_status;
+
+enum { RFKV_RANK_POSITION = 0, RFKV_RANK_SCORE = 1 };
+enum { RFKV_DTYPE_FP32 = 0, RFKV_DTYPE_BF16 = 1 };
+
+/* Limits of this build. */
+enum {
+  RFKV_MAX_SCORE_ROWS = 512,     /* window * G, after rounding up to a multiple of 32             */
+  RFKV_MAX_UNITS = 65535         /* B * n_kv_heads                                                */
+};
+
+/*
+ * Problem description.  Symbols follow the paper: `window` is its k (number of
+ * last attention rows averaged into A', Sec. 3.2 "Reducing Overhead", Eq. 2),
+ * `n_sink` its m (positions ranked first, Sec. 3.2 "Initial Ranking"),
+ * `threshold` its T (Eq. 1; the universal value is 0.01).
+ */
+typedef struct rfkv_params {
+  int32_t batch;            /* B >= 0                                                             */
+  int32_t n_q_heads;        /* Hq, a multiple of n_kv_heads                                       */
+  int32_t n_kv_heads;       /* Hkv                                                                */
+  int32_t head_dim;         /* d: 64 or 128                                                       */
+  int32_t window;           /* k >= 1; rows used per sequence = min(window, n_b)                  */
+  int32_t n_sink;           /* m >= 0, used by RFKV_RANK_POSITION only                            */
+  float   threshold;        /* T; <= 0 keeps everything, >= 1 keeps one position                  */
+  int32_t rank_mode;        /* RFKV_RANK_POSITION (the paper's method) or RFKV_RANK_SCORE
+                               (descending A', equal scores by ascending position; Sec. 4.4)      */
+  int32_t dtype;            /* storage type of Q, K, V: RFKV_DTYPE_FP32 or RFKV_DTYPE_BF16        */
+  float   softmax_scale;    /* logit scale; 0 selects 1 / sqrt(head_dim)                          */
+  int32_t min_keep;         /* floor on the kept count per unit (0 = the paper's rule alone)      */
+  /* strides in elements; the head_dim axis is contiguous.  Token index is the packed index
+     0..N-1 for K/V and the packed window-row index 0..sum_b w'_b - 1 for Q.                      */
+  int64_t k_stride_tok, k_stride_head;
+  int64_t v_stride_tok, v_stride_head;
+  int64_t q_stride_row, q_stride_head;
+} rfkv_params;
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+RFKV_API int32_t rfkv_version(void);
+
+/* Static, human-readable name of a status code. */
+RFKV_API const char* rfkv_status_string(rfkv_status status);
+
+/* hipError_t (as int) of the most recent RFKV_DEVICE_ERROR on the calling thread, 0 if none. */
+RFKV_API int32_t rfkv_last_device_error(void);
+
+/*
+ * Bytes of device scratch that rfkv_score / rfkv_select / rfkv_compress_layer need for a batch
+ * with `total_tokens` = N and longest sequence `max_seqlen`.  Pure host arithmetic; returns 0 if
+ * `params` is NULL or describes an unsupported problem.  The workspace contents need no
+ * initialisation and carry nothing from one call to the next.
+ */
+RFKV_API size_t rfkv_workspace_bytes(const rfkv_params* params, int64_t total_tokens, int32_t max_seqlen);
+
+/*
+ * Scoring (Sec. 3.2 "Reducing Overhead", Eq. 2; Alg. 1 "Attention(Q[-1], K^T)").
+ *   scores[h * N + cu[b] + i] = (1/G) sum_g (1/cnt_i) sum_{t : i <= n_b - w'_b + t} P[t, g, i]
+ * where P[t, g, :] is the causal softmax of scale * q_{t,g} . k_i over the keys i the window row
+ * t (absolute position n_b - w'_b + t) can see, and cnt_i = min(w'_b, n_b - i) is the number of
+ * window rows that see key i.
+ *   q_win   device, [sum_b w'_b, Hq, d] through q_stride_*: the (post-RoPE) queries of the last
+ *           w'_b positions of each sequence, sequences packed in batch order
+ *   k       device, [N, Hkv, d] through k_stride_*
+ *   scores  device, float [Hkv, N], written in full
+ *   ws      device scratch of at least rfkv_workspace_bytes(...)
+ * bf16 inputs are multiplied on the matrix cores with fp32 accumulation; softmax and the
+ * reductions run in fp32.
+ */
+RFKV_API rfkv_status rfkv_score(const rfkv_params* params, const void* q_win, const void* k,
+                       const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
+                       float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Ranking + budget rule (Sec. 3.2 "Initial Ranking", Eq. 1; Sec. 3.3, Eq. 3).  For each unit, with
+ * s[r] the score at rank r and P_i = sum_{r <= i} s[r]^2, F^2 = P_n:
+ *   i* = min { i : 1 - sqrt(P_i) / F < T }   (n if there is none or F = 0),
+ *   kept = min(n, max(i*, min_keep)),
+ * and the retained set is ranks 1..kept.  P is accumulated exactly (integer fixed point scaled by
+ * F^2, resolution 2^-60), so the result does not depend on reduction order.
+ *   scores       device, float [Hkv, N] as written by rfkv_score
+ *   kept         device, int32 [B * Hkv]
+ *   out_offsets  device, int64 [B * Hkv + 1], exclusive prefix sum of kept
+ *   idx          device, int32, capacity N * Hkv: retained positions relative to their sequence
+ *                start, ascending, unit u at idx[out_offsets[u] .. out_offsets[u+1])
+ */
+RFKV_API rfkv_status rfkv_select(const rfkv_params* params, const float* scores,
+                        const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
+                        int32_t* kept, int64_t* out_offsets, int32_t* idx,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Compaction (Alg. 1, "Compress K / V by R"): k_out[out_offsets[u] + t] = K[cu[b] + idx[...], h]
+ * and the same for V, rows in ascending original position, moved bit for bit.
+ *   kept, out_offsets, idx   device, as produced by rfkv_select
+ *   k_out, v_out             device, [out_capacity_rows, d] contiguous.  Rows at or beyond
+ *                            out_capacity_rows are not written; N * Hkv rows always suffice.
+ */
+RFKV_API rfkv_status rfkv_compact(const rfkv_params* params, const void* k, const void* v,
+                         const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
+                         const int32_t* kept, const int64_t* out_offsets, const int32_t* idx,
+                         void* k_out, void* v_out, int64_t out_capacity_rows, void* stream);
+
+/*
+ * One layer of Alg. 1's loop body: score -> rank -> budget rule -> compaction, enqueued
+ * back to back with no host synchronisation.  Arguments as above; `scores_opt` may be NULL
+ * (scores then live in the workspace only) and `idx_opt` may be NULL (indices not reported).
+ * Layers the caller wants to leave uncompressed (the paper keeps the first two, Sec. 3.3
+ * "Retaining Bottom Layers") are simply not passed to the library.
+ */
+RFKV_API rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, const void* k,
+                                const void* v, const int32_t* cu_seqlens_host,
+                                const int32_t* cu_seqlens_dev, float* scores_opt, int32_t* kept,
+                                int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
+                                int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RFKV_H */

@@ -1,0 +1,207 @@
+"""ctypes binding of librfkv.so -- argument marshalling only.
+
+The functions have the names and meanings of the C entry points in include/rfkv.h.
+torch is used for device memory (`torch.empty`, `data_ptr`) and the current HIP
+stream; every step of the computation runs inside the library's kernels.  There
+is no fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+RFKV_OK = 0
+RFKV_INVALID_ARG = 1
+RFKV_UNSUPPORTED = 2
+RFKV_WORKSPACE_TOO_SMALL = 3
+RFKV_OUTPUT_TOO_SMALL = 4
+RFKV_DEVICE_ERROR = 5
+
+RANK_POSITION = 0
+RANK_SCORE = 1
+DTYPE_FP32 = 0
+DTYPE_BF16 = 1
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librfkv.so")
+
+
+class RfkvParams(ctypes.Structure):
+    """Mirror of `rfkv_params`."""
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("window", ctypes.c_int32), ("n_sink", ctypes.c_int32),
+        ("threshold", ctypes.c_float), ("rank_mode", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("min_keep", ctypes.c_int32),
+        ("k_stride_tok", ctypes.c_int64), ("k_stride_head", ctypes.c_int64),
+        ("v_stride_tok", ctypes.c_int64), ("v_stride_head", ctypes.c_int64),
+        ("q_stride_row", ctypes.c_int64), ("q_stride_head", ctypes.c_int64),
+    ]
+
+
+class RfkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen librfkv.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2502_16886_amd.build` "
+            "(there is no CPU fallback for the compression pass)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(RfkvParams)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    lib.rfkv_version.restype = i32
+    lib.rfkv_version.argtypes = []
+    lib.rfkv_status_string.restype = ctypes.c_char_p
+    lib.rfkv_status_string.argtypes = [ctypes.c_int]
+    lib.rfkv_last_device_error.restype = i32
+    lib.rfkv_last_device_error.argtypes = []
+    lib.rfkv_workspace_bytes.restype = sz
+    lib.rfkv_workspace_bytes.argtypes = [P, i64, i32]
+    lib.rfkv_score.restype = ctypes.c_int
+    lib.rfkv_score.argtypes = [P, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.rfkv_select.restype = ctypes.c_int
+    lib.rfkv_select.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.rfkv_compact.restype = ctypes.c_int
+    lib.rfkv_compact.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+    lib.rfkv_compress_layer.restype = ctypes.c_int
+    lib.rfkv_compress_layer.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+EXPORTED_SYMBOLS = ("rfkv_version", "rfkv_status_string", "rfkv_last_device_error", "rfkv_workspace_bytes",
+                    "rfkv_score", "rfkv_select", "rfkv_compact", "rfkv_compress_layer")
+
+
+def status_string(status: int) -> str:
+    return load_library().rfkv_status_string(int(status)).decode()
+
+
+def rfkv_version() -> int:
+    return int(load_library().rfkv_version())
+
+
+def rfkv_last_device_error() -> int:
+    return int(load_library().rfkv_last_device_error())
+
+
+def rfkv_workspace_bytes(params: RfkvParams, total_tokens: int, max_seqlen: int) -> int:
+    return int(load_library().rfkv_workspace_bytes(ctypes.byref(params), int(total_tokens), int(max_seqlen)))
+
+
+def _ptr(x) -> int | None:
+    """Address of a torch tensor / numpy array / raw int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    return x.ctypes.data           # numpy (host)
+
+
+def _stream(stream) -> int | None:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _check(status: int, where: str, check: bool) -> int:
+    if check and status != RFKV_OK:
+        raise RfkvError(status, where)
+    return status
+
+
+def rfkv_score(params, q_win, k, cu_host, cu_dev, scores, ws, ws_bytes, stream=None, check=True) -> int:
+    st = load_library().rfkv_score(ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(cu_host), _ptr(cu_dev),
+                                   _ptr(scores), _ptr(ws), int(ws_bytes), _stream(stream))
+    return _check(st, "rfkv_score", check)
+
+
+def rfkv_select(params, scores, cu_host, cu_dev, kept, out_offsets, idx, ws, ws_bytes, stream=None,
+                check=True) -> int:
+    st = load_library().rfkv_select(ctypes.byref(params), _ptr(scores), _ptr(cu_host), _ptr(cu_dev), _ptr(kept),
+                                    _ptr(out_offsets), _ptr(idx), _ptr(ws), int(ws_bytes), _stream(stream))
+    return _check(st, "rfkv_select", check)
+
+
+def rfkv_compact(params, k, v, cu_host, cu_dev, kept, out_offsets, idx, k_out, v_out, out_capacity_rows,
+                 stream=None, check=True) -> int:
+    st = load_library().rfkv_compact(ctypes.byref(params), _ptr(k), _ptr(v), _ptr(cu_host), _ptr(cu_dev),
+                                     _ptr(kept), _ptr(out_offsets), _ptr(idx), _ptr(k_out), _ptr(v_out),
+                                     int(out_capacity_rows), _stream(stream))
+    return _check(st, "rfkv_compact", check)
+
+
+def rfkv_compress_layer(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, out_offsets, idx_opt, k_out,
+                        v_out, out_capacity_rows, ws, ws_bytes, stream=None, check=True) -> int:
+    st = load_library().rfkv_compress_layer(ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(v), _ptr(cu_host),
+                                            _ptr(cu_dev), _ptr(scores_opt), _ptr(kept), _ptr(out_offsets),
+                                            _ptr(idx_opt), _ptr(k_out), _ptr(v_out), int(out_capacity_rows),
+                                            _ptr(ws), int(ws_bytes), _stream(stream))
+    return _check(st, "rfkv_compress_layer", check)
+
+
+# ----------------------------------------------------------------------------
+# convenience: parameter struct for contiguous [N, Hkv, d] / [rows, Hq, d] tensors
+# ----------------------------------------------------------------------------
+def make_params(batch, n_q_heads, n_kv_heads, head_dim, window, dtype, n_sink=4, threshold=0.01,
+                rank_mode=RANK_POSITION, softmax_scale=0.0, min_keep=0) -> RfkvParams:
+    p = RfkvParams()
+    p.batch, p.n_q_heads, p.n_kv_heads, p.head_dim = batch, n_q_heads, n_kv_heads, head_dim
+    p.window, p.n_sink, p.threshold, p.rank_mode = window, n_sink, threshold, rank_mode
+    p.dtype = DTYPE_BF16 if dtype in ("bf16", DTYPE_BF16) else DTYPE_FP32
+    p.softmax_scale, p.min_keep = softmax_scale, min_keep
+    p.k_stride_tok = p.v_stride_tok = n_kv_heads * head_dim
+    p.k_stride_head = p.v_stride_head = head_dim
+    p.q_stride_row = n_q_heads * head_dim
+    p.q_stride_head = head_dim
+    return p
+
+
+@dataclass
+class LayerBuffers:
+    """Device buffers for one rfkv_compress_layer call (all owned by the caller)."""
+    scores: object
+    kept: object
+    out_offsets: object
+    idx: object
+    k_out: object
+    v_out: object
+    ws: object
+    ws_bytes: int
+    capacity_rows: int
+
+
+def alloc_layer_buffers(params: RfkvParams, total_tokens: int, max_seqlen: int, device="cuda",
+                        capacity_rows: int | None = None) -> LayerBuffers:
+    import torch
+    units = params.batch * params.n_kv_heads
+    rows = total_tokens * params.n_kv_heads if capacity_rows is None else capacity_rows
+    tdt = torch.bfloat16 if params.dtype == DTYPE_BF16 else torch.float32
+    ws_bytes = rfkv_workspace_bytes(params, total_tokens, max_seqlen)
+    if ws_bytes == 0 and total_tokens > 0:
+        raise RfkvError(RFKV_UNSUPPORTED, "rfkv_workspace_bytes")
+    return LayerBuffers(
+        scores=torch.empty((params.n_kv_heads, total_tokens), dtype=torch.float32, device=device),
+        kept=torch.empty(units, dtype=torch.int32, device=device),
+        out_offsets=torch.empty(units + 1, dtype=torch.int64, device=device),
+        idx=torch.empty(max(1, total_tokens * params.n_kv_heads), dtype=torch.int32, device=device),
+        k_out=torch.empty((max(1, rows), params.head_dim), dtype=tdt, device=device),
+        v_out=torch.empty((max(1, rows), params.head_dim), dtype=tdt, device=device),
+        ws=torch.empty(max(256, ws_bytes), dtype=torch.uint8, device=device),
+        ws_bytes=ws_bytes, capacity_rows=rows)

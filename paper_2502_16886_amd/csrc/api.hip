@@ -1,0 +1,319 @@
+// C-ABI layer of librfkv: host-side validation, launch geometry, workspace carving and the
+// kernel launch sequences.  The contract of every entry point is documented in include/rfkv.h.
+#include "../../include/rfkv.h"
+
+#include <cmath>
+#include <cstring>
+
+#include "kernels.h"
+
+namespace rfkv {
+
+static thread_local int32_t g_last_device_error = 0;
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+Workspace carve_workspace(const Geometry& g, void* base) {
+  Workspace w{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    void* p = base ? static_cast<unsigned char*>(base) + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  };
+  w.partials = static_cast<float2*>(take((size_t)g.units * g.nspans * g.rows_pad * sizeof(float2)));
+  w.bvec = static_cast<float*>(take((size_t)g.units * g.rows_pad * sizeof(float)));
+  w.desc = static_cast<int4*>(take((size_t)g.units * sizeof(int4)));
+  w.idx_pad = static_cast<int32_t*>(take((size_t)g.total_tokens * g.n_kv_heads * sizeof(int32_t)));
+  w.scores = static_cast<float*>(take((size_t)g.total_tokens * g.n_kv_heads * sizeof(float)));
+  w.bytes = off;
+  return w;
+}
+
+namespace {
+
+// keys one score workgroup covers: enough workgroups to fill 256 CUs a few times over, but long
+// enough that staging the window queries (once per workgroup) stays a small part of its traffic
+int32_t choose_span(int64_t total_tokens, int32_t n_kv_heads) {
+  const int64_t work = total_tokens * n_kv_heads;      // keys to score in the layer
+  int64_t span = (work / 1024 + kKeysPerIter - 1) / kKeysPerIter * kKeysPerIter;
+  if (span < 2 * kKeysPerIter) span = 2 * kKeysPerIter;
+  if (span > 16 * kKeysPerIter) span = 16 * kKeysPerIter;
+  return (int32_t)span;
+}
+
+rfkv_status check_params(const rfkv_params* p) {
+  if (!p) return RFKV_INVALID_ARG;
+  if (p->batch < 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0 || p->window < 1 || p->n_sink < 0 ||
+      p->min_keep < 0)
+    return RFKV_INVALID_ARG;
+  if (p->n_q_heads % p->n_kv_heads != 0) return RFKV_INVALID_ARG;
+  if (!(p->softmax_scale >= 0.f) || !std::isfinite(p->softmax_scale)) return RFKV_INVALID_ARG;
+  if (std::isnan(p->threshold)) return RFKV_INVALID_ARG;
+  if (p->rank_mode != RFKV_RANK_POSITION && p->rank_mode != RFKV_RANK_SCORE) return RFKV_INVALID_ARG;
+  if (p->dtype != RFKV_DTYPE_FP32 && p->dtype != RFKV_DTYPE_BF16) return RFKV_UNSUPPORTED;
+  if (p->head_dim != 64 && p->head_dim != 128) return RFKV_UNSUPPORTED;
+  const int64_t rows = (int64_t)p->window * (p->n_q_heads / p->n_kv_heads);
+  if ((rows + 31) / 32 * 32 > RFKV_MAX_SCORE_ROWS) return RFKV_UNSUPPORTED;
+  if ((int64_t)p->batch * p->n_kv_heads > RFKV_MAX_UNITS) return RFKV_UNSUPPORTED;
+  const int eb = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
+  // the window queries of one unit must fit in LDS next to the per-row tables
+  const int64_t rows_pad = (rows + 31) / 32 * 32;
+  if (rows_pad * (p->head_dim * eb + 16 + 8) > 156 * 1024) return RFKV_UNSUPPORTED;
+  return RFKV_OK;
+}
+
+rfkv_status check_strides(const rfkv_params* p, bool need_q, bool need_k, bool need_v) {
+  const int per16 = p->dtype == RFKV_DTYPE_BF16 ? 8 : 4;      // elements per 16 bytes
+  auto ok = [&](int64_t tok, int64_t head) {
+    return tok >= p->head_dim && head >= p->head_dim && tok % per16 == 0 && head % per16 == 0;
+  };
+  if (need_q && !ok(p->q_stride_row, p->q_stride_head)) return RFKV_INVALID_ARG;
+  if (need_k && !ok(p->k_stride_tok, p->k_stride_head)) return RFKV_INVALID_ARG;
+  if (need_v && !ok(p->v_stride_tok, p->v_stride_head)) return RFKV_INVALID_ARG;
+  return RFKV_OK;
+}
+
+bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+rfkv_status check_cu(const rfkv_params* p, const int32_t* cu_host, const int32_t* cu_dev, int64_t* total,
+                     int32_t* max_len) {
+  if (!cu_host || !cu_dev) return RFKV_INVALID_ARG;
+  if (cu_host[0] != 0) return RFKV_INVALID_ARG;
+  int32_t mx = 0;
+  for (int b = 0; b < p->batch; ++b) {
+    const int64_t len = (int64_t)cu_host[b + 1] - cu_host[b];
+    if (len < 0) return RFKV_INVALID_ARG;
+    if (len > mx) mx = (int32_t)len;
+  }
+  *total = cu_host[p->batch];
+  *max_len = mx;
+  if (*total * p->n_kv_heads >= (int64_t)1 << 31) return RFKV_UNSUPPORTED;   // int32 index lists
+  return RFKV_OK;
+}
+
+Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len) {
+  Geometry g{};
+  g.batch = p->batch;
+  g.n_q_heads = p->n_q_heads;
+  g.n_kv_heads = p->n_kv_heads;
+  g.group = p->n_q_heads / p->n_kv_heads;
+  g.head_dim = p->head_dim;
+  g.window = p->window;
+  g.units = p->batch * p->n_kv_heads;
+  g.rows_pad = (p->window * g.group + 31) / 32 * 32;
+  g.span = choose_span(total, p->n_kv_heads);
+  g.nspans = (max_len + g.span - 1) / g.span;
+  g.max_seqlen = max_len;
+  g.total_tokens = total;
+  g.elem_bytes = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
+  return g;
+}
+
+rfkv_status device_status(hipError_t e) {
+  if (e == hipSuccess) return RFKV_OK;
+  g_last_device_error = (int32_t)e;
+  return RFKV_DEVICE_ERROR;
+}
+
+float scale_times_log2e(const rfkv_params* p) {
+  const double s = p->softmax_scale > 0.f ? (double)p->softmax_scale : 1.0 / std::sqrt((double)p->head_dim);
+  return (float)(s * 1.4426950408889634);
+}
+
+hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w, const void* q, const void* k,
+                     const int32_t* cu_dev, float* scores, hipStream_t stream) {
+  ScoreArgs a{};
+  a.q = q;
+  a.k = k;
+  a.scores = scores;
+  a.cu = cu_dev;
+  a.partials = w.partials;
+  a.bvec = w.bvec;
+  a.k_stride_tok = p->k_stride_tok;
+  a.k_stride_head = p->k_stride_head;
+  a.q_stride_row = p->q_stride_row;
+  a.q_stride_head = p->q_stride_head;
+  a.total_tokens = g.total_tokens;
+  a.n_kv_heads = g.n_kv_heads;
+  a.group = g.group;
+  a.window = g.window;
+  a.rows_pad = g.rows_pad;
+  a.span = g.span;
+  a.nspans = g.nspans;
+  a.c = scale_times_log2e(p);
+  return launch_score(g, a, p->dtype == RFKV_DTYPE_BF16, stream);
+}
+
+hipError_t run_select(const rfkv_params* p, const Geometry& g, const Workspace& w, const float* scores,
+                      const int32_t* cu_dev, int32_t* kept, hipStream_t stream) {
+  SelectArgs a{};
+  a.scores = scores;
+  a.cu = cu_dev;
+  a.kept = kept;
+  a.desc = w.desc;
+  a.idx_pad = p->rank_mode == RFKV_RANK_SCORE ? w.idx_pad : nullptr;
+  a.total_tokens = g.total_tokens;
+  a.n_kv_heads = g.n_kv_heads;
+  a.n_sink = p->n_sink;
+  a.min_keep = p->min_keep;
+  a.rank_mode = p->rank_mode;
+  a.threshold = p->threshold;
+  return launch_select(g, a, stream);
+}
+
+CompactArgs compact_base(const rfkv_params* p, const Geometry& g, const int32_t* cu_dev, const int32_t* kept) {
+  CompactArgs a{};
+  a.cu = cu_dev;
+  a.kept = kept;
+  a.k_stride_tok = p->k_stride_tok * g.elem_bytes;
+  a.k_stride_head = p->k_stride_head * g.elem_bytes;
+  a.v_stride_tok = p->v_stride_tok * g.elem_bytes;
+  a.v_stride_head = p->v_stride_head * g.elem_bytes;
+  a.n_kv_heads = g.n_kv_heads;
+  a.units = g.units;
+  a.row_bytes = g.head_dim * g.elem_bytes;
+  return a;
+}
+
+}  // namespace
+}  // namespace rfkv
+
+using namespace rfkv;
+
+extern "C" {
+
+int32_t rfkv_version(void) { return 100; }
+
+const char* rfkv_status_string(rfkv_status status) {
+  switch (status) {
+    case RFKV_OK: return "ok";
+    case RFKV_INVALID_ARG: return "invalid argument";
+    case RFKV_UNSUPPORTED: return "unsupported problem";
+    case RFKV_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case RFKV_OUTPUT_TOO_SMALL: return "output too small";
+    case RFKV_DEVICE_ERROR: return "device error";
+  }
+  return "unknown status";
+}
+
+int32_t rfkv_last_device_error(void) { return g_last_device_error; }
+
+size_t rfkv_workspace_bytes(const rfkv_params* params, int64_t total_tokens, int32_t max_seqlen) {
+  if (check_params(params) != RFKV_OK || total_tokens < 0 || max_seqlen < 0 || max_seqlen > total_tokens) return 0;
+  if (total_tokens * params->n_kv_heads >= (int64_t)1 << 31) return 0;
+  const Geometry g = make_geometry(params, total_tokens, max_seqlen);
+  return carve_workspace(g, nullptr).bytes + 256;
+}
+
+rfkv_status rfkv_score(const rfkv_params* params, const void* q_win, const void* k,
+                       const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores, void* ws,
+                       size_t ws_bytes, void* stream) {
+  rfkv_status st = check_params(params);
+  if (st != RFKV_OK) return st;
+  if ((st = check_strides(params, true, true, false)) != RFKV_OK) return st;
+  int64_t total;
+  int32_t max_len;
+  if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
+  if (total == 0) return RFKV_OK;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(scores) || !aligned16(ws)) return RFKV_INVALID_ARG;
+  const Geometry g = make_geometry(params, total, max_len);
+  const Workspace w = carve_workspace(g, ws);
+  if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
+  return device_status(run_score(params, g, w, q_win, k, cu_seqlens_dev, scores, static_cast<hipStream_t>(stream)));
+}
+
+rfkv_status rfkv_select(const rfkv_params* params, const float* scores, const int32_t* cu_seqlens_host,
+                        const int32_t* cu_seqlens_dev, int32_t* kept, int64_t* out_offsets, int32_t* idx,
+                        void* ws, size_t ws_bytes, void* stream) {
+  rfkv_status st = check_params(params);
+  if (st != RFKV_OK) return st;
+  int64_t total;
+  int32_t max_len;
+  if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
+  if (!kept || !out_offsets) return RFKV_INVALID_ARG;
+  if (params->batch == 0) return RFKV_OK;
+  if (!aligned16(ws)) return RFKV_INVALID_ARG;
+  if (total > 0 && (!aligned16(scores) || !idx)) return RFKV_INVALID_ARG;
+  const Geometry g = make_geometry(params, total, max_len);
+  const Workspace w = carve_workspace(g, ws);
+  if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = run_select(params, g, w, scores, cu_seqlens_dev, kept, s);
+  if (e != hipSuccess) return device_status(e);
+  CompactArgs c = compact_base(params, g, cu_seqlens_dev, kept);
+  c.source = params->rank_mode == RFKV_RANK_SCORE ? kSrcPaddedIdx : kSrcPositionDesc;
+  c.desc = w.desc;
+  c.idx_pad = w.idx_pad;
+  c.offsets_out = out_offsets;
+  c.idx_out = idx;
+  return device_status(launch_compact(g, c, s));
+}
+
+rfkv_status rfkv_compact(const rfkv_params* params, const void* k, const void* v, const int32_t* cu_seqlens_host,
+                         const int32_t* cu_seqlens_dev, const int32_t* kept, const int64_t* out_offsets,
+                         const int32_t* idx, void* k_out, void* v_out, int64_t out_capacity_rows, void* stream) {
+  rfkv_status st = check_params(params);
+  if (st != RFKV_OK) return st;
+  if ((st = check_strides(params, false, true, true)) != RFKV_OK) return st;
+  int64_t total;
+  int32_t max_len;
+  if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
+  if (out_capacity_rows < 0) return RFKV_INVALID_ARG;
+  if (total == 0) return RFKV_OK;
+  if (!kept || !out_offsets || !idx) return RFKV_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)) return RFKV_INVALID_ARG;
+  const Geometry g = make_geometry(params, total, max_len);
+  CompactArgs c = compact_base(params, g, cu_seqlens_dev, kept);
+  c.k = k;
+  c.v = v;
+  c.k_out = k_out;
+  c.v_out = v_out;
+  c.source = kSrcPackedIdx;
+  c.idx_packed = idx;
+  c.offsets_in = out_offsets;
+  c.capacity_rows = out_capacity_rows;
+  return device_status(launch_compact(g, c, static_cast<hipStream_t>(stream)));
+}
+
+rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, const void* k, const void* v,
+                                const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores_opt,
+                                int32_t* kept, int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
+                                int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream) {
+  rfkv_status st = check_params(params);
+  if (st != RFKV_OK) return st;
+  if ((st = check_strides(params, true, true, true)) != RFKV_OK) return st;
+  int64_t total;
+  int32_t max_len;
+  if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
+  if (!kept || !out_offsets || out_capacity_rows < 0) return RFKV_INVALID_ARG;
+  if (params->batch == 0) return RFKV_OK;
+  if (!aligned16(ws)) return RFKV_INVALID_ARG;
+  if (total > 0 && (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)))
+    return RFKV_INVALID_ARG;
+  if (scores_opt && !aligned16(scores_opt)) return RFKV_INVALID_ARG;
+  const Geometry g = make_geometry(params, total, max_len);
+  const Workspace w = carve_workspace(g, ws);
+  if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* scores = scores_opt ? scores_opt : w.scores;
+  hipError_t e = hipSuccess;
+  if (total > 0) e = run_score(params, g, w, q_win, k, cu_seqlens_dev, scores, s);
+  if (e != hipSuccess) return device_status(e);
+  e = run_select(params, g, w, scores, cu_seqlens_dev, kept, s);
+  if (e != hipSuccess) return device_status(e);
+  CompactArgs c = compact_base(params, g, cu_seqlens_dev, kept);
+  c.k = k;
+  c.v = v;
+  c.k_out = total > 0 ? k_out : nullptr;
+  c.v_out = v_out;
+  c.source = params->rank_mode == RFKV_RANK_SCORE ? kSrcPaddedIdx : kSrcPositionDesc;
+  c.desc = w.desc;
+  c.idx_pad = w.idx_pad;
+  c.offsets_out = out_offsets;
+  c.idx_out = idx_opt;
+  c.capacity_rows = out_capacity_rows;
+  return device_status(launch_compact(g, c, s));
+}
+
+}  // extern "C"

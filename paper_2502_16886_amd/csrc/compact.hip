@@ -1,0 +1,116 @@
+// Gather-compaction of the retained K/V rows (Alg. 1, "Compress K / V by R") for gfx950.
+//
+// Grid (row blocks, units).  Workgroup (x, u) moves output rows [x * kRowsPerBlock, ...) of unit
+// u; workgroups past the unit's kept count leave at once.  A row of d elements is moved as
+// 16-byte pieces by row_bytes / 16 neighbouring lanes, so loads and stores of a row are fully
+// coalesced, and every thread keeps several independent 16-byte loads in flight.
+//
+// Where the source position of output row t comes from:
+//   kSrcPositionDesc  position ranking keeps two slabs, [0, sinks) and [n - (kept - sinks), n):
+//                     pos = t < sinks ? t : n - kept + t           (no index list is read)
+//   kSrcPaddedIdx     the per-unit padded list the select kernel wrote
+//   kSrcPackedIdx     a packed list plus offsets supplied by the caller
+// In the first two cases the unit's output offset is the sum of the kept counts of the units
+// before it; workgroup x == 0 of each unit also publishes it (and the grand total).
+#include "kernels.h"
+
+namespace rfkv {
+namespace {
+
+constexpr int kRowsPerBlock = 64;
+constexpr int kUnroll = 4;
+
+__device__ __forceinline__ int64_t block_sum_i64(int64_t v, int64_t* sh /*[4]*/) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+__global__ __launch_bounds__(kBlockThreads) void compact_kernel(CompactArgs a) {
+  __shared__ int64_t sh_sum[4];
+  const int unit = blockIdx.y;
+  const int b = unit / a.n_kv_heads, h = unit - b * a.n_kv_heads;
+  const int s0 = a.cu[b];
+  const int n = a.cu[b + 1] - s0;
+  const int kept = min(max(a.kept[unit], 0), n);         // never trust a count past the sequence
+  const int row0 = blockIdx.x * kRowsPerBlock;
+  if (blockIdx.x > 0 && row0 >= kept) return;            // uniform
+
+  int64_t off;
+  if (a.source == kSrcPackedIdx) {
+    off = a.offsets_in[unit];
+  } else {
+    int64_t part = 0;
+    for (int u = threadIdx.x; u < unit; u += kBlockThreads) {
+      const int bu = u / a.n_kv_heads;
+      part += min(max(a.kept[u], 0), a.cu[bu + 1] - a.cu[bu]);
+    }
+    off = block_sum_i64(part, sh_sum);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.offsets_out) {
+      a.offsets_out[unit] = off;
+      if (unit == a.units - 1) a.offsets_out[a.units] = off + kept;
+    }
+  }
+  if (row0 >= kept) return;
+
+  int sinks = 0;
+  const int32_t* idx = nullptr;
+  if (a.source == kSrcPositionDesc) sinks = a.desc[unit].y;
+  else if (a.source == kSrcPaddedIdx) idx = a.idx_pad + ((int64_t)s0 * a.n_kv_heads + (int64_t)h * n);
+  else idx = a.idx_packed + off;
+
+  const int row1 = min(kept, row0 + kRowsPerBlock);
+  if (a.idx_out) {
+    for (int t = row0 + threadIdx.x; t < row1; t += kBlockThreads)
+      a.idx_out[off + t] = idx ? idx[t] : (t < sinks ? t : n - kept + t);
+  }
+  if (!a.k_out) return;
+
+  const int lanes_per_row = a.row_bytes >> 4;
+  const int rows_per_step = kBlockThreads / lanes_per_row;
+  const int sub = threadIdx.x / lanes_per_row;
+  const int piece = threadIdx.x - sub * lanes_per_row;
+  const unsigned char* kb = static_cast<const unsigned char*>(a.k);
+  const unsigned char* vb = static_cast<const unsigned char*>(a.v);
+  unsigned char* ko = static_cast<unsigned char*>(a.k_out);
+  unsigned char* vo = static_cast<unsigned char*>(a.v_out);
+
+  for (int t0 = row0 + sub; t0 < row1; t0 += rows_per_step * kUnroll) {
+    uint4 kv[kUnroll], vv[kUnroll];
+    int64_t dst[kUnroll];
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      const int t = t0 + j * rows_per_step;
+      dst[j] = -1;
+      if (t < row1) {
+        int pos = idx ? idx[t] : (t < sinks ? t : n - kept + t);
+        pos = min(max(pos, 0), n - 1);                   // a bad caller-supplied index cannot leave the sequence
+        const int64_t tok = (int64_t)s0 + pos;
+        kv[j] = *reinterpret_cast<const uint4*>(kb + a.k_stride_tok * tok + a.k_stride_head * h + piece * 16);
+        vv[j] = *reinterpret_cast<const uint4*>(vb + a.v_stride_tok * tok + a.v_stride_head * h + piece * 16);
+        if (off + t < a.capacity_rows) dst[j] = (off + t) * a.row_bytes + piece * 16;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j) {
+      if (dst[j] >= 0) {
+        *reinterpret_cast<uint4*>(ko + dst[j]) = kv[j];
+        *reinterpret_cast<uint4*>(vo + dst[j]) = vv[j];
+      }
+    }
+  }
+}
+
+}  // namespace
+
+// Strides arrive in bytes here (the C-ABI layer converts from elements).
+hipError_t launch_compact(const Geometry& g, const CompactArgs& a, hipStream_t stream) {
+  if (g.units == 0) return hipSuccess;
+  const int xblocks = max(1, (g.max_seqlen + kRowsPerBlock - 1) / kRowsPerBlock);
+  hipLaunchKernelGGL(compact_kernel, dim3(xblocks, g.units), dim3(kBlockThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace rfkv

@@ -1,0 +1,86 @@
+// Internal launch interface between the C-ABI layer (api.hip) and the gfx950 kernels.
+// Everything here is device-pointer based; validation happens in api.hip.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rfkv {
+
+constexpr int kBlockThreads = 256;     // 4 wavefronts per workgroup in the score / compact kernels
+constexpr int kKeyTilesPerWave = 2;    // 32-key MFMA tiles a wavefront processes per iteration
+constexpr int kKeysPerIter = 4 * kKeyTilesPerWave * 32;   // keys a workgroup consumes per iteration
+constexpr int kSelectThreads = 1024;
+
+// Geometry shared by the host (workspace sizing, grids) and the kernels.
+struct Geometry {
+  int32_t batch, n_q_heads, n_kv_heads, group, head_dim, window;
+  int32_t units;          // batch * n_kv_heads
+  int32_t rows_pad;       // window * group rounded up to a multiple of 32
+  int32_t span;           // keys one score workgroup covers (multiple of kKeysPerIter)
+  int32_t nspans;         // ceil(max_seqlen / span)
+  int32_t max_seqlen;
+  int64_t total_tokens;   // N
+  int32_t elem_bytes;     // 2 (bf16) or 4 (fp32)
+};
+
+struct Workspace {
+  float2*  partials;      // [units][nspans][rows_pad]  (reference exponent, sum) per span
+  float*   bvec;          // [units][rows_pad]          per-row exponent offset for the second pass
+  int4*    desc;          // [units]                    {kept, sinks kept, -, -}
+  int32_t* idx_pad;       // [N * Hkv]                  per-unit padded index lists (score ranking)
+  float*   scores;        // [Hkv][N]                   used when the caller does not want scores
+  size_t   bytes;
+};
+
+Workspace carve_workspace(const Geometry& g, void* base);
+
+struct ScoreArgs {
+  const void* q;
+  const void* k;
+  float* scores;
+  const int32_t* cu;
+  float2* partials;
+  float* bvec;
+  int64_t k_stride_tok, k_stride_head, q_stride_row, q_stride_head;
+  int64_t total_tokens;
+  int32_t n_kv_heads, group, window, rows_pad, span, nspans;
+  float c;                // softmax scale * log2(e)
+};
+
+struct SelectArgs {
+  const float* scores;
+  const int32_t* cu;
+  int32_t* kept;
+  int4* desc;
+  int32_t* idx_pad;
+  int64_t total_tokens;
+  int32_t n_kv_heads, n_sink, min_keep, rank_mode;
+  float threshold;
+};
+
+enum CompactSource { kSrcPositionDesc = 0, kSrcPaddedIdx = 1, kSrcPackedIdx = 2 };
+
+struct CompactArgs {
+  const void* k;
+  const void* v;
+  void* k_out;            // may be null together with v_out: indices / offsets only
+  void* v_out;
+  const int32_t* cu;
+  const int32_t* kept;
+  const int4* desc;             // kSrcPositionDesc
+  const int32_t* idx_pad;       // kSrcPaddedIdx
+  const int32_t* idx_packed;    // kSrcPackedIdx (with offsets_in)
+  const int64_t* offsets_in;    // kSrcPackedIdx
+  int64_t* offsets_out;         // other sources: exclusive scan of kept, written here (may be null)
+  int32_t* idx_out;             // other sources: packed indices written here (may be null)
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
+  int64_t capacity_rows;
+  int32_t n_kv_heads, units, row_bytes, source;
+};
+
+hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream);
+hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t stream);
+hipError_t launch_compact(const Geometry& g, const CompactArgs& a, hipStream_t stream);
+
+}  // namespace rfkv

@@ -1,0 +1,392 @@
+// Scoring kernels for gfx950 (Sec. 3.2 "Reducing Overhead", Eq. 2 of the paper).
+//
+// A'[i] = (1/G) sum_g (1/cnt_i) sum_t softmax_row(t, g)[i] needs every row's softmax
+// normaliser before any column can be finished, so the keys are streamed twice:
+//
+//   score_stats_kernel   logits = K . Q^T on the matrix cores (keys along M, window rows
+//                        along N, so one lane owns one row and 16 keys per tile) and a
+//                        running (reference exponent, sum of 2^x) per row; one partial per
+//                        workgroup span.
+//   score_merge_kernel   folds the per-span partials into one offset per row,
+//                        b_r = ref_r + log2(sum_r * G).
+//   score_reduce_kernel  logits again with the operands swapped (rows along M, keys along
+//                        N, so one lane owns one key and the row reduction is in-lane),
+//                        p = 2^(logit * c - b_r), column sum, divide by the causal count.
+//
+// Operand layout.  A 32x32 MFMA wants, per lane, 16 bytes of the contraction axis of row
+// (lane % 32); which elements those are is free as long as both operands agree.  Each lane
+// therefore owns one contiguous half of its row (lane / 32 picks the half) and feeds
+// 16-byte chunk c of it at step c: global loads of K are eight consecutive 16-byte loads
+// per lane, and Q is staged in LDS with a 16-byte row pad so the same chunk reads are
+// bank-conflict free.  fp32 inputs use the 32x32x2 fp32 MFMA with the same scheme.
+#include "kernels.h"
+
+namespace rfkv {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct Bf16 { static constexpr int kBytes = 2; };
+struct Fp32 { static constexpr int kBytes = 4; };
+
+template <typename T, int D>
+struct Shape {
+  static constexpr int kRowBytes = D * T::kBytes;
+  static constexpr int kHalfBytes = kRowBytes / 2;      // owned by one lane
+  static constexpr int kChunks = kHalfBytes / 16;
+  static constexpr int kLdsRowBytes = kRowBytes + 16;   // pad: consecutive rows shift by 4 banks
+};
+
+constexpr int KT = kKeyTilesPerWave;
+
+template <typename T>
+__device__ __forceinline__ f32x16 mma_chunk(const uint4& a, const uint4& b, f32x16 acc);
+
+template <>
+__device__ __forceinline__ f32x16 mma_chunk<Bf16>(const uint4& a, const uint4& b, f32x16 acc) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                 __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+
+template <>
+__device__ __forceinline__ f32x16 mma_chunk<Fp32>(const uint4& a, const uint4& b, f32x16 acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+  return acc;
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+struct Unit {
+  int b, h;
+  int s0, n;        // first packed token and length of the sequence
+  int wp;           // window rows in use, min(window, n)
+  int q0;           // first packed window row of the sequence
+  int rows;         // wp * group
+  int row_tiles;    // ceil(rows / 32)
+};
+
+__device__ __forceinline__ Unit load_unit(const ScoreArgs& a, int unit) {
+  Unit u;
+  u.b = unit / a.n_kv_heads;
+  u.h = unit - u.b * a.n_kv_heads;
+  int q0 = 0;
+  for (int bb = 0; bb < u.b; ++bb) q0 += min(a.window, a.cu[bb + 1] - a.cu[bb]);
+  u.q0 = q0;
+  u.s0 = a.cu[u.b];
+  u.n = a.cu[u.b + 1] - u.s0;
+  u.wp = min(a.window, u.n);
+  u.rows = u.wp * a.group;
+  u.row_tiles = (u.rows + 31) >> 5;
+  return u;
+}
+
+// Window queries of the unit -> LDS, row r = t * G + g, rows beyond `rows` zero.
+template <typename T, int D>
+__device__ __forceinline__ void stage_q(const ScoreArgs& a, const Unit& u, unsigned char* smem) {
+  using S = Shape<T, D>;
+  constexpr int kChunksPerRow = S::kRowBytes / 16;
+  const int total = u.row_tiles * 32 * kChunksPerRow;
+  const unsigned char* qbase = static_cast<const unsigned char*>(a.q);
+  for (int i = threadIdx.x; i < total; i += kBlockThreads) {
+    const int r = i / kChunksPerRow;
+    const int c = i - r * kChunksPerRow;
+    uint4 val = make_uint4(0, 0, 0, 0);
+    if (r < u.rows) {
+      const int t = r / a.group;
+      const int g = r - t * a.group;
+      const int64_t off = (int64_t)(u.q0 + t) * a.q_stride_row + (int64_t)(u.h * a.group + g) * a.q_stride_head;
+      val = *reinterpret_cast<const uint4*>(qbase + off * T::kBytes + c * 16);
+    }
+    *reinterpret_cast<uint4*>(smem + r * S::kLdsRowBytes + c * 16) = val;
+  }
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void load_k_half(uint4* f, const unsigned char* kunit,
+                                            int64_t tok_bytes, int key, int hi) {
+  const uint4* p = reinterpret_cast<const uint4*>(kunit + (int64_t)key * tok_bytes + hi * Shape<T, D>::kHalfBytes);
+#pragma unroll
+  for (int c = 0; c < Shape<T, D>::kChunks; ++c) f[c] = p[c];
+}
+
+// ---------------------------------------------------------------------------------------------
+// pass 1: per-row (reference exponent, sum) over this workgroup's span of keys
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D, int RT_T>
+__global__ __launch_bounds__(kBlockThreads) void score_stats_kernel(ScoreArgs a) {
+  using S = Shape<T, D>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const Unit u = load_unit(a, blockIdx.y);
+  const int span_begin = blockIdx.x * a.span;
+  if (span_begin >= u.n) return;                       // uniform for the whole workgroup
+  const int span_end = min(u.n, span_begin + a.span);
+
+  stage_q<T, D>(a, u, smem);
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, hi = lane >> 5;
+  const float c = a.c;
+  const float kNegInf = -__builtin_inff();
+
+  float mc[RT_T], l[RT_T];
+  int rowlast[RT_T];                                   // last key this lane's row may see
+#pragma unroll
+  for (int rt = 0; rt < RT_T; ++rt) {
+    mc[rt] = -1e30f;
+    l[rt] = 0.f;
+    const int r = rt * 32 + col;
+    rowlast[rt] = r < u.rows ? u.n - u.wp + r / a.group : -1;
+  }
+  const int first_masked_key = u.n - u.wp + 1;         // keys below are visible to every row
+  const unsigned char* kunit = static_cast<const unsigned char*>(a.k) +
+                               ((int64_t)u.s0 * a.k_stride_tok + (int64_t)u.h * a.k_stride_head) * T::kBytes;
+  const int64_t tok_bytes = a.k_stride_tok * T::kBytes;
+
+  for (int tile0 = span_begin + wave * (KT * 32); tile0 < span_end; tile0 += 4 * KT * 32) {
+    uint4 kf[KT][S::kChunks];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+      load_k_half<T, D>(kf[kt], kunit, tok_bytes, min(tile0 + kt * 32 + col, u.n - 1), hi);
+    const bool masked = tile0 + KT * 32 > first_masked_key;
+
+#pragma unroll
+    for (int rt = 0; rt < RT_T; ++rt) {
+      if (rt < u.row_tiles) {
+        f32x16 acc[KT];
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[kt][i] = 0.f;
+        const unsigned char* qrow = smem + (rt * 32 + col) * S::kLdsRowBytes + hi * S::kHalfBytes;
+#pragma unroll
+        for (int ch = 0; ch < S::kChunks; ++ch) {
+          const uint4 qf = *reinterpret_cast<const uint4*>(qrow + ch * 16);
+#pragma unroll
+          for (int kt = 0; kt < KT; ++kt) acc[kt] = mma_chunk<T>(kf[kt][ch], qf, acc[kt]);   // keys x rows
+        }
+        if (masked) {
+#pragma unroll
+          for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = tile0 + kt * 32 + (i >> 2) * 8 + hi * 4 + (i & 3);
+              if (key > rowlast[rt]) acc[kt][i] = kNegInf;
+            }
+        }
+        float tmax = kNegInf;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[kt][i]);
+        const float mnew = fmaxf(mc[rt], tmax * c);
+        float sum = 0.f;
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sum += fast_exp2(__builtin_fmaf(acc[kt][i], c, -mnew));
+        l[rt] = l[rt] * fast_exp2(mc[rt] - mnew) + sum;
+        mc[rt] = mnew;
+      }
+    }
+  }
+
+  // the two half-waves hold disjoint keys of the same rows
+#pragma unroll
+  for (int rt = 0; rt < RT_T; ++rt) {
+    const float om = __shfl_xor(mc[rt], 32), ol = __shfl_xor(l[rt], 32);
+    const float nm = fmaxf(mc[rt], om);
+    l[rt] = l[rt] * fast_exp2(mc[rt] - nm) + ol * fast_exp2(om - nm);
+    mc[rt] = nm;
+  }
+  __syncthreads();                                     // everyone is done reading Q from LDS
+  const int rows32 = u.row_tiles * 32;
+  float2* red = reinterpret_cast<float2*>(smem);       // [4 waves][rows32]
+  if (hi == 0) {
+#pragma unroll
+    for (int rt = 0; rt < RT_T; ++rt)
+      if (rt < u.row_tiles) red[wave * rows32 + rt * 32 + col] = make_float2(mc[rt], l[rt]);
+  }
+  __syncthreads();
+  for (int r = threadIdx.x; r < rows32; r += kBlockThreads) {
+    float m = red[r].x, s = red[r].y;
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const float2 o = red[w * rows32 + r];
+      const float nm = fmaxf(m, o.x);
+      s = s * fast_exp2(m - nm) + o.y * fast_exp2(o.x - nm);
+      m = nm;
+    }
+    a.partials[((int64_t)blockIdx.y * a.nspans + blockIdx.x) * a.rows_pad + r] = make_float2(m, s);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// merge: b_r = ref_r + log2(sum_r * G); rows that do not exist get +inf (weight zero)
+// ---------------------------------------------------------------------------------------------
+__global__ void score_merge_kernel(ScoreArgs a) {
+  const Unit u = load_unit(a, blockIdx.x);
+  const int r = threadIdx.x;
+  if (r >= a.rows_pad) return;
+  float out = __builtin_inff();
+  if (r < u.rows) {
+    const int nsp = (u.n + a.span - 1) / a.span;
+    const float2* p = a.partials + (int64_t)blockIdx.x * a.nspans * a.rows_pad + r;
+    float m = -1e30f;
+    for (int s = 0; s < nsp; ++s) m = fmaxf(m, p[(int64_t)s * a.rows_pad].x);
+    float sum = 0.f;
+    for (int s = 0; s < nsp; ++s) {
+      const float2 v = p[(int64_t)s * a.rows_pad];
+      sum += v.y * fast_exp2(v.x - m);
+    }
+    out = m + __log2f(sum * (float)a.group);
+  }
+  a.bvec[(int64_t)blockIdx.x * a.rows_pad + r] = out;
+}
+
+// ---------------------------------------------------------------------------------------------
+// pass 2: column sums of the normalised probabilities
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(kBlockThreads) void score_reduce_kernel(ScoreArgs a) {
+  using S = Shape<T, D>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const Unit u = load_unit(a, blockIdx.y);
+  const int span_begin = blockIdx.x * a.span;
+  if (span_begin >= u.n) return;
+  const int span_end = min(u.n, span_begin + a.span);
+  const int rows32 = u.row_tiles * 32;
+
+  stage_q<T, D>(a, u, smem);
+  float* bsm = reinterpret_cast<float*>(smem + rows32 * S::kLdsRowBytes);   // [rows32] exponent offsets
+  int* rlast = reinterpret_cast<int*>(bsm + rows32);                        // [rows32] last visible key
+  for (int r = threadIdx.x; r < rows32; r += kBlockThreads) {
+    bsm[r] = a.bvec[(int64_t)blockIdx.y * a.rows_pad + r];
+    rlast[r] = r < u.rows ? u.n - u.wp + r / a.group : -1;
+  }
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, hi = lane >> 5;
+  const float c = a.c;
+  const int first_masked_key = u.n - u.wp + 1;
+  const unsigned char* kunit = static_cast<const unsigned char*>(a.k) +
+                               ((int64_t)u.s0 * a.k_stride_tok + (int64_t)u.h * a.k_stride_head) * T::kBytes;
+  const int64_t tok_bytes = a.k_stride_tok * T::kBytes;
+  float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
+
+  for (int tile0 = span_begin + wave * (KT * 32); tile0 < span_end; tile0 += 4 * KT * 32) {
+    uint4 kf[KT][S::kChunks];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt)
+      load_k_half<T, D>(kf[kt], kunit, tok_bytes, min(tile0 + kt * 32 + col, u.n - 1), hi);
+    const bool masked = tile0 + KT * 32 > first_masked_key;
+
+    float colsum[KT];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) colsum[kt] = 0.f;
+
+    for (int rt = 0; rt < u.row_tiles; ++rt) {
+      f32x16 acc[KT];
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[kt][i] = 0.f;
+      const unsigned char* qrow = smem + (rt * 32 + col) * S::kLdsRowBytes + hi * S::kHalfBytes;
+#pragma unroll
+      for (int ch = 0; ch < S::kChunks; ++ch) {
+        const uint4 qf = *reinterpret_cast<const uint4*>(qrow + ch * 16);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) acc[kt] = mma_chunk<T>(qf, kf[kt][ch], acc[kt]);     // rows x keys
+      }
+      // accumulator i of this lane is row rt*32 + (i/4)*8 + hi*4 + i%4, key tile0 + kt*32 + col
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int rbase = rt * 32 + j * 8 + hi * 4;
+        const float4 bv = *reinterpret_cast<const float4*>(bsm + rbase);
+        const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+        if (!masked) {
+#pragma unroll
+          for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) colsum[kt] += fast_exp2(__builtin_fmaf(acc[kt][j * 4 + e], c, -bb[e]));
+        } else {
+          const int4 rv = *reinterpret_cast<const int4*>(rlast + rbase);
+          const int rl[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+          for (int kt = 0; kt < KT; ++kt) {
+            const int key = tile0 + kt * 32 + col;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const float p = fast_exp2(__builtin_fmaf(acc[kt][j * 4 + e], c, -bb[e]));
+              colsum[kt] += key <= rl[e] ? p : 0.f;
+            }
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      const float tot = colsum[kt] + __shfl_xor(colsum[kt], 32);
+      const int key = tile0 + kt * 32 + col;
+      if (hi == 0 && key < u.n) out[key] = tot / (float)min(u.wp, u.n - key);
+    }
+  }
+}
+
+template <typename K>
+hipError_t allow_lds(K kernel, size_t bytes) {
+  if (bytes <= 48 * 1024) return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)bytes);
+}
+
+template <typename T, int D, int RT_T>
+hipError_t launch_stats(const Geometry& g, const ScoreArgs& a, dim3 grid, hipStream_t stream) {
+  const size_t lds = (size_t)g.rows_pad * Shape<T, D>::kLdsRowBytes;
+  hipError_t e = allow_lds(score_stats_kernel<T, D, RT_T>, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((score_stats_kernel<T, D, RT_T>), grid, dim3(kBlockThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t launch_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream) {
+  const dim3 grid(g.nspans, g.units);
+  const int rt = g.rows_pad / 32;
+  hipError_t e;
+  if (rt <= 1) e = launch_stats<T, D, 1>(g, a, grid, stream);
+  else if (rt <= 2) e = launch_stats<T, D, 2>(g, a, grid, stream);
+  else if (rt <= 4) e = launch_stats<T, D, 4>(g, a, grid, stream);
+  else if (rt <= 8) e = launch_stats<T, D, 8>(g, a, grid, stream);
+  else e = launch_stats<T, D, 16>(g, a, grid, stream);
+  if (e != hipSuccess) return e;
+
+  hipLaunchKernelGGL(score_merge_kernel, dim3(g.units), dim3(g.rows_pad), 0, stream, a);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+
+  const size_t lds = (size_t)g.rows_pad * (Shape<T, D>::kLdsRowBytes + 8);
+  e = allow_lds(score_reduce_kernel<T, D>, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((score_reduce_kernel<T, D>), grid, dim3(kBlockThreads), lds, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream) {
+  if (g.units == 0 || g.nspans == 0) return hipSuccess;
+  if (bf16) {
+    if (g.head_dim == 64) return launch_typed<Bf16, 64>(g, a, stream);
+    return launch_typed<Bf16, 128>(g, a, stream);
+  }
+  if (g.head_dim == 64) return launch_typed<Fp32, 64>(g, a, stream);
+  return launch_typed<Fp32, 128>(g, a, stream);
+}
+
+}  // namespace rfkv

@@ -1,0 +1,132 @@
+"""Host-side behaviour of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, sizes its workspace, and rejects bad arguments before touching the device.
+Device pointers here are fake aligned addresses: every call below must fail validation (or be
+a no-op) on the host, so nothing is ever dereferenced or launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_16886_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # aligned, never dereferenced
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return B.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "rfkv.h")).read()
+    declared = set(re.findall(r"RFKV_API\s+[\w\s\*]+?\b(rfkv_\w+)\s*\(", header))
+    assert declared == set(B.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert B.rfkv_version() >= 100
+    assert B.status_string(B.RFKV_OK) == "ok"
+    assert "workspace" in B.status_string(B.RFKV_WORKSPACE_TOO_SMALL)
+    assert B.rfkv_last_device_error() == 0
+
+
+def test_params_struct_matches_header_layout():
+    # 11 four-byte fields, 4 bytes of padding, 6 eight-byte strides
+    assert ctypes.sizeof(B.RfkvParams) == 96
+    assert B.RfkvParams.k_stride_tok.offset == 48
+
+
+def good(**kw):
+    p = B.make_params(1, 32, 8, 128, 32, "bf16")
+    for k, v in kw.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_workspace_bytes(lib):
+    p = good()
+    small, big = B.rfkv_workspace_bytes(p, 8192, 8192), B.rfkv_workspace_bytes(p, 32768, 32768)
+    assert 0 < small < big
+    assert big >= 2 * 32768 * 8 * 4                         # padded index lists + scores at least
+    assert B.rfkv_workspace_bytes(good(head_dim=96), 8192, 8192) == 0
+    assert B.rfkv_workspace_bytes(p, 100, 200) == 0          # longest sequence exceeds the total
+    assert lib.rfkv_workspace_bytes(None, 10, 10) == 0
+
+
+CU = np.array([0, 4096], dtype=np.int32)
+
+
+def score(p, q=FAKE, k=FAKE, cu_h=CU, cu_d=FAKE, s=FAKE, ws=FAKE, wsb=1 << 40):
+    return B.rfkv_score(p, q, k, cu_h, cu_d, s, ws, wsb, stream=0, check=False)
+
+
+def layer(p, q=FAKE, k=FAKE, v=FAKE, cu_h=CU, cu_d=FAKE, kept=FAKE, offs=FAKE, ko=FAKE, vo=FAKE, cap=1 << 20,
+          ws=FAKE, wsb=1 << 40):
+    return B.rfkv_compress_layer(p, q, k, v, cu_h, cu_d, None, kept, offs, None, ko, vo, cap, ws, wsb, stream=0,
+                                 check=False)
+
+
+def test_invalid_arguments_are_rejected_on_the_host(lib):
+    assert lib.rfkv_score(None, FAKE, FAKE, CU.ctypes.data, FAKE, FAKE, FAKE, 1 << 40, None) == B.RFKV_INVALID_ARG
+    assert score(good(), q=None) == B.RFKV_INVALID_ARG
+    assert score(good(), k=None) == B.RFKV_INVALID_ARG
+    assert score(good(), s=None) == B.RFKV_INVALID_ARG
+    assert score(good(), ws=None) == B.RFKV_INVALID_ARG
+    assert score(good(), cu_h=None) == B.RFKV_INVALID_ARG
+    assert score(good(), cu_d=None) == B.RFKV_INVALID_ARG
+    assert score(good(), k=FAKE + 8) == B.RFKV_INVALID_ARG                  # misaligned
+    assert score(good(n_q_heads=30)) == B.RFKV_INVALID_ARG                  # not a multiple of Hkv
+    assert score(good(window=0)) == B.RFKV_INVALID_ARG
+    assert score(good(n_sink=-1)) == B.RFKV_INVALID_ARG
+    assert score(good(rank_mode=7)) == B.RFKV_INVALID_ARG
+    assert score(good(softmax_scale=-1.0)) == B.RFKV_INVALID_ARG
+    assert score(good(threshold=float("nan"))) == B.RFKV_INVALID_ARG
+    assert score(good(k_stride_tok=100)) == B.RFKV_INVALID_ARG              # rows would overlap / misalign
+    assert score(good(q_stride_head=132)) == B.RFKV_INVALID_ARG             # 264 bytes: not 16-byte aligned
+    assert score(good(), cu_h=np.array([1, 4096], dtype=np.int32)) == B.RFKV_INVALID_ARG
+    assert score(good(batch=2), cu_h=np.array([0, 500, 300], dtype=np.int32)) == B.RFKV_INVALID_ARG
+    assert layer(good(), kept=None) == B.RFKV_INVALID_ARG
+    assert layer(good(), offs=None) == B.RFKV_INVALID_ARG
+    assert layer(good(), v=None) == B.RFKV_INVALID_ARG
+    assert layer(good(), ko=None) == B.RFKV_INVALID_ARG
+    assert layer(good(), cap=-1) == B.RFKV_INVALID_ARG
+    assert layer(good(v_stride_head=64)) == B.RFKV_INVALID_ARG
+    st = B.rfkv_compact(good(), FAKE, FAKE, CU, FAKE, FAKE, FAKE, None, FAKE, FAKE, 10, stream=0, check=False)
+    assert st == B.RFKV_INVALID_ARG
+    st = B.rfkv_select(good(), FAKE, CU, FAKE, None, FAKE, FAKE, FAKE, 1 << 40, stream=0, check=False)
+    assert st == B.RFKV_INVALID_ARG
+
+
+def test_unsupported_problems(lib):
+    assert score(good(dtype=3)) == B.RFKV_UNSUPPORTED
+    assert score(good(head_dim=96)) == B.RFKV_UNSUPPORTED
+    assert score(good(window=256)) == B.RFKV_UNSUPPORTED                     # 256 * 4 rows > 512
+    assert score(good(dtype=B.DTYPE_FP32, window=128)) == B.RFKV_UNSUPPORTED  # fp32 queries do not fit in LDS
+    assert score(good(batch=10000), cu_h=np.zeros(10001, dtype=np.int32)) == B.RFKV_UNSUPPORTED
+
+
+def test_workspace_too_small(lib):
+    p = good()
+    need = B.rfkv_workspace_bytes(p, 4096, 4096)
+    assert score(p, wsb=need // 2) == B.RFKV_WORKSPACE_TOO_SMALL
+    assert layer(p, wsb=16) == B.RFKV_WORKSPACE_TOO_SMALL
+    st = B.rfkv_select(p, FAKE, CU, FAKE, FAKE, FAKE, FAKE, FAKE, 0, stream=0, check=False)
+    assert st == B.RFKV_WORKSPACE_TOO_SMALL
+
+
+def test_empty_batches_are_no_ops(lib):
+    empty = np.array([0], dtype=np.int32)
+    assert score(good(batch=0), cu_h=empty) == B.RFKV_OK
+    assert layer(good(batch=0), cu_h=empty) == B.RFKV_OK
+    assert score(good(batch=1), cu_h=np.array([0, 0], dtype=np.int32)) == B.RFKV_OK     # one empty sequence
+
+
+def test_binding_raises_on_error(lib):
+    with pytest.raises(B.RfkvError) as e:
+        B.rfkv_score(good(window=0), FAKE, FAKE, CU, FAKE, FAKE, FAKE, 1 << 40, stream=0)
+    assert e.value.status == B.RFKV_INVALID_ARG

@@ -1,0 +1,199 @@
+"""GPU parity: librfkv (through its C ABI) against the float64 oracle, element by element, on
+the same seeded inputs.  Sizes: small shapes that still span several MFMA tiles, workgroup spans
+and a ragged tail; the five workload configurations plus the headline shape at full size (one or
+a few layers each, in the launch geometry the benchmark uses); and the degenerate cases."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import rfkv_harness as H                                   # noqa: E402
+from oracle import refreekv_oracle as O                    # noqa: E402
+from paper_2502_16886_amd import binding as B              # noqa: E402
+from paper_2502_16886_amd import workloads as W            # noqa: E402
+
+pytestmark = pytest.mark.gpu
+MODES = [B.RANK_POSITION, B.RANK_SCORE]
+FULL = os.environ.get("RFKV_FULL_LAYERS", "0") == "1"
+
+
+def run_and_compare(layer, mode, **kw):
+    dl = H.DeviceLayer(layer, rank_mode=mode, **kw)
+    dl.compress()
+    gpu = dl.results()
+    rep = H.compare_layer(layer, gpu, mode, **kw)
+    print(f"\n  cfg={layer.meta.get('cfg_id')} layer={layer.meta.get('layer')} mode={mode} {rep}", flush=True)
+    return dl, gpu, rep
+
+
+def small_cfg(dtype, Hq, Hkv, d, w, **kw):
+    return W.Config("small", 1, Hq, Hkv, d, w, dtype, **kw)
+
+
+# ------------------------------------------------------------------ config 0 and small shapes
+@pytest.mark.parametrize("mode", MODES)
+def test_config0_tiny_fp32(mode):
+    _, gpu, rep = run_and_compare(W.make_layer(0, 0), mode)
+    assert rep["max_rel_score_err"] < 1e-4
+
+
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,w,lens", [
+    ("bf16", 8, 2, 128, 32, [777]),                 # several tiles + ragged tail
+    ("bf16", 28, 4, 128, 32, [1500, 333]),          # G = 7: 224 rows -> 7 row tiles
+    ("bf16", 8, 8, 64, 16, [300, 1, 45, 1029]),     # G = 1, d = 64, a length-1 sequence
+    ("fp32", 8, 2, 128, 8, [513, 64]),              # fp32 d = 128
+    ("fp32", 4, 4, 64, 1, [260]),                   # the paper's k = 1
+    ("bf16", 32, 8, 128, 64, [40, 2100]),           # n < window for the first sequence; 256 rows
+    ("bf16", 4, 1, 128, 5, [3, 2, 4, 70]),          # n <= m (sinks) and odd window
+])
+def test_small_shapes(mode, dtype, Hq, Hkv, d, w, lens):
+    cfg = small_cfg(dtype, Hq, Hkv, d, w, batch=len(lens))
+    layer = W.make_layer(0, 17, cfg=cfg, lengths=lens)
+    run_and_compare(layer, mode)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_thresholds_and_min_keep(mode):
+    cfg = small_cfg("bf16", 8, 2, 128, 16, batch=2)
+    layer = W.make_layer(0, 3, cfg=cfg, lengths=[600, 90])
+    n_units = np.repeat([600, 90], 2)
+    for T in (0.0, 1e-4, 0.05, 0.5, 1.0, 2.0):
+        _, gpu, _ = run_and_compare(layer, mode, threshold=T)
+        if T == 0.0:      # full budget reproduces the cache bit for bit
+            assert np.array_equal(gpu["kept"], n_units)
+            o = 0
+            for u, b, h, s, e in H.unit_slices(layer):
+                assert np.array_equal(gpu["k_out"][o:o + e - s], layer.k[s:e, h])
+                assert np.array_equal(gpu["v_out"][o:o + e - s], layer.v[s:e, h])
+                o += e - s
+        if T >= 1.0:
+            assert np.all(gpu["kept"] == 1)
+    _, gpu, _ = run_and_compare(layer, mode, threshold=0.5, min_keep=100)
+    assert np.array_equal(gpu["kept"], np.minimum(np.maximum(gpu["kept"], 100), n_units))
+    assert np.all(gpu["kept"][:2] >= 100) and np.all(gpu["kept"][2:] == 90)
+
+
+def test_large_logits_do_not_overflow():
+    # logits of magnitude ~80: the running reference exponent must keep exp2 in range
+    cfg = small_cfg("fp32", 4, 2, 64, 4, q_shared=0.0, x_sink=(0.0, 0.0), spike_frac=0.0)
+    layer = W.make_layer(0, 5, cfg=cfg, lengths=[400])
+    layer.q_win *= np.float32(9.0)
+    layer.k *= np.float32(9.0)
+    dl = H.DeviceLayer(layer)
+    dl.compress()
+    gpu = dl.results()
+    assert np.all(np.isfinite(gpu["scores"]))
+    ref = O.oracle_score(layer.f64("q_win"), layer.f64("k"), layer.cu_seqlens, 4, 2, 4)
+    assert np.abs(layer.f64("q_win")[0, 0] @ layer.f64("k")[:, 0].T / 8).max() > 60
+    rel, nbad = H.score_errors(gpu["scores"], ref)
+    assert nbad == 0
+
+
+def test_all_equal_scores_tie_break_lowest_index():
+    # feed rfkv_select directly: equal scores -> score ranking keeps positions 0..kept-1
+    import torch
+    n, Hkv = 5000, 2
+    p = B.make_params(1, 2, Hkv, 128, 1, "bf16", threshold=0.1, rank_mode=B.RANK_SCORE)
+    cu = np.array([0, n], dtype=np.int32)
+    cu_d = torch.from_numpy(cu).cuda()
+    scores = torch.full((Hkv, n), 0.25, dtype=torch.float32, device="cuda")
+    buf = B.alloc_layer_buffers(p, n, n)
+    B.rfkv_select(p, scores, cu, cu_d, buf.kept, buf.out_offsets, buf.idx, buf.ws, buf.ws_bytes)
+    torch.cuda.synchronize()
+    kept = buf.kept.cpu().numpy()
+    expect = O.select_unit(np.full(n, 0.25), O.RANK_SCORE, 4, H.threshold_as_float32(0.1))[0]
+    assert np.all(kept == expect) and expect == int(np.floor(0.81 * n)) + 1
+    offs = buf.out_offsets.cpu().numpy()
+    assert list(offs) == [0, expect, 2 * expect]
+    idx = buf.idx[:2 * expect].cpu().numpy()
+    assert np.array_equal(idx[:expect], np.arange(expect)) and np.array_equal(idx[expect:], np.arange(expect))
+    # all-zero scores: F = 0 keeps everything
+    scores.zero_()
+    B.rfkv_select(p, scores, cu, cu_d, buf.kept, buf.out_offsets, buf.idx, buf.ws, buf.ws_bytes)
+    torch.cuda.synchronize()
+    assert np.all(buf.kept.cpu().numpy() == n)
+
+
+@pytest.mark.parametrize("mode", MODES)
+def test_staged_calls_equal_fused_call(mode):
+    # rfkv_score -> rfkv_select -> rfkv_compact give what rfkv_compress_layer gives; strided
+    # (head-major) K/V layouts give the same result as token-major ones
+    import torch
+    cfg = small_cfg("bf16", 8, 2, 128, 32, batch=2)
+    layer = W.make_layer(0, 9, cfg=cfg, lengths=[1200, 257])
+    dl = H.DeviceLayer(layer, rank_mode=mode)
+    dl.compress()
+    fused = dl.results()
+    b2 = B.alloc_layer_buffers(dl.params, dl.N, dl.max_len)
+    B.rfkv_score(dl.params, dl.q, dl.k, dl.cu_host, dl.cu_dev, b2.scores, b2.ws, b2.ws_bytes)
+    B.rfkv_select(dl.params, b2.scores, dl.cu_host, dl.cu_dev, b2.kept, b2.out_offsets, b2.idx, b2.ws, b2.ws_bytes)
+    B.rfkv_compact(dl.params, dl.k, dl.v, dl.cu_host, dl.cu_dev, b2.kept, b2.out_offsets, b2.idx, b2.k_out,
+                   b2.v_out, b2.capacity_rows)
+    torch.cuda.synchronize()
+    total = int(b2.out_offsets[-1])
+    assert np.array_equal(b2.scores.cpu().numpy(), fused["scores"])
+    assert np.array_equal(b2.kept.cpu().numpy(), fused["kept"])
+    assert np.array_equal(b2.idx[:total].cpu().numpy(), fused["idx"])
+    assert np.array_equal(H.to_host_bits(b2.k_out[:total], "bf16"), fused["k_out"])
+    assert np.array_equal(H.to_host_bits(b2.v_out[:total], "bf16"), fused["v_out"])
+    # head-major storage [Hkv, N, d] described through the strides
+    dl3 = H.DeviceLayer(layer, rank_mode=mode)
+    dl3.k = dl3.k.permute(1, 0, 2).contiguous()
+    dl3.v = dl3.v.permute(1, 0, 2).contiguous()
+    dl3.params.k_stride_tok = dl3.params.v_stride_tok = 128
+    dl3.params.k_stride_head = dl3.params.v_stride_head = dl3.N * 128
+    dl3.compress()
+    again = dl3.results()
+    for key in ("scores", "kept", "idx", "k_out", "v_out"):
+        assert np.array_equal(again[key], fused[key]), key
+
+
+def test_repeat_runs_are_bit_identical_and_capacity_is_respected():
+    import torch
+    cfg = small_cfg("bf16", 32, 8, 128, 32)
+    layer = W.make_layer(1, 2, cfg=cfg, lengths=[3000])
+    for mode in MODES:
+        dl = H.DeviceLayer(layer, rank_mode=mode)
+        dl.compress()
+        a = dl.results()
+        dl.compress()
+        b = dl.results()
+        for key in a:
+            assert np.array_equal(a[key], b[key]), key
+        # a too-small output is never overrun: rows past the capacity are simply not written
+        total = int(a["out_offsets"][-1])
+        cap = total // 2
+        dl.buf.k_out.fill_(7.0)
+        dl.buf.v_out.fill_(7.0)
+        B.rfkv_compress_layer(dl.params, dl.q, dl.k, dl.v, dl.cu_host, dl.cu_dev, None, dl.buf.kept,
+                              dl.buf.out_offsets, None, dl.buf.k_out, dl.buf.v_out, cap, dl.buf.ws, dl.buf.ws_bytes)
+        torch.cuda.synchronize()
+        assert int(dl.buf.out_offsets[-1]) == total                    # the caller can see the overflow
+        assert np.array_equal(H.to_host_bits(dl.buf.k_out[:cap], "bf16"), a["k_out"][:cap])
+        assert torch.all(dl.buf.k_out[cap:total].float() == 7.0) and torch.all(dl.buf.v_out[cap:total].float() == 7.0)
+
+
+# ------------------------------------------------------------------ the workload configurations at full size
+FULL_CASES = [(1, [0, 13, 31]), (2, [5]), (3, [2]), ("H", [0]), (4, [1])]
+
+
+@pytest.mark.parametrize("cfg_id,layers", FULL_CASES)
+def test_full_size_configs(cfg_id, layers):
+    cfg = W.CONFIGS[cfg_id]
+    if FULL:
+        layers = list(range(cfg.layers))
+    for li in layers:
+        layer = W.make_layer(cfg_id, li)
+        ref_scores = O.oracle_score(layer.f64("q_win"), layer.f64("k"), layer.cu_seqlens, cfg.n_q_heads,
+                                    cfg.n_kv_heads, cfg.window)
+        for mode in MODES:
+            ref = H.oracle_layer(layer, mode, scores=ref_scores)
+            dl = H.DeviceLayer(layer, rank_mode=mode)
+            dl.compress()
+            gpu = dl.results()
+            rep = H.compare_layer(layer, gpu, mode, ref=ref)
+            print(f"\n  cfg={cfg_id} layer={li} mode={mode} {rep}", flush=True)
+            del dl, gpu
