@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the ReFreeKV compression pass on one MI355X.
+
+A step is one rfkv_compress_layer call (score -> rank -> budget rule -> gather-compact) over one
+transformer layer of the headline workload: Llama3-8B attention shape (32 query / 8 KV heads,
+d = 128, bf16), one 32768-token sequence, observation window 32, T = 1 %, m = 4, position ranking
+(the paper's method).  Steps rotate over several layers' distinct buffers so that no step finds
+its inputs in the 256 MB Infinity Cache left there by the previous one.  Inputs are synthetic
+(paper_2502_16886_amd.workloads) and resident in HBM before timing starts.
+
+Prints one JSON line (see the design doc for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(N, Hkv, d, e, Hq, wrows, kept_rows, units, score_mode):
+    """Bytes the method itself must move for one layer-pass (K counted once)."""
+    k_read = N * Hkv * d * e
+    q_read = wrows * Hq * d * e
+    scores = 2 * N * Hkv * 4
+    gather = 4 * kept_rows * d * e
+    idx = kept_rows * 8 if score_mode else 0
+    return k_read + q_read + scores + gather + idx + 12 * units
+
+
+def kernel_bytes(name, N, Hkv, d, e, Hq, wrows, kept_rows):
+    """Algorithmic bytes of one kernel launch."""
+    if name == "score_stats":
+        return N * Hkv * d * e + wrows * Hq * d * e
+    if name == "score_reduce":
+        return N * Hkv * d * e + wrows * Hq * d * e + N * Hkv * 4
+    if name == "select":
+        return N * Hkv * 4
+    if name == "compact":
+        return 4 * kept_rows * d * e
+    return 0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--layers", type=int, default=8, help="distinct layer buffers to rotate over")
+    ap.add_argument("--config", default="H", help="workload id in paper_2502_16886_amd.workloads.CONFIGS")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kv-layout", default="head_major", choices=["head_major", "token_major"],
+                    help="storage of K/V: [Hkv, N, d] (the [B, H, n, d] cache of the paper's setting) or [N, Hkv, d]")
+    ap.add_argument("--graph", type=int, default=1, help="replay the timed steps from a HIP graph (1) or launch eagerly (0)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU by design (units are independent; see DESIGN.md); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import rfkv_harness as H
+    from paper_2502_16886_amd import binding as B
+    from paper_2502_16886_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.load_library()
+    cfg_id = int(args.config) if args.config.isdigit() else args.config
+    cfg = W.CONFIGS[cfg_id]
+    e = 2 if cfg.dtype == "bf16" else 4
+
+    t0 = time.time()
+    host_layers = [W.make_layer(cfg_id, li) for li in range(args.layers)]
+    dls = {B.RANK_POSITION: [H.DeviceLayer(l, rank_mode=B.RANK_POSITION, kv_layout=args.kv_layout)
+                              for l in host_layers]}
+    # score ranking shares the inputs, with its own outputs
+    dls[B.RANK_SCORE] = []
+    for dl in dls[B.RANK_POSITION]:
+        d2 = H.DeviceLayer.__new__(H.DeviceLayer)
+        d2.__dict__.update(dl.__dict__)
+        d2.params = B.RfkvParams.from_buffer_copy(dl.params)
+        d2.params.rank_mode = B.RANK_SCORE
+        d2.buf = dl.buf
+        dls[B.RANK_SCORE].append(d2)
+    gen_s = time.time() - t0
+    N = dls[B.RANK_POSITION][0].N
+    wrows = int(np.minimum(cfg.window, np.diff(host_layers[0].cu_seqlens)).sum())
+    units = dls[B.RANK_POSITION][0].batch * cfg.n_kv_heads
+
+    def run_steps(mode, count, start=0):
+        for i in range(count):
+            dls[mode][(start + i) % args.layers].compress(None)   # torch's current stream
+
+    def timed(mode, steps, warmup):
+        run_steps(mode, warmup)
+        torch.cuda.synchronize()
+        graph = None
+        if args.graph:
+            # one graph holds `layers` consecutive steps; replays cover the timed region
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=None):
+                run_steps(mode, args.layers)
+            torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        ev0.record()
+        if graph is not None:
+            reps = (steps + args.layers - 1) // args.layers
+            for _ in range(reps):
+                graph.replay()
+            done = reps * args.layers
+        else:
+            run_steps(mode, steps)
+            done = steps
+        ev1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t
+        return wall / done * 1e3, ev0.elapsed_time(ev1) / done, done
+
+    results = {}
+    for mode in (B.RANK_POSITION, B.RANK_SCORE):
+        steps = args.steps if mode == B.RANK_POSITION else max(args.layers, args.steps // 4)
+        try:
+            wall_ms, ev_ms, done = timed(mode, steps, args.warmup)
+        except Exception as ex:          # graph capture unavailable: fall back to eager launches
+            if not args.graph:
+                raise
+            print(f"bench.py: graph replay failed ({ex}); timing eager launches", file=sys.stderr)
+            args.graph = 0
+            wall_ms, ev_ms, done = timed(mode, steps, args.warmup)
+        # per-kernel durations from HIP events recorded on the launch stream between kernels
+        kms = np.zeros(len(B.KERNEL_NAMES))
+        reps = max(args.layers, min(64, steps))
+        for i in range(reps):
+            dl = dls[mode][i % args.layers]
+            b = dl.buf
+            _, ms = B.rfkv_compress_layer_timed(dl.params, dl.q, dl.k, dl.v, dl.cu_host, dl.cu_dev, b.scores, b.kept,
+                                                b.out_offsets, b.idx, b.k_out, b.v_out, b.capacity_rows, b.ws,
+                                                b.ws_bytes, None)
+            kms += np.array(ms)
+        kms /= reps
+        kept_rows = float(np.mean([int(dl.buf.out_offsets[-1]) for dl in dls[mode]]))
+        results[mode] = dict(wall_ms=wall_ms, ev_ms=ev_ms, steps=done, kernel_ms=dict(zip(B.KERNEL_NAMES, kms.tolist())),
+                             kept_rows=kept_rows, retained=kept_rows / (N * cfg.n_kv_heads))
+
+    pos = results[B.RANK_POSITION]
+    ms_per_step = pos["wall_ms"]
+    value = N / (ms_per_step * 1e-3)
+    shape = (N, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows)
+    alg = algorithmic_bytes(*shape, pos["kept_rows"], units, False)
+    # dominant kernel = the one with the longest average duration
+    dom = max(pos["kernel_ms"], key=pos["kernel_ms"].get)
+    dom_bytes = kernel_bytes(dom, *shape, pos["kept_rows"])
+    dom_gbs = dom_bytes / (pos["kernel_ms"][dom] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel_ms": {k: round(v, 5) for k, v in pos["kernel_ms"].items()},
+                "kernel_algorithmic_bytes": int(dom_bytes),
+                "pipeline_algorithmic_bytes": int(alg),
+                "pipeline_achieved": round(alg / (ms_per_step * 1e-3) / 1e9, 1),
+                "pipeline_frac": round(alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    sco = results[B.RANK_SCORE]
+    alg_s = algorithmic_bytes(*shape, sco["kept_rows"], units, True)
+    score_mode = {"value": N / (sco["wall_ms"] * 1e-3), "ms_per_step": round(sco["wall_ms"], 5),
+                  "retained_fraction": round(sco["retained"], 4),
+                  "kernel_ms": {k: round(v, 5) for k, v in sco["kernel_ms"].items()},
+                  "pipeline_frac": round(alg_s / (sco["wall_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import refreekv_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        L0 = host_layers[0]
+        qf, kf = L0.f64("q_win"), L0.f64("k")
+        t = time.perf_counter()
+        out = O.oracle_compress_layer(qf, kf, L0.k, L0.v, L0.cu_seqlens, cfg.n_q_heads, cfg.n_kv_heads, cfg.window,
+                                      n_sink=cfg.n_sink, T=H.threshold_as_float32(cfg.threshold),
+                                      rank_mode=O.RANK_POSITION, form="cumsum")
+        dt = time.perf_counter() - t
+        # the run doubles as a last parity check of the benchmarked launch configuration
+        dl = dls[B.RANK_POSITION][0]
+        dl.compress(None)
+        gpu = dl.results()
+        agree = bool(np.array_equal(gpu["kept"], out["kept"]))
+        cpu = {"value": round(N / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"1 layer of the same workload ({N} tokens, all {cfg.n_kv_heads} KV heads), float64 numpy, "
+                         f"{dt:.2f} s", "kept_counts_match_gpu": agree}
+
+    line = {
+        "metric": "tokens/s compressed per layer-pass at Llama3-8B shape, 32K ctx; % peak HBM BW",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": pos["steps"], "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, d={cfg.head_dim}, "
+                               f"batch {dls[B.RANK_POSITION][0].batch}, {N} tokens, window {cfg.window}, T={cfg.threshold}, "
+                               f"m={cfg.n_sink}, position ranking, K/V {args.kv_layout}, {args.layers} rotating layer buffers",
+                   "rank_mode": "position", "retained_fraction": round(pos["retained"], 4),
+                   "launch": "hip_graph" if args.graph else "eager", "event_ms_per_step": round(pos["ev_ms"], 5),
+                   "input_generation_s": round(gen_s, 1)},
+        "percent_peak_hbm": round(100 * roofline["pipeline_frac"], 2),
+        "roofline": roofline, "cpu_baseline": cpu, "score_ranking": score_mode,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

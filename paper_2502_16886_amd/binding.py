@@ -23,7 +23,8 @@ RANK_SCORE = 1
 DTYPE_FP32 = 0
 DTYPE_BF16 = 1
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librfkv.so")
+# RFKV_LIBRARY points the binding at another build of the same library (kernel tuning variants)
+LIB_PATH = os.environ.get("RFKV_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librfkv.so")
 
 
 class RfkvParams(ctypes.Structure):
@@ -76,12 +77,16 @@ def load_library() -> ctypes.CDLL:
     lib.rfkv_compact.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.rfkv_compress_layer.restype = ctypes.c_int
     lib.rfkv_compress_layer.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    lib.rfkv_compress_layer_timed.restype = ctypes.c_int
+    lib.rfkv_compress_layer_timed.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp, vp]
     _lib = lib
     return lib
 
 
 EXPORTED_SYMBOLS = ("rfkv_version", "rfkv_status_string", "rfkv_last_device_error", "rfkv_workspace_bytes",
-                    "rfkv_score", "rfkv_select", "rfkv_compact", "rfkv_compress_layer")
+                    "rfkv_score", "rfkv_select", "rfkv_compact", "rfkv_compress_layer",
+                    "rfkv_compress_layer_timed")
+KERNEL_NAMES = ("score_stats", "score_merge", "score_reduce", "select", "compact")
 
 
 def status_string(status: int) -> str:
@@ -154,6 +159,17 @@ def rfkv_compress_layer(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, 
                                             _ptr(idx_opt), _ptr(k_out), _ptr(v_out), int(out_capacity_rows),
                                             _ptr(ws), int(ws_bytes), _stream(stream))
     return _check(st, "rfkv_compress_layer", check)
+
+
+def rfkv_compress_layer_timed(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, out_offsets, idx_opt,
+                              k_out, v_out, out_capacity_rows, ws, ws_bytes, stream=None, check=True):
+    """Returns (status, [ms per kernel in KERNEL_NAMES order]); synchronises the stream."""
+    ms = (ctypes.c_float * len(KERNEL_NAMES))()
+    st = load_library().rfkv_compress_layer_timed(
+        ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(v), _ptr(cu_host), _ptr(cu_dev), _ptr(scores_opt),
+        _ptr(kept), _ptr(out_offsets), _ptr(idx_opt), _ptr(k_out), _ptr(v_out), int(out_capacity_rows), _ptr(ws),
+        int(ws_bytes), _stream(stream), ctypes.cast(ms, ctypes.c_void_p))
+    return _check(st, "rfkv_compress_layer_timed", check), list(ms)
 
 
 # ----------------------------------------------------------------------------

@@ -26,6 +26,7 @@ Workspace carve_workspace(const Geometry& g, void* base) {
   w.desc = static_cast<int4*>(take((size_t)g.units * sizeof(int4)));
   w.idx_pad = static_cast<int32_t*>(take((size_t)g.total_tokens * g.n_kv_heads * sizeof(int32_t)));
   w.scores = static_cast<float*>(take((size_t)g.total_tokens * g.n_kv_heads * sizeof(float)));
+  w.tile_sq = static_cast<double*>(take((size_t)g.tiles_total * g.n_kv_heads * sizeof(double)));
   w.bytes = off;
   return w;
 }
@@ -92,7 +93,7 @@ rfkv_status check_cu(const rfkv_params* p, const int32_t* cu_host, const int32_t
   return RFKV_OK;
 }
 
-Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len) {
+Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len, const int32_t* cu_host = nullptr) {
   Geometry g{};
   g.batch = p->batch;
   g.n_q_heads = p->n_q_heads;
@@ -107,6 +108,12 @@ Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len) {
   g.max_seqlen = max_len;
   g.total_tokens = total;
   g.elem_bytes = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
+  // 32-position tiles per sequence; without the lengths, the bound every batch of this size obeys
+  g.tiles_total = (total + 31) / 32 + p->batch;
+  if (cu_host) {
+    g.tiles_total = 0;
+    for (int b = 0; b < p->batch; ++b) g.tiles_total += (cu_host[b + 1] - cu_host[b] + 31) / 32;
+  }
   return g;
 }
 
@@ -122,7 +129,7 @@ float scale_times_log2e(const rfkv_params* p) {
 }
 
 hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w, const void* q, const void* k,
-                     const int32_t* cu_dev, float* scores, hipStream_t stream) {
+                     const int32_t* cu_dev, float* scores, hipStream_t stream, const Marks* marks = nullptr) {
   ScoreArgs a{};
   a.q = q;
   a.k = k;
@@ -130,6 +137,8 @@ hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w
   a.cu = cu_dev;
   a.partials = w.partials;
   a.bvec = w.bvec;
+  a.tile_sq = w.tile_sq;
+  a.tiles_total = g.tiles_total;
   a.k_stride_tok = p->k_stride_tok;
   a.k_stride_head = p->k_stride_head;
   a.q_stride_row = p->q_stride_row;
@@ -142,17 +151,20 @@ hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w
   a.span = g.span;
   a.nspans = g.nspans;
   a.c = scale_times_log2e(p);
-  return launch_score(g, a, p->dtype == RFKV_DTYPE_BF16, stream);
+  return launch_score(g, a, p->dtype == RFKV_DTYPE_BF16, stream, marks);
 }
 
 hipError_t run_select(const rfkv_params* p, const Geometry& g, const Workspace& w, const float* scores,
-                      const int32_t* cu_dev, int32_t* kept, hipStream_t stream) {
+                      const int32_t* cu_dev, int32_t* kept, bool from_scores, hipStream_t stream) {
   SelectArgs a{};
   a.scores = scores;
   a.cu = cu_dev;
   a.kept = kept;
   a.desc = w.desc;
   a.idx_pad = p->rank_mode == RFKV_RANK_SCORE ? w.idx_pad : nullptr;
+  a.tile_sq = w.tile_sq;
+  a.tiles_total = g.tiles_total;
+  a.from_scores = from_scores ? 1 : 0;
   a.total_tokens = g.total_tokens;
   a.n_kv_heads = g.n_kv_heads;
   a.n_sink = p->n_sink;
@@ -217,7 +229,7 @@ rfkv_status rfkv_score(const rfkv_params* params, const void* q_win, const void*
   if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
   if (total == 0) return RFKV_OK;
   if (!aligned16(q_win) || !aligned16(k) || !aligned16(scores) || !aligned16(ws)) return RFKV_INVALID_ARG;
-  const Geometry g = make_geometry(params, total, max_len);
+  const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
   const Workspace w = carve_workspace(g, ws);
   if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
   return device_status(run_score(params, g, w, q_win, k, cu_seqlens_dev, scores, static_cast<hipStream_t>(stream)));
@@ -235,11 +247,11 @@ rfkv_status rfkv_select(const rfkv_params* params, const float* scores, const in
   if (params->batch == 0) return RFKV_OK;
   if (!aligned16(ws)) return RFKV_INVALID_ARG;
   if (total > 0 && (!aligned16(scores) || !idx)) return RFKV_INVALID_ARG;
-  const Geometry g = make_geometry(params, total, max_len);
+  const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
   const Workspace w = carve_workspace(g, ws);
   if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = run_select(params, g, w, scores, cu_seqlens_dev, kept, s);
+  hipError_t e = run_select(params, g, w, scores, cu_seqlens_dev, kept, true, s);
   if (e != hipSuccess) return device_status(e);
   CompactArgs c = compact_base(params, g, cu_seqlens_dev, kept);
   c.source = params->rank_mode == RFKV_RANK_SCORE ? kSrcPaddedIdx : kSrcPositionDesc;
@@ -263,7 +275,7 @@ rfkv_status rfkv_compact(const rfkv_params* params, const void* k, const void* v
   if (total == 0) return RFKV_OK;
   if (!kept || !out_offsets || !idx) return RFKV_INVALID_ARG;
   if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)) return RFKV_INVALID_ARG;
-  const Geometry g = make_geometry(params, total, max_len);
+  const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
   CompactArgs c = compact_base(params, g, cu_seqlens_dev, kept);
   c.k = k;
   c.v = v;
@@ -276,10 +288,10 @@ rfkv_status rfkv_compact(const rfkv_params* params, const void* k, const void* v
   return device_status(launch_compact(g, c, static_cast<hipStream_t>(stream)));
 }
 
-rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, const void* k, const void* v,
+static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_win, const void* k, const void* v,
                                 const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores_opt,
                                 int32_t* kept, int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
-                                int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream) {
+                                int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream, const Marks* marks) {
   rfkv_status st = check_params(params);
   if (st != RFKV_OK) return st;
   if ((st = check_strides(params, true, true, true)) != RFKV_OK) return st;
@@ -292,16 +304,17 @@ rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, co
   if (total > 0 && (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)))
     return RFKV_INVALID_ARG;
   if (scores_opt && !aligned16(scores_opt)) return RFKV_INVALID_ARG;
-  const Geometry g = make_geometry(params, total, max_len);
+  const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
   const Workspace w = carve_workspace(g, ws);
   if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* scores = scores_opt ? scores_opt : w.scores;
   hipError_t e = hipSuccess;
-  if (total > 0) e = run_score(params, g, w, q_win, k, cu_seqlens_dev, scores, s);
+  if (total > 0) e = run_score(params, g, w, q_win, k, cu_seqlens_dev, scores, s, marks);
   if (e != hipSuccess) return device_status(e);
-  e = run_select(params, g, w, scores, cu_seqlens_dev, kept, s);
+  e = run_select(params, g, w, scores, cu_seqlens_dev, kept, false, s);
   if (e != hipSuccess) return device_status(e);
+  if (marks) marks->after(kKernelSelect);
   CompactArgs c = compact_base(params, g, cu_seqlens_dev, kept);
   c.k = k;
   c.v = v;
@@ -313,7 +326,51 @@ rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, co
   c.offsets_out = out_offsets;
   c.idx_out = idx_opt;
   c.capacity_rows = out_capacity_rows;
-  return device_status(launch_compact(g, c, s));
+  e = launch_compact(g, c, s);
+  if (marks && e == hipSuccess) marks->after(kKernelCompact);
+  return device_status(e);
+}
+
+rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, const void* k, const void* v,
+                                const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores_opt,
+                                int32_t* kept, int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
+                                int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream) {
+  return compress_layer_impl(params, q_win, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept, out_offsets,
+                             idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, nullptr);
+}
+
+rfkv_status rfkv_compress_layer_timed(const rfkv_params* params, const void* q_win, const void* k, const void* v,
+                                      const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
+                                      float* scores_opt, int32_t* kept, int64_t* out_offsets, int32_t* idx_opt,
+                                      void* k_out, void* v_out, int64_t out_capacity_rows, void* ws,
+                                      size_t ws_bytes, void* stream, float* kernel_ms_host) {
+  if (!kernel_ms_host) return RFKV_INVALID_ARG;
+  for (int i = 0; i < kNumKernels; ++i) kernel_ms_host[i] = 0.f;
+  Marks m{};
+  m.stream = static_cast<hipStream_t>(stream);
+  int made = 0;
+  hipError_t e = hipSuccess;
+  for (; made <= kNumKernels && e == hipSuccess; ++made) e = hipEventCreate(&m.ev[made]);
+  if (e != hipSuccess) --made;
+  rfkv_status st = RFKV_OK;
+  if (e != hipSuccess) {
+    st = device_status(e);
+  } else {
+    // every slot gets a record first so that kernels this problem skips read as zero time
+    for (int i = 0; i <= kNumKernels; ++i) (void)hipEventRecord(m.ev[i], m.stream);
+    st = compress_layer_impl(params, q_win, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept, out_offsets,
+                             idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, &m);
+    e = hipStreamSynchronize(m.stream);
+    if (st == RFKV_OK && e != hipSuccess) st = device_status(e);
+    if (st == RFKV_OK) {
+      for (int i = 0; i < kNumKernels; ++i) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, m.ev[i], m.ev[i + 1]) == hipSuccess && ms > 0.f) kernel_ms_host[i] = ms;
+      }
+    }
+  }
+  for (int i = 0; i < made; ++i) (void)hipEventDestroy(m.ev[i]);
+  return st;
 }
 
 }  // extern "C"

@@ -17,8 +17,15 @@
 namespace rfkv {
 namespace {
 
-constexpr int kRowsPerBlock = 64;
-constexpr int kUnroll = 4;
+#ifndef RFKV_COMPACT_ROWS
+#define RFKV_COMPACT_ROWS 16
+#endif
+#ifndef RFKV_COMPACT_UNROLL
+#define RFKV_COMPACT_UNROLL 1
+#endif
+constexpr int kRowsPerBlock = RFKV_COMPACT_ROWS;
+constexpr int kUnroll = RFKV_COMPACT_UNROLL;
+constexpr int kUniformPrefixUnits = 256;   // up to here every thread sums the earlier kept counts itself
 
 __device__ __forceinline__ int64_t block_sum_i64(int64_t v, int64_t* sh /*[4]*/) {
 #pragma unroll
@@ -42,12 +49,21 @@ __global__ __launch_bounds__(kBlockThreads) void compact_kernel(CompactArgs a) {
   if (a.source == kSrcPackedIdx) {
     off = a.offsets_in[unit];
   } else {
-    int64_t part = 0;
-    for (int u = threadIdx.x; u < unit; u += kBlockThreads) {
-      const int bu = u / a.n_kv_heads;
-      part += min(max(a.kept[u], 0), a.cu[bu + 1] - a.cu[bu]);
+    if (unit <= kUniformPrefixUnits) {
+      // uniform loop: scalar loads, no LDS, no barrier
+      off = 0;
+      for (int u = 0; u < unit; ++u) {
+        const int bu = u / a.n_kv_heads;
+        off += min(max(a.kept[u], 0), a.cu[bu + 1] - a.cu[bu]);
+      }
+    } else {
+      int64_t part = 0;
+      for (int u = threadIdx.x; u < unit; u += kBlockThreads) {
+        const int bu = u / a.n_kv_heads;
+        part += min(max(a.kept[u], 0), a.cu[bu + 1] - a.cu[bu]);
+      }
+      off = block_sum_i64(part, sh_sum);
     }
-    off = block_sum_i64(part, sh_sum);
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.offsets_out) {
       a.offsets_out[unit] = off;
       if (unit == a.units - 1) a.offsets_out[a.units] = off + kept;

@@ -22,6 +22,7 @@ struct Geometry {
   int32_t max_seqlen;
   int64_t total_tokens;   // N
   int32_t elem_bytes;     // 2 (bf16) or 4 (fp32)
+  int64_t tiles_total;    // sum over sequences of ceil(n_b / 32) (an upper bound when sizing)
 };
 
 struct Workspace {
@@ -30,6 +31,7 @@ struct Workspace {
   int4*    desc;          // [units]                    {kept, sinks kept, -, -}
   int32_t* idx_pad;       // [N * Hkv]                  per-unit padded index lists (score ranking)
   float*   scores;        // [Hkv][N]                   used when the caller does not want scores
+  double*  tile_sq;       // [Hkv][tiles_total]         sum of squared scores per 32-position tile
   size_t   bytes;
 };
 
@@ -42,6 +44,8 @@ struct ScoreArgs {
   const int32_t* cu;
   float2* partials;
   float* bvec;
+  double* tile_sq;
+  int64_t tiles_total;
   int64_t k_stride_tok, k_stride_head, q_stride_row, q_stride_head;
   int64_t total_tokens;
   int32_t n_kv_heads, group, window, rows_pad, span, nspans;
@@ -54,7 +58,10 @@ struct SelectArgs {
   int32_t* kept;
   int4* desc;
   int32_t* idx_pad;
+  double* tile_sq;        // per-tile squared-score sums: read; written first when from_scores is set
+  int64_t tiles_total;
   int64_t total_tokens;
+  int32_t from_scores;    // the tile sums are not there yet: form them from the scores first
   int32_t n_kv_heads, n_sink, min_keep, rank_mode;
   float threshold;
 };
@@ -79,7 +86,16 @@ struct CompactArgs {
   int32_t n_kv_heads, units, row_bytes, source;
 };
 
-hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream);
+// Optional per-kernel timing: events recorded on the launch stream between kernels.
+enum KernelId { kKernelStats = 0, kKernelMerge, kKernelReduce, kKernelSelect, kKernelCompact, kNumKernels };
+struct Marks {
+  hipEvent_t ev[kNumKernels + 1];
+  hipStream_t stream;
+  void after(int kernel) const { (void)hipEventRecord(ev[kernel + 1], stream); }
+};
+
+hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream,
+                        const Marks* marks = nullptr);
 hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t stream);
 hipError_t launch_compact(const Geometry& g, const CompactArgs& a, hipStream_t stream);
 

@@ -20,6 +20,7 @@
 // per lane, and Q is staged in LDS with a 16-byte row pad so the same chunk reads are
 // bank-conflict free.  fp32 inputs use the 32x32x2 fp32 MFMA with the same scheme.
 #include "kernels.h"
+#include "tile_sum.h"
 
 namespace rfkv {
 namespace {
@@ -67,15 +68,21 @@ struct Unit {
   int q0;           // first packed window row of the sequence
   int rows;         // wp * group
   int row_tiles;    // ceil(rows / 32)
+  int tile_base;    // first 32-position tile of the sequence in the per-head tile arrays
 };
 
 __device__ __forceinline__ Unit load_unit(const ScoreArgs& a, int unit) {
   Unit u;
   u.b = unit / a.n_kv_heads;
   u.h = unit - u.b * a.n_kv_heads;
-  int q0 = 0;
-  for (int bb = 0; bb < u.b; ++bb) q0 += min(a.window, a.cu[bb + 1] - a.cu[bb]);
+  int q0 = 0, tb = 0;
+  for (int bb = 0; bb < u.b; ++bb) {
+    const int len = a.cu[bb + 1] - a.cu[bb];
+    q0 += min(a.window, len);
+    tb += (len + kTileKeys - 1) / kTileKeys;
+  }
   u.q0 = q0;
+  u.tile_base = tb;
   u.s0 = a.cu[u.b];
   u.n = a.cu[u.b + 1] - u.s0;
   u.wp = min(a.window, u.n);
@@ -226,26 +233,37 @@ __global__ __launch_bounds__(kBlockThreads) void score_stats_kernel(ScoreArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
-// merge: b_r = ref_r + log2(sum_r * G); rows that do not exist get +inf (weight zero)
+// merge: b_r = ref_r + log2(sum_r * G); rows that do not exist get +inf (weight zero).
+// Workgroup = 8 rows x 32 lanes; the 32 lanes of a row split the spans and combine by shuffles.
 // ---------------------------------------------------------------------------------------------
-__global__ void score_merge_kernel(ScoreArgs a) {
-  const Unit u = load_unit(a, blockIdx.x);
-  const int r = threadIdx.x;
+constexpr int kMergeRows = 8;
+
+__global__ __launch_bounds__(kBlockThreads) void score_merge_kernel(ScoreArgs a) {
+  const Unit u = load_unit(a, blockIdx.y);
+  const int r = blockIdx.x * kMergeRows + (threadIdx.x >> 5);
+  const int sub = threadIdx.x & 31;
   if (r >= a.rows_pad) return;
-  float out = __builtin_inff();
+  const int nsp = (u.n + a.span - 1) / a.span;
+  const float2* p = a.partials + (int64_t)blockIdx.y * a.nspans * a.rows_pad + r;
+  float m = -1e30f, sum = 0.f;
   if (r < u.rows) {
-    const int nsp = (u.n + a.span - 1) / a.span;
-    const float2* p = a.partials + (int64_t)blockIdx.x * a.nspans * a.rows_pad + r;
-    float m = -1e30f;
-    for (int s = 0; s < nsp; ++s) m = fmaxf(m, p[(int64_t)s * a.rows_pad].x);
-    float sum = 0.f;
-    for (int s = 0; s < nsp; ++s) {
+    for (int s = sub; s < nsp; s += 32) {
       const float2 v = p[(int64_t)s * a.rows_pad];
-      sum += v.y * fast_exp2(v.x - m);
+      const float nm = fmaxf(m, v.x);
+      sum = sum * fast_exp2(m - nm) + v.y * fast_exp2(v.x - nm);
+      m = nm;
     }
-    out = m + __log2f(sum * (float)a.group);
   }
-  a.bvec[(int64_t)blockIdx.x * a.rows_pad + r] = out;
+#pragma unroll
+  for (int d = 16; d >= 1; d >>= 1) {
+    const float om = __shfl_xor(m, d), os = __shfl_xor(sum, d);
+    const float nm = fmaxf(m, om);
+    sum = sum * fast_exp2(m - nm) + os * fast_exp2(om - nm);
+    m = nm;
+  }
+  if (sub == 0)
+    a.bvec[(int64_t)blockIdx.y * a.rows_pad + r] =
+        r < u.rows ? m + __log2f(sum * (float)a.group) : __builtin_inff();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -333,7 +351,11 @@ __global__ __launch_bounds__(kBlockThreads) void score_reduce_kernel(ScoreArgs a
     for (int kt = 0; kt < KT; ++kt) {
       const float tot = colsum[kt] + __shfl_xor(colsum[kt], 32);
       const int key = tile0 + kt * 32 + col;
-      if (hi == 0 && key < u.n) out[key] = tot / (float)min(u.wp, u.n - key);
+      const float score = key < u.n ? tot / (float)min(u.wp, u.n - key) : 0.f;
+      if (hi == 0 && key < u.n) out[key] = score;
+      const double tsq = tile_sum_sq(score, lane);
+      if (lane == 0 && tile0 + kt * 32 < u.n)
+        a.tile_sq[(int64_t)u.h * a.tiles_total + u.tile_base + (tile0 >> 5) + kt] = tsq;
     }
   }
 }
@@ -355,7 +377,7 @@ hipError_t launch_stats(const Geometry& g, const ScoreArgs& a, dim3 grid, hipStr
 }
 
 template <typename T, int D>
-hipError_t launch_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream) {
+hipError_t launch_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const dim3 grid(g.nspans, g.units);
   const int rt = g.rows_pad / 32;
   hipError_t e;
@@ -365,28 +387,33 @@ hipError_t launch_typed(const Geometry& g, const ScoreArgs& a, hipStream_t strea
   else if (rt <= 8) e = launch_stats<T, D, 8>(g, a, grid, stream);
   else e = launch_stats<T, D, 16>(g, a, grid, stream);
   if (e != hipSuccess) return e;
+  if (marks) marks->after(kKernelStats);
 
-  hipLaunchKernelGGL(score_merge_kernel, dim3(g.units), dim3(g.rows_pad), 0, stream, a);
+  hipLaunchKernelGGL(score_merge_kernel, dim3((g.rows_pad + kMergeRows - 1) / kMergeRows, g.units),
+                     dim3(kBlockThreads), 0, stream, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (marks) marks->after(kKernelMerge);
 
   const size_t lds = (size_t)g.rows_pad * (Shape<T, D>::kLdsRowBytes + 8);
   e = allow_lds(score_reduce_kernel<T, D>, lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((score_reduce_kernel<T, D>), grid, dim3(kBlockThreads), lds, stream, a);
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (marks && e == hipSuccess) marks->after(kKernelReduce);
+  return e;
 }
 
 }  // namespace
 
-hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream) {
+hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks) {
   if (g.units == 0 || g.nspans == 0) return hipSuccess;
   if (bf16) {
-    if (g.head_dim == 64) return launch_typed<Bf16, 64>(g, a, stream);
-    return launch_typed<Bf16, 128>(g, a, stream);
+    if (g.head_dim == 64) return launch_typed<Bf16, 64>(g, a, stream, marks);
+    return launch_typed<Bf16, 128>(g, a, stream, marks);
   }
-  if (g.head_dim == 64) return launch_typed<Fp32, 64>(g, a, stream);
-  return launch_typed<Fp32, 128>(g, a, stream);
+  if (g.head_dim == 64) return launch_typed<Fp32, 64>(g, a, stream, marks);
+  return launch_typed<Fp32, 128>(g, a, stream, marks);
 }
 
 }  // namespace rfkv

@@ -16,6 +16,7 @@
 // of elements taken from the final all-equal bucket by bisection.  The retained positions are
 // then emitted in ascending order with a block-wide scan (ties: the lowest positions win).
 #include "kernels.h"
+#include "tile_sum.h"
 
 namespace rfkv {
 namespace {
@@ -89,9 +90,54 @@ __device__ __forceinline__ double block_sum_double(double v, double* wave_tot) {
   return t;
 }
 
+// Per-tile squared-score sums straight from a score array (used when scoring did not run in
+// the same call).  One wavefront per tile, same butterfly as the scoring kernel.
+__global__ __launch_bounds__(kBlockThreads) void tile_sums_kernel(SelectArgs a) {
+  const int unit = blockIdx.y;
+  const int b = unit / a.n_kv_heads, h = unit - b * a.n_kv_heads;
+  int tile_base = 0;
+  for (int bb = 0; bb < b; ++bb) tile_base += (a.cu[bb + 1] - a.cu[bb] + kTileKeys - 1) / kTileKeys;
+  const int s0 = a.cu[b];
+  const int n = a.cu[b + 1] - s0;
+  const int nt = (n + kTileKeys - 1) / kTileKeys;
+  const int lane = threadIdx.x & 63;
+  const int tile = blockIdx.x * (kBlockThreads / 64) + (threadIdx.x >> 6);
+  if (tile >= nt) return;                                  // uniform per wavefront
+  const float* s = a.scores + (int64_t)h * a.total_tokens + s0;
+  const int pos = tile * kTileKeys + lane;
+  const float v = (lane < kTileKeys && pos < n) ? s[pos] : 0.f;
+  const double t = tile_sum_sq(v, lane);
+  if (lane == 0) a.tile_sq[(int64_t)h * a.tiles_total + tile_base + tile] = t;
+}
+
+// The stopping test 1 - sqrt(P / F^2) < T on fp64 masses.  Away from the boundary the cheap
+// squared form P > (1 - T)^2 F^2 decides; only within 1e-9 relative of it is the paper's form
+// (an fp64 divide and square root) evaluated, so sequential walks stay short.
+struct PredF {
+  double total;     // F^2
+  double T;
+  int min_keep;
+  double lo, hi;    // (1 - T)^2 F^2 shrunk / grown by 1e-9: below lo certainly false, above hi certainly true
+  __device__ PredF(double f2, double t, int mk) : total(f2), T(t), min_keep(mk) {
+    const double thr = t < 1.0 ? (1.0 - t) * (1.0 - t) * f2 : -1.0;     // T >= 1: any positive mass qualifies
+    lo = thr * (1.0 - 1e-9);
+    hi = thr * (1.0 + 1e-9);
+    if (t >= 1.0) { lo = -1.0; hi = -2.0; }                             // always take the exact path
+  }
+  __device__ bool operator()(int64_t count, double mass) const {
+    if (count <= 0 || count < min_keep) return false;
+    if (hi >= lo) {
+      if (mass > hi) return true;
+      if (mass < lo) return false;
+    }
+    return 1.0 - sqrt(mass / total) < T;
+  }
+};
+
 __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
   __shared__ uint64_t sh_scan[kWaves + 1];
   __shared__ double sh_dbl[kWaves];
+  __shared__ double sh_incl[kT];
   __shared__ uint32_t sh_cnt[kBuckets];
   __shared__ uint64_t sh_mass[kBuckets];
   __shared__ int sh_i[8];
@@ -99,6 +145,8 @@ __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
 
   const int unit = blockIdx.x;
   const int b = unit / a.n_kv_heads, h = unit - b * a.n_kv_heads;
+  int tile_base = 0;
+  for (int bb = 0; bb < b; ++bb) tile_base += (a.cu[bb + 1] - a.cu[bb] + kTileKeys - 1) / kTileKeys;
   const int s0 = a.cu[b];
   const int n = a.cu[b + 1] - s0;
   const int tid = threadIdx.x;
@@ -110,53 +158,138 @@ __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
     return;
   }
   const float* s = a.scores + (int64_t)h * a.total_tokens + s0;
+  const double* tiles = a.tile_sq + (int64_t)h * a.tiles_total + tile_base;
+  const int nt = (n + kTileKeys - 1) / kTileKeys;
   int32_t* idx_pad = a.idx_pad ? a.idx_pad + ((int64_t)s0 * a.n_kv_heads + (int64_t)h * n) : nullptr;
   const int m_eff = min(max(a.n_sink, 0), n);
   const bool by_score = a.rank_mode == 1;
-
-  // F^2 in fp64 (fixed reduction order), then exact integer masses
-  double f2 = 0.0;
-  for (int i = tid; i < n; i += kT) f2 += (double)s[i] * (double)s[i];
-  f2 = block_sum_double(f2, sh_dbl);
-  const bool degenerate = !(f2 > 0.0) || !(f2 < 1e300);   // all-zero (or non-finite) scores: keep all
-  const double inv = degenerate ? 0.0 : 1152921504606846976.0 / f2;      // 2^60 / F^2
+  const bool keep_all = !(a.threshold > 0.f);              // T <= 0: no prefix short of everything qualifies
 
   int kept = n;
-  int sinks_kept = m_eff;
+  bool degenerate = false;
+  double f2 = 0.0;
 
-  if (!degenerate && !by_score) {
-    // ---------------- position ranking: rank r -> position r (r < m) or n-1-(r-m)
-    const int L = (n + kT - 1) / kT;
-    const int r0 = min(n, tid * L), r1 = min(n, r0 + L);
-    uint64_t mine = 0;
-    for (int r = r0; r < r1; ++r) {
-      const int pos = r < m_eff ? r : n - 1 - (r - m_eff);
-      mine += quantise(s[pos], inv);
+  if (!by_score && !keep_all) {
+    // ---------------- position ranking: first the sinks [0, m), then the rest from the end backwards.
+    // Sink mass directly; tail mass per 32-position tile (from the scoring kernel), reversed.
+    double sink = 0.0;
+    if (m_eff <= 32) {                                     // the usual case (m = 4): every thread sums them itself
+      for (int p = 0; p < m_eff; ++p) sink += (double)s[p] * (double)s[p];
+    } else {
+      for (int p = tid; p < m_eff; p += kT) sink += (double)s[p] * (double)s[p];
+      sink = block_sum_double(sink, sh_dbl);
     }
-    uint64_t total;
-    const uint64_t base = block_exclusive_scan<uint64_t>(mine, sh_scan, &total);
-    const Pred pred{(double)total, (double)a.threshold, a.min_keep};
-    if (tid == 0) sh_i[0] = n;                     // no crossing: keep everything
+    const int jm = m_eff / kTileKeys;                      // first tile holding a tail position
+    const int ntail = m_eff < n ? nt - jm : 0;
+    const int C = (ntail + kT - 1) / kT;                   // tail tiles per thread, in rank order
+    const int k0 = min(ntail, tid * C), k1 = min(ntail, k0 + C);
+    auto tile_mass = [&](int j) -> double {                // tail mass of tile j
+      if (j > jm || m_eff % kTileKeys == 0) return tiles[j];
+      double v = 0.0;                                      // the tile shared with the sinks
+      for (int p = min(n, (j + 1) * kTileKeys) - 1; p >= m_eff; --p) v += (double)s[p] * (double)s[p];
+      return v;
+    };
+    double mine = 0.0;
+    for (int k = k0; k < k1; ++k) mine += tile_mass(nt - 1 - k);
+    // inclusive scan over threads, fixed order
+    const int lane = tid & 63, wave = tid >> 6;
+    double inc = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const double o = __shfl_up(inc, d);
+      if (lane >= d) inc += o;
+    }
     __syncthreads();
-    if (r1 > r0) {
-      const bool before = r0 > 0 && pred(r0, base);
-      const bool after = pred(r1, base + mine);
-      if (!before && after) {
-        uint64_t run = base;
-        for (int r = r0; r < r1; ++r) {
-          const int pos = r < m_eff ? r : n - 1 - (r - m_eff);
-          run += quantise(s[pos], inv);
-          if (pred(r + 1, run)) {
-            sh_i[0] = r + 1;
-            break;
+    if (lane == 63) sh_dbl[wave] = inc;
+    __syncthreads();
+    double wave_off = 0.0;
+    for (int w = 0; w < wave; ++w) wave_off += sh_dbl[w];
+    double tail_total = 0.0;
+    for (int w = 0; w < kWaves; ++w) tail_total += sh_dbl[w];
+    inc += wave_off;
+    sh_incl[tid] = inc;
+    f2 = sink + tail_total;
+    degenerate = !(f2 > 0.0) || !(f2 < 1e300);
+    if (tid == 0) {
+      sh_i[0] = n;          // result: no crossing keeps everything
+      sh_i[3] = kT;         // first thread whose chunk end satisfies the rule
+    }
+    __syncthreads();
+    if (!degenerate) {
+      const PredF pred(f2, (double)a.threshold, a.min_keep);
+      // ranks covered up to and including tail-rank tile k: sinks + positions from the end down to tile start
+      auto count_through = [&](int k) -> int { return m_eff + n - max((nt - 1 - k) * kTileKeys, m_eff); };
+      // Search one run of consecutive ranks with a wavefront: lane l takes the l-th rank of the
+      // run (position first + l * step), an inclusive fp64 prefix over lanes gives the mass through
+      // each rank, and the first lane whose prefix satisfies the rule is the cut.
+      auto wave_search = [&](int first, int step, int len, int ranks_before, double mass_before, int fallback) {
+        const int p = first + lane * step;
+        double v = 0.0;
+        if (lane < len) v = (double)s[p] * (double)s[p];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const double o = __shfl_up(v, d);
+          if (lane >= d) v += o;
+        }
+        const bool ok = lane < len && pred(ranks_before + lane + 1, mass_before + v);
+        const unsigned long long mask = __ballot(ok);
+        if (lane == 0) sh_i[0] = mask ? ranks_before + __ffsll((long long)mask) : fallback;
+      };
+      if (pred(m_eff, sink)) {
+        // the cut falls inside the sinks
+        if (m_eff <= 64) {
+          if (wave == 0) wave_search(0, 1, m_eff, 0, 0.0, m_eff);
+        } else if (tid == 0) {
+          double run = 0.0;
+          int res = m_eff;
+          for (int p = 0; p < m_eff; ++p) {
+            run += (double)s[p] * (double)s[p];
+            if (pred(p + 1, run)) {
+              res = p + 1;
+              break;
+            }
           }
+          sh_i[0] = res;
+        }
+      } else {
+        if (k1 > k0 && pred(count_through(k1 - 1), sink + inc)) atomicMin(&sh_i[3], tid);
+        __syncthreads();
+        if (sh_i[3] == tid) {
+          // the tile of this thread's chunk in which the rule is first met (the last one if rounding hides it)
+          double run = sink + (tid > 0 ? sh_incl[tid - 1] : 0.0);
+          int jstar = nt - k1;
+          for (int k = k0; k + 1 < k1; ++k) {
+            const double tm = tile_mass(nt - 1 - k);
+            if (pred(count_through(k), run + tm)) {
+              jstar = nt - 1 - k;
+              break;
+            }
+            run += tm;
+          }
+          sh_i[4] = jstar;
+          sh_dbl[0] = run;
+        }
+        __syncthreads();
+        if (sh_i[3] < kT && wave == 0) {
+          const int jt = sh_i[4];
+          const int hi_p = min(n, (jt + 1) * kTileKeys) - 1, lo_p = max(jt * kTileKeys, m_eff);
+          wave_search(hi_p, -1, hi_p - lo_p + 1, m_eff + (n - 1 - hi_p), sh_dbl[0], m_eff + (n - lo_p));
         }
       }
     }
     __syncthreads();
-    kept = sh_i[0];
-    sinks_kept = min(kept, m_eff);
-  } else if (!degenerate) {
+    kept = degenerate ? n : sh_i[0];
+  } else if (by_score && !keep_all) {
+    for (int j = tid; j < nt; j += kT) f2 += tiles[j];
+    f2 = block_sum_double(f2, sh_dbl);
+    degenerate = !(f2 > 0.0) || !(f2 < 1e300);
+  }
+  const double inv = (degenerate || keep_all || !by_score) ? 0.0 : 1152921504606846976.0 / f2;      // 2^60 / F^2
+
+  if (by_score && (degenerate || keep_all)) {
+    if (idx_pad)
+      for (int i = tid; i < n; i += kT) idx_pad[i] = i;
+  } else if (by_score) {
     // ---------------- score ranking: radix select of the cut value
     uint64_t mine = 0;
     for (int i = tid; i < n; i += kT) mine += quantise(s[i], inv);
@@ -282,23 +415,26 @@ __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
         }
       }
     }
-    sinks_kept = 0;
-  } else if (by_score && idx_pad) {
-    for (int i = tid; i < n; i += kT) idx_pad[i] = i;
   }
 
-  if (degenerate) kept = n;
   if (tid == 0) {
     a.kept[unit] = kept;
     a.desc[unit] = make_int4(kept, by_score ? 0 : min(kept, m_eff), 0, 0);
   }
-  (void)sinks_kept;
 }
 
 }  // namespace
 
 hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t stream) {
   if (g.units == 0) return hipSuccess;
+  if (a.from_scores && g.max_seqlen > 0) {
+    const int tiles = (g.max_seqlen + kTileKeys - 1) / kTileKeys;
+    const int per_block = kBlockThreads / 64;
+    hipLaunchKernelGGL(tile_sums_kernel, dim3((tiles + per_block - 1) / per_block, g.units), dim3(kBlockThreads), 0,
+                       stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL(select_kernel, dim3(g.units), dim3(kT), 0, stream, a);
   return hipGetLastError();
 }

@@ -36,7 +36,8 @@ def to_host_bits(t, dtype: str) -> np.ndarray:
 class DeviceLayer:
     """Inputs of one layer resident on the GPU plus the parameter struct."""
 
-    def __init__(self, layer: W.Layer, rank_mode=B.RANK_POSITION, threshold=None, min_keep=0, n_sink=None):
+    def __init__(self, layer: W.Layer, rank_mode=B.RANK_POSITION, threshold=None, min_keep=0, n_sink=None,
+                 kv_layout="token_major"):
         import torch
         c = layer.cfg
         self.layer = layer
@@ -53,6 +54,15 @@ class DeviceLayer:
                                     n_sink=c.n_sink if n_sink is None else n_sink,
                                     threshold=c.threshold if threshold is None else threshold,
                                     rank_mode=rank_mode, min_keep=min_keep)
+        self.kv_layout = kv_layout
+        if kv_layout == "head_major":
+            # [Hkv, N, d]: each head's rows contiguous (for one sequence, the [B, H, n, d] cache layout)
+            self.k = self.k.permute(1, 0, 2).contiguous()
+            self.v = self.v.permute(1, 0, 2).contiguous()
+            self.params.k_stride_tok = self.params.v_stride_tok = c.head_dim
+            self.params.k_stride_head = self.params.v_stride_head = max(self.N, 1) * c.head_dim
+        else:
+            assert kv_layout == "token_major"          # [N, Hkv, d]
         self.buf = B.alloc_layer_buffers(self.params, self.N, self.max_len)
 
     def compress(self, stream=None):
