@@ -357,7 +357,7 @@ rfkv_status rfkv_compress_layer_timed(const rfkv_params* params, const void* q_w
     st = device_status(e);
   } else {
     // every slot gets a record first so that kernels this problem skips read as zero time
-    for (int i = 0; i <= kNumKernels; ++i) (void)hipEventRecord(m.ev[i], m.stream);
+    for (int i = kNumKernels; i >= 0; --i) (void)hipEventRecord(m.ev[i], m.stream);      // start event last
     st = compress_layer_impl(params, q_win, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept, out_offsets,
                              idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, &m);
     e = hipStreamSynchronize(m.stream);

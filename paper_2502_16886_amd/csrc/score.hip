@@ -20,97 +20,11 @@
 // per lane, and Q is staged in LDS with a 16-byte row pad so the same chunk reads are
 // bank-conflict free.  fp32 inputs use the 32x32x2 fp32 MFMA with the same scheme.
 #include "kernels.h"
+#include "score_common.h"
 #include "tile_sum.h"
 
 namespace rfkv {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-struct Bf16 { static constexpr int kBytes = 2; };
-struct Fp32 { static constexpr int kBytes = 4; };
-
-template <typename T, int D>
-struct Shape {
-  static constexpr int kRowBytes = D * T::kBytes;
-  static constexpr int kHalfBytes = kRowBytes / 2;      // owned by one lane
-  static constexpr int kChunks = kHalfBytes / 16;
-  static constexpr int kLdsRowBytes = kRowBytes + 16;   // pad: consecutive rows shift by 4 banks
-};
-
-constexpr int KT = kKeyTilesPerWave;
-
-template <typename T>
-__device__ __forceinline__ f32x16 mma_chunk(const uint4& a, const uint4& b, f32x16 acc);
-
-template <>
-__device__ __forceinline__ f32x16 mma_chunk<Bf16>(const uint4& a, const uint4& b, f32x16 acc) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                 __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
-}
-
-template <>
-__device__ __forceinline__ f32x16 mma_chunk<Fp32>(const uint4& a, const uint4& b, f32x16 acc) {
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
-  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
-  return acc;
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-struct Unit {
-  int b, h;
-  int s0, n;        // first packed token and length of the sequence
-  int wp;           // window rows in use, min(window, n)
-  int q0;           // first packed window row of the sequence
-  int rows;         // wp * group
-  int row_tiles;    // ceil(rows / 32)
-  int tile_base;    // first 32-position tile of the sequence in the per-head tile arrays
-};
-
-__device__ __forceinline__ Unit load_unit(const ScoreArgs& a, int unit) {
-  Unit u;
-  u.b = unit / a.n_kv_heads;
-  u.h = unit - u.b * a.n_kv_heads;
-  int q0 = 0, tb = 0;
-  for (int bb = 0; bb < u.b; ++bb) {
-    const int len = a.cu[bb + 1] - a.cu[bb];
-    q0 += min(a.window, len);
-    tb += (len + kTileKeys - 1) / kTileKeys;
-  }
-  u.q0 = q0;
-  u.tile_base = tb;
-  u.s0 = a.cu[u.b];
-  u.n = a.cu[u.b + 1] - u.s0;
-  u.wp = min(a.window, u.n);
-  u.rows = u.wp * a.group;
-  u.row_tiles = (u.rows + 31) >> 5;
-  return u;
-}
-
-// Window queries of the unit -> LDS, row r = t * G + g, rows beyond `rows` zero.
-template <typename T, int D>
-__device__ __forceinline__ void stage_q(const ScoreArgs& a, const Unit& u, unsigned char* smem) {
-  using S = Shape<T, D>;
-  constexpr int kChunksPerRow = S::kRowBytes / 16;
-  const int total = u.row_tiles * 32 * kChunksPerRow;
-  const unsigned char* qbase = static_cast<const unsigned char*>(a.q);
-  for (int i = threadIdx.x; i < total; i += kBlockThreads) {
-    const int r = i / kChunksPerRow;
-    const int c = i - r * kChunksPerRow;
-    uint4 val = make_uint4(0, 0, 0, 0);
-    if (r < u.rows) {
-      const int t = r / a.group;
-      const int g = r - t * a.group;
-      const int64_t off = (int64_t)(u.q0 + t) * a.q_stride_row + (int64_t)(u.h * a.group + g) * a.q_stride_head;
-      val = *reinterpret_cast<const uint4*>(qbase + off * T::kBytes + c * 16);
-    }
-    *reinterpret_cast<uint4*>(smem + r * S::kLdsRowBytes + c * 16) = val;
-  }
-}
 
 template <typename T, int D>
 __device__ __forceinline__ void load_k_half(uint4* f, const unsigned char* kunit,
@@ -360,13 +274,6 @@ __global__ __launch_bounds__(kBlockThreads) void score_reduce_kernel(ScoreArgs a
   }
 }
 
-template <typename K>
-hipError_t allow_lds(K kernel, size_t bytes) {
-  if (bytes <= 48 * 1024) return hipSuccess;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)bytes);
-}
-
 template <typename T, int D, int RT_T>
 hipError_t launch_stats(const Geometry& g, const ScoreArgs& a, dim3 grid, hipStream_t stream) {
   const size_t lds = (size_t)g.rows_pad * Shape<T, D>::kLdsRowBytes;
@@ -389,9 +296,7 @@ hipError_t launch_typed(const Geometry& g, const ScoreArgs& a, hipStream_t strea
   if (e != hipSuccess) return e;
   if (marks) marks->after(kKernelStats);
 
-  hipLaunchKernelGGL(score_merge_kernel, dim3((g.rows_pad + kMergeRows - 1) / kMergeRows, g.units),
-                     dim3(kBlockThreads), 0, stream, a);
-  e = hipGetLastError();
+  e = launch_score_merge(g, a, stream);
   if (e != hipSuccess) return e;
   if (marks) marks->after(kKernelMerge);
 
@@ -406,8 +311,15 @@ hipError_t launch_typed(const Geometry& g, const ScoreArgs& a, hipStream_t strea
 
 }  // namespace
 
+hipError_t launch_score_merge(const Geometry& g, const ScoreArgs& a, hipStream_t stream) {
+  hipLaunchKernelGGL(score_merge_kernel, dim3((g.rows_pad + kMergeRows - 1) / kMergeRows, g.units),
+                     dim3(kBlockThreads), 0, stream, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks) {
   if (g.units == 0 || g.nspans == 0) return hipSuccess;
+  if (score_qreg_covers(g, bf16)) return launch_score_qreg(g, a, bf16, stream, marks);
   if (bf16) {
     if (g.head_dim == 64) return launch_typed<Bf16, 64>(g, a, stream, marks);
     return launch_typed<Bf16, 128>(g, a, stream, marks);

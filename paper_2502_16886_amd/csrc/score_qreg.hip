@@ -1,0 +1,307 @@
+// Scoring kernels for up to 128 score rows per KV head (window * G <= 128: the Llama / Mistral
+// shapes with a 32-row window, and the paper's own k = 1), Sec. 3.2 "Reducing Overhead", Eq. 2.
+//
+// Same two-pass scheme as score.hip (row statistics, merge, column reduction); what differs is
+// where the operands live:
+//
+//   Q   every wavefront keeps the MFMA fragments of ALL window rows in registers for the whole
+//       kernel (4 row tiles x 8 chunks x 16 bytes per lane for bf16, d = 128).  They pass
+//       through LDS once per workgroup (coalesced global loads, padded rows) and are never
+//       touched again.
+//   K   streamed through two wavefront-private LDS buffers of one 32-key tile each by
+//       direct-to-LDS loads (global_load_lds_dwordx4): each instruction moves 1 KB of
+//       consecutive key bytes, so HBM/L2 requests are whole cache lines, and no VGPRs are held
+//       while the data is in flight.  A tile lands XOR-swizzled (16-byte slot s of row r holds
+//       chunk s ^ (r & 15)) so the MFMA-layout read-back (lane = row, 8 x ds_read_b128) is
+//       bank-conflict free.  While tile i is being multiplied, tiles i+1 and i+2 are in flight.
+//       The second buffer set reuses the LDS the Q staging occupied.
+//
+// A wavefront therefore touches LDS only for 16 KB per 8 KB key tile (DMA write + fragment
+// read); its 32 MFMAs per tile reuse the K fragments 4x and the Q fragments for ever.
+#include "kernels.h"
+#include "score_common.h"
+#include "tile_sum.h"
+
+namespace rfkv {
+namespace {
+
+// Issue the direct-to-LDS loads of the 32-key tile starting at `tile0` (keys past the end of the
+// sequence re-read the last key; their logits are masked later).
+template <typename T, int D>
+__device__ __forceinline__ void issue_tile_load(const unsigned char* kunit, int64_t tok_bytes, int tile0, int n,
+                                                unsigned char* buf, int lane) {
+  using S = Shape<T, D>;
+  constexpr int kCpr = S::kRowBytes / 16;               // 16-byte chunks per key row
+  constexpr int kSw = (kCpr < 16 ? kCpr : 16) - 1;
+  constexpr int kLoads = 32 * kCpr / 64;                // instructions per tile, 1 KB each
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    const int slot = j * 64 + lane;
+    const int r = slot / kCpr;
+    const int chunk = (slot % kCpr) ^ (r & kSw);
+    const unsigned char* src = kunit + (int64_t)min(tile0 + r, n - 1) * tok_bytes + chunk * 16;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(buf + j * 1024), 16, 0, 0);
+  }
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void read_tile_frags(uint4* kf, const unsigned char* buf, int col, int hi) {
+  using S = Shape<T, D>;
+  constexpr int kCpr = S::kRowBytes / 16;
+  constexpr int kSw = (kCpr < 16 ? kCpr : 16) - 1;
+#pragma unroll
+  for (int ch = 0; ch < S::kChunks; ++ch) {
+    const int slot = col * kCpr + ((hi * S::kChunks + ch) ^ (col & kSw));
+    kf[ch] = *reinterpret_cast<const uint4*>(buf + slot * 16);
+  }
+}
+
+// PASS 1: per-row (reference exponent, sum) partials of this workgroup's span.
+// PASS 2: scores (and per-tile squared sums) of this workgroup's span.
+template <typename T, int D, int RT_T, int PASS>
+__global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs a) {
+  using S = Shape<T, D>;
+  constexpr int kTileBytes = 32 * S::kRowBytes;
+  constexpr int kLoads = kTileBytes / 1024;            // direct-to-LDS instructions per tile
+  constexpr int kQStage = RT_T * 32 * S::kLdsRowBytes;
+  constexpr int kBytesB = 4 * kTileBytes > kQStage ? 4 * kTileBytes : kQStage;
+  // distinct LDS objects, so that reads of the row tables are known not to touch the tile buffers
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes];     // tile buffers, even tiles
+  __shared__ __attribute__((aligned(1024))) unsigned char smem_b[kBytesB];          // Q staging, then odd tiles
+  __shared__ __attribute__((aligned(16))) float bsm[RT_T * 32];      // pass 2: exponent offset per row
+  __shared__ __attribute__((aligned(16))) int rlast_s[RT_T * 32];    // pass 2: last visible key per row
+  const Unit u = load_unit(a, blockIdx.y);
+  const int span_begin = blockIdx.x * a.span;
+  if (span_begin >= u.n) return;                       // uniform for the whole workgroup
+  const int span_end = min(u.n, span_begin + a.span);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, hi = lane >> 5;
+  const float c = a.c;
+  const float kNegInf = -__builtin_inff();
+  unsigned char* kbuf0 = smem + wave * kTileBytes;     // this wavefront's two tile buffers
+  unsigned char* kbuf1 = smem_b + wave * kTileBytes;
+  const unsigned char* kunit = static_cast<const unsigned char*>(a.k) +
+                               ((int64_t)u.s0 * a.k_stride_tok + (int64_t)u.h * a.k_stride_head) * T::kBytes;
+  const int64_t tok_bytes = a.k_stride_tok * T::kBytes;
+  const int first_masked_key = u.n - u.wp + 1;         // keys below are visible to every row
+
+  // window queries (row r = t * G + g of this KV head) pass through LDS once per workgroup: issue
+  // their loads, then the first key tile's, and wait for the queries only (loads return in order)
+  constexpr int kCpr = S::kRowBytes / 16;
+  constexpr int kQPerThread = RT_T * 32 * kCpr / kBlockThreads;
+  uint4 qv[kQPerThread];
+  {
+    const unsigned char* qbase = static_cast<const unsigned char*>(a.q);
+#pragma unroll
+    for (int j = 0; j < kQPerThread; ++j) {
+      const int i = threadIdx.x + j * kBlockThreads;
+      const int r = i / kCpr;
+      const int ch = i - r * kCpr;
+      qv[j] = make_uint4(0, 0, 0, 0);
+      if (r < u.rows) {
+        const int t = r / a.group;
+        const int g = r - t * a.group;
+        const int64_t off = (int64_t)(u.q0 + t) * a.q_stride_row + (int64_t)(u.h * a.group + g) * a.q_stride_head;
+        qv[j] = *reinterpret_cast<const uint4*>(qbase + off * T::kBytes + ch * 16);
+      }
+    }
+  }
+  int tile0 = span_begin + wave * 32;
+  if (tile0 < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0, u.n, kbuf0, lane);
+#pragma unroll
+  for (int j = 0; j < kQPerThread; ++j) {
+    const int i = threadIdx.x + j * kBlockThreads;
+    const int r = i / kCpr;
+    *reinterpret_cast<uint4*>(smem_b + r * S::kLdsRowBytes + (i - r * kCpr) * 16) = qv[j];
+  }
+  __syncthreads();
+  uint4 qf[RT_T][S::kChunks];                          // fragments of all row tiles, for the whole kernel
+#pragma unroll
+  for (int rt = 0; rt < RT_T; ++rt) {
+    const unsigned char* qrow = smem_b + (rt * 32 + col) * S::kLdsRowBytes + hi * S::kHalfBytes;
+#pragma unroll
+    for (int ch = 0; ch < S::kChunks; ++ch) qf[rt][ch] = *reinterpret_cast<const uint4*>(qrow + ch * 16);
+  }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __syncthreads();                                     // the staging area becomes the second buffer set
+  if (tile0 + 4 * 32 < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + 4 * 32, u.n, kbuf1, lane);
+
+  float mc[RT_T], l[RT_T];
+  int rowlast[RT_T];
+  if (PASS == 1) {
+#pragma unroll
+    for (int rt = 0; rt < RT_T; ++rt) {
+      mc[rt] = -1e30f;
+      l[rt] = 0.f;
+      const int r = rt * 32 + col;
+      rowlast[rt] = r < u.rows ? u.n - u.wp + r / a.group : -1;
+    }
+  } else {
+    for (int r = threadIdx.x; r < RT_T * 32; r += kBlockThreads) {
+      bsm[r] = r < a.rows_pad ? a.bvec[(int64_t)blockIdx.y * a.rows_pad + r] : __builtin_inff();
+      rlast_s[r] = r < u.rows ? u.n - u.wp + r / a.group : -1;
+    }
+    __syncthreads();
+  }
+  float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
+
+  for (int it = 0; tile0 < span_end; tile0 += 4 * 32, ++it) {
+    uint4 kf[S::kChunks];
+    unsigned char* kbuf = (it & 1) ? kbuf1 : kbuf0;
+    // loads complete in issue order: once at most one tile's worth is outstanding, this tile has landed
+    if (tile0 + 4 * 32 < span_end) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    read_tile_frags<T, D>(kf, kbuf, col, hi);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // fragments are in registers: the buffer is free
+    if (tile0 + 8 * 32 < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + 8 * 32, u.n, kbuf, lane);
+    const bool masked = tile0 + 32 > first_masked_key;
+
+    if (PASS == 1) {
+#pragma unroll
+      for (int rt = 0; rt < RT_T; ++rt) {
+        if (rt < u.row_tiles) {
+          f32x16 acc;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+          for (int ch = 0; ch < S::kChunks; ++ch) acc = mma_chunk<T>(kf[ch], qf[rt][ch], acc);   // keys x rows
+          if (masked) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int key = tile0 + (i >> 2) * 8 + hi * 4 + (i & 3);
+              if (key > rowlast[rt]) acc[i] = kNegInf;
+            }
+          }
+          float tmax = kNegInf;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+          const float mnew = fmaxf(mc[rt], tmax * c);
+          float sum = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sum += fast_exp2(__builtin_fmaf(acc[i], c, -mnew));
+          l[rt] = l[rt] * fast_exp2(mc[rt] - mnew) + sum;
+          mc[rt] = mnew;
+        }
+      }
+    } else {
+      float colsum = 0.f;
+#pragma unroll
+      for (int rt = 0; rt < RT_T; ++rt) {
+        if (rt < u.row_tiles) {
+          f32x16 acc;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+          for (int ch = 0; ch < S::kChunks; ++ch) acc = mma_chunk<T>(qf[rt][ch], kf[ch], acc);   // rows x keys
+          // accumulator i of this lane: row rt*32 + (i/4)*8 + hi*4 + i%4, key tile0 + col
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int rbase = rt * 32 + j * 8 + hi * 4;
+            const float4 bv = *reinterpret_cast<const float4*>(bsm + rbase);
+            const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
+            if (!masked) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) colsum += fast_exp2(__builtin_fmaf(acc[j * 4 + e], c, -bb[e]));
+            } else {
+              const int4 rv = *reinterpret_cast<const int4*>(rlast_s + rbase);
+              const int rl[4] = {rv.x, rv.y, rv.z, rv.w};
+              const int key = tile0 + col;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float p = fast_exp2(__builtin_fmaf(acc[j * 4 + e], c, -bb[e]));
+                colsum += key <= rl[e] ? p : 0.f;
+              }
+            }
+          }
+        }
+      }
+      const float tot = colsum + __shfl_xor(colsum, 32);
+      const int key = tile0 + col;
+      const float score = key < u.n ? tot / (float)min(u.wp, u.n - key) : 0.f;
+      if (hi == 0 && key < u.n) out[key] = score;
+      const double tsq = tile_sum_sq(score, lane);
+      if (lane == 0) a.tile_sq[(int64_t)u.h * a.tiles_total + u.tile_base + (tile0 >> 5)] = tsq;
+    }
+  }
+  if (PASS == 1) {
+    // the two half-waves hold disjoint keys of the same rows; then the four wavefronts
+#pragma unroll
+    for (int rt = 0; rt < RT_T; ++rt) {
+      const float om = __shfl_xor(mc[rt], 32), ol = __shfl_xor(l[rt], 32);
+      const float nm = fmaxf(mc[rt], om);
+      l[rt] = l[rt] * fast_exp2(mc[rt] - nm) + ol * fast_exp2(om - nm);
+      mc[rt] = nm;
+    }
+    __syncthreads();                                   // every wavefront is done with its tile buffer
+    constexpr int kRows32 = RT_T * 32;
+    float2* red = reinterpret_cast<float2*>(smem);     // [4 waves][kRows32]
+    if (hi == 0) {
+#pragma unroll
+      for (int rt = 0; rt < RT_T; ++rt) red[wave * kRows32 + rt * 32 + col] = make_float2(mc[rt], l[rt]);
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < u.row_tiles * 32; r += kBlockThreads) {
+      float m = red[r].x, s = red[r].y;
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const float2 o = red[w * kRows32 + r];
+        const float nm = fmaxf(m, o.x);
+        s = s * fast_exp2(m - nm) + o.y * fast_exp2(o.x - nm);
+        m = nm;
+      }
+      a.partials[((int64_t)blockIdx.y * a.nspans + blockIdx.x) * a.rows_pad + r] = make_float2(m, s);
+    }
+  }
+}
+
+template <typename T, int D, int RT_T>
+hipError_t launch_qreg_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
+  const dim3 grid(g.nspans, g.units);
+  const size_t lds = 0;                                 // all LDS of these kernels is static
+  hipLaunchKernelGGL((score_qreg_kernel<T, D, RT_T, 1>), grid, dim3(kBlockThreads), lds, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (marks) marks->after(kKernelStats);
+  e = launch_score_merge(g, a, stream);
+  if (e != hipSuccess) return e;
+  if (marks) marks->after(kKernelMerge);
+  hipLaunchKernelGGL((score_qreg_kernel<T, D, RT_T, 2>), grid, dim3(kBlockThreads), lds, stream, a);
+  e = hipGetLastError();
+  if (marks && e == hipSuccess) marks->after(kKernelReduce);
+  return e;
+}
+
+template <typename T, int D>
+hipError_t launch_qreg_rt(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
+  const int rt = g.rows_pad / 32;
+  if (rt <= 1) return launch_qreg_typed<T, D, 1>(g, a, stream, marks);
+  if (rt <= 2) return launch_qreg_typed<T, D, 2>(g, a, stream, marks);
+  if constexpr (Shape<T, D>::kChunks * 4 <= 32) {
+    return launch_qreg_typed<T, D, 4>(g, a, stream, marks);
+  } else {
+    return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace
+
+bool score_qreg_covers(const Geometry& g, bool bf16) {
+  const int rt = g.rows_pad / 32;
+  const int chunks = g.head_dim * g.elem_bytes / 32;    // 16-byte chunks of half a row
+  (void)bf16;
+  return rt <= 4 && rt * chunks <= 32;
+}
+
+hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream,
+                             const Marks* marks) {
+  if (bf16) {
+    if (g.head_dim == 64) return launch_qreg_rt<Bf16, 64>(g, a, stream, marks);
+    return launch_qreg_rt<Bf16, 128>(g, a, stream, marks);
+  }
+  if (g.head_dim == 64) return launch_qreg_rt<Fp32, 64>(g, a, stream, marks);
+  return launch_qreg_rt<Fp32, 128>(g, a, stream, marks);
+}
+
+}  // namespace rfkv
