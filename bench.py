@@ -48,6 +48,27 @@ def kernel_bytes(name, N, Hkv, d, e, Hq, wrows, kept_rows):
     return 0
 
 
+def read_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+    (scaled by a plain copy of known size); the summary lives in profiles/.  None if there is no
+    summary for this kernel and workload."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{kernel}_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    vals = {}
+    for ln in open(path):
+        if "=" in ln and not ln.lstrip().startswith("#"):
+            k, v = ln.split("=", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except ValueError:
+                pass
+    if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
+        return {"fetch_bytes": int(vals["fetch_bytes_per_launch"]), "write_bytes": int(vals["write_bytes_per_launch"]),
+                "total_bytes": int(vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"])}
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,6 +79,13 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kv-layout", default="head_major", choices=["head_major", "token_major"],
                     help="storage of K/V: [Hkv, N, d] (the [B, H, n, d] cache of the paper's setting) or [N, Hkv, d]")
+    ap.add_argument("--modes", default="both", choices=["both", "position"],
+                    help="also time score ranking (both) or only the paper's position ranking")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 128 MiB device copy a few times (a kernel of known traffic, for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--streams", type=int, default=2,
+                    help="HIP streams the steps are spread over (layers are independent; step i runs on stream i %% S)")
     ap.add_argument("--graph", type=int, default=1, help="replay the timed steps from a HIP graph (1) or launch eagerly (0)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -95,9 +123,24 @@ def main():
     wrows = int(np.minimum(cfg.window, np.diff(host_layers[0].cu_seqlens)).sum())
     units = dls[B.RANK_POSITION][0].batch * cfg.n_kv_heads
 
+    # Layers are independent, so consecutive steps may run on different streams (all at the default
+    # priority).  Layer j always uses stream j % S, hence two uses of one layer's buffers stay ordered.
+    side = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else []
+
     def run_steps(mode, count, start=0):
+        if not side:
+            for i in range(count):
+                dls[mode][(start + i) % args.layers].compress(None)   # torch's current stream
+            return
+        cur = torch.cuda.current_stream()
+        for st in side:
+            st.wait_stream(cur)
         for i in range(count):
-            dls[mode][(start + i) % args.layers].compress(None)   # torch's current stream
+            j = (start + i) % args.layers
+            with torch.cuda.stream(side[j % args.streams]):
+                dls[mode][j].compress(None)
+        for st in side:
+            cur.wait_stream(st)
 
     def timed(mode, steps, warmup):
         run_steps(mode, warmup)
@@ -127,7 +170,8 @@ def main():
         return wall / done * 1e3, ev0.elapsed_time(ev1) / done, done
 
     results = {}
-    for mode in (B.RANK_POSITION, B.RANK_SCORE):
+    modes = (B.RANK_POSITION, B.RANK_SCORE) if args.modes == "both" else (B.RANK_POSITION,)
+    for mode in modes:
         steps = args.steps if mode == B.RANK_POSITION else max(args.layers, args.steps // 4)
         try:
             wall_ms, ev_ms, done = timed(mode, steps, args.warmup)
@@ -169,12 +213,21 @@ def main():
                 "pipeline_achieved": round(alg / (ms_per_step * 1e-3) / 1e9, 1),
                 "pipeline_frac": round(alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
-    sco = results[B.RANK_SCORE]
-    alg_s = algorithmic_bytes(*shape, sco["kept_rows"], units, True)
-    score_mode = {"value": N / (sco["wall_ms"] * 1e-3), "ms_per_step": round(sco["wall_ms"], 5),
-                  "retained_fraction": round(sco["retained"], 4),
-                  "kernel_ms": {k: round(v, 5) for k, v in sco["kernel_ms"].items()},
-                  "pipeline_frac": round(alg_s / (sco["wall_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    score_mode = None
+    if B.RANK_SCORE in results:
+        sco = results[B.RANK_SCORE]
+        alg_s = algorithmic_bytes(*shape, sco["kept_rows"], units, True)
+        score_mode = {"value": round(N / (sco["wall_ms"] * 1e-3), 1), "ms_per_step": round(sco["wall_ms"], 5),
+                      "retained_fraction": round(sco["retained"], 4),
+                      "kernel_ms": {k: round(v, 5) for k, v in sco["kernel_ms"].items()},
+                      "pipeline_frac": round(alg_s / (sco["wall_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # the same steps on one stream (no overlap between layers): per-layer latency
+    single = None
+    if args.streams > 1:
+        side.clear()
+        w1, e1, _ = timed(B.RANK_POSITION, max(args.layers, args.steps // 2), 2)
+        single = {"ms_per_step": round(w1, 5), "pipeline_frac": round(alg / (w1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -200,6 +253,14 @@ def main():
                "sample": f"1 layer of the same workload ({N} tokens, all {cfg.n_kv_heads} KV heads), float64 numpy, "
                          f"{dt:.2f} s", "kept_counts_match_gpu": agree}
 
+    if args.calibrate_copy:
+        src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    roofline["traffic"] = read_traffic(dom, cfg.name)
     line = {
         "metric": "tokens/s compressed per layer-pass at Llama3-8B shape, 32K ctx; % peak HBM BW",
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": pos["steps"], "warmup": args.warmup,
@@ -209,10 +270,10 @@ def main():
                                f"batch {dls[B.RANK_POSITION][0].batch}, {N} tokens, window {cfg.window}, T={cfg.threshold}, "
                                f"m={cfg.n_sink}, position ranking, K/V {args.kv_layout}, {args.layers} rotating layer buffers",
                    "rank_mode": "position", "retained_fraction": round(pos["retained"], 4),
-                   "launch": "hip_graph" if args.graph else "eager", "event_ms_per_step": round(pos["ev_ms"], 5),
+                   "launch": "hip_graph" if args.graph else "eager", "streams": args.streams, "event_ms_per_step": round(pos["ev_ms"], 5),
                    "input_generation_s": round(gen_s, 1)},
         "percent_peak_hbm": round(100 * roofline["pipeline_frac"], 2),
-        "roofline": roofline, "cpu_baseline": cpu, "score_ranking": score_mode,
+        "roofline": roofline, "cpu_baseline": cpu, "score_ranking": score_mode, "single_stream": single,
     }
     print(json.dumps(line))
 

@@ -71,8 +71,21 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
   __shared__ __attribute__((aligned(1024))) unsigned char smem_b[kBytesB];          // Q staging, then odd tiles
   __shared__ __attribute__((aligned(16))) float bsm[RT_T * 32];      // pass 2: exponent offset per row
   __shared__ __attribute__((aligned(16))) int rlast_s[RT_T * 32];    // pass 2: last visible key per row
-  const Unit u = load_unit(a, blockIdx.y);
-  const int span_begin = blockIdx.x * a.span;
+  // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2.
+  // The second pass walks the (span, unit) items backwards in groups of 8, keeping each item on the
+  // XCD that streamed it in the first pass: what that pass read last is still in that L2.
+  int bx = blockIdx.x, by = blockIdx.y;
+  if (PASS == 2) {
+    const int total = gridDim.x * gridDim.y;
+    if ((total & 7) == 0) {
+      const int lin = by * gridDim.x + bx;
+      const int rev = (total / 8 - 1 - lin / 8) * 8 + (lin & 7);
+      by = rev / gridDim.x;
+      bx = rev - by * gridDim.x;
+    }
+  }
+  const Unit u = load_unit(a, by);
+  const int span_begin = bx * a.span;
   if (span_begin >= u.n) return;                       // uniform for the whole workgroup
   const int span_end = min(u.n, span_begin + a.span);
 
@@ -140,7 +153,7 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
     }
   } else {
     for (int r = threadIdx.x; r < RT_T * 32; r += kBlockThreads) {
-      bsm[r] = r < a.rows_pad ? a.bvec[(int64_t)blockIdx.y * a.rows_pad + r] : __builtin_inff();
+      bsm[r] = r < a.rows_pad ? a.bvec[(int64_t)by * a.rows_pad + r] : __builtin_inff();
       rlast_s[r] = r < u.rows ? u.n - u.wp + r / a.group : -1;
     }
     __syncthreads();
@@ -158,65 +171,73 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
     if (tile0 + 8 * 32 < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + 8 * 32, u.n, kbuf, lane);
     const bool masked = tile0 + 32 > first_masked_key;
 
-    if (PASS == 1) {
+    // Logits of one row tile against this key tile.  Row tiles past the unit's rows hold zero
+    // queries: they are computed like the others and their results are never used.
+    auto logits = [&](int rt) {
+      f32x16 acc;
 #pragma unroll
-      for (int rt = 0; rt < RT_T; ++rt) {
-        if (rt < u.row_tiles) {
-          f32x16 acc;
+      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+      for (int ch = 0; ch < S::kChunks; ++ch)
+        acc = PASS == 1 ? mma_chunk<T>(kf[ch], qf[rt][ch], acc)      // keys x rows: a lane owns one row
+                        : mma_chunk<T>(qf[rt][ch], kf[ch], acc);     // rows x keys: a lane owns one key
+      return acc;
+    };
+    // The MFMA chain of row tile rt + 1 is issued before the softmax arithmetic of row tile rt, so the
+    // matrix pipe and the vector ALU of this wavefront work at the same time.
+    float colsum = 0.f;
+    f32x16 acc = logits(0);
 #pragma unroll
-          for (int ch = 0; ch < S::kChunks; ++ch) acc = mma_chunk<T>(kf[ch], qf[rt][ch], acc);   // keys x rows
-          if (masked) {
+    for (int rt = 0; rt < RT_T; ++rt) {
+      f32x16 nxt = acc;
+      if (rt + 1 < RT_T) nxt = logits(rt + 1);
+      if (PASS == 1) {
+        if (masked) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int key = tile0 + (i >> 2) * 8 + hi * 4 + (i & 3);
-              if (key > rowlast[rt]) acc[i] = kNegInf;
-            }
+          for (int i = 0; i < 16; ++i) {
+            const int key = tile0 + (i >> 2) * 8 + hi * 4 + (i & 3);
+            if (key > rowlast[rt]) acc[i] = kNegInf;
           }
-          float tmax = kNegInf;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
-          const float mnew = fmaxf(mc[rt], tmax * c);
-          float sum = 0.f;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sum += fast_exp2(__builtin_fmaf(acc[i], c, -mnew));
-          l[rt] = l[rt] * fast_exp2(mc[rt] - mnew) + sum;
-          mc[rt] = mnew;
         }
-      }
-    } else {
-      float colsum = 0.f;
+        float tmax = kNegInf;
 #pragma unroll
-      for (int rt = 0; rt < RT_T; ++rt) {
-        if (rt < u.row_tiles) {
-          f32x16 acc;
+        for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+        const float mnew = fmaxf(mc[rt], tmax * c);
+        float sum = 0.f;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        for (int i = 0; i < 16; ++i) sum += fast_exp2(__builtin_fmaf(acc[i], c, -mnew));
+        l[rt] = l[rt] * fast_exp2(mc[rt] - mnew) + sum;
+        mc[rt] = mnew;
+      } else {
+        // accumulator i of this lane: row rt*32 + (i/4)*8 + hi*4 + i%4, key tile0 + col
+        float4 bv[4];
 #pragma unroll
-          for (int ch = 0; ch < S::kChunks; ++ch) acc = mma_chunk<T>(qf[rt][ch], kf[ch], acc);   // rows x keys
-          // accumulator i of this lane: row rt*32 + (i/4)*8 + hi*4 + i%4, key tile0 + col
+        for (int j = 0; j < 4; ++j) bv[j] = *reinterpret_cast<const float4*>(bsm + rt * 32 + j * 8 + hi * 4);
+        if (!masked) {
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const int rbase = rt * 32 + j * 8 + hi * 4;
-            const float4 bv = *reinterpret_cast<const float4*>(bsm + rbase);
-            const float bb[4] = {bv.x, bv.y, bv.z, bv.w};
-            if (!masked) {
+            colsum += fast_exp2(__builtin_fmaf(acc[j * 4 + 0], c, -bv[j].x));
+            colsum += fast_exp2(__builtin_fmaf(acc[j * 4 + 1], c, -bv[j].y));
+            colsum += fast_exp2(__builtin_fmaf(acc[j * 4 + 2], c, -bv[j].z));
+            colsum += fast_exp2(__builtin_fmaf(acc[j * 4 + 3], c, -bv[j].w));
+          }
+        } else {
+          const int key = tile0 + col;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) colsum += fast_exp2(__builtin_fmaf(acc[j * 4 + e], c, -bb[e]));
-            } else {
-              const int4 rv = *reinterpret_cast<const int4*>(rlast_s + rbase);
-              const int rl[4] = {rv.x, rv.y, rv.z, rv.w};
-              const int key = tile0 + col;
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const float p = fast_exp2(__builtin_fmaf(acc[j * 4 + e], c, -bb[e]));
-                colsum += key <= rl[e] ? p : 0.f;
-              }
-            }
+          for (int j = 0; j < 4; ++j) {
+            const int4 rv = *reinterpret_cast<const int4*>(rlast_s + rt * 32 + j * 8 + hi * 4);
+            const float p0 = fast_exp2(__builtin_fmaf(acc[j * 4 + 0], c, -bv[j].x));
+            const float p1 = fast_exp2(__builtin_fmaf(acc[j * 4 + 1], c, -bv[j].y));
+            const float p2 = fast_exp2(__builtin_fmaf(acc[j * 4 + 2], c, -bv[j].z));
+            const float p3 = fast_exp2(__builtin_fmaf(acc[j * 4 + 3], c, -bv[j].w));
+            colsum += (key <= rv.x ? p0 : 0.f) + (key <= rv.y ? p1 : 0.f) + (key <= rv.z ? p2 : 0.f) +
+                      (key <= rv.w ? p3 : 0.f);
           }
         }
       }
+      acc = nxt;
+    }
+    if (PASS == 2) {
       const float tot = colsum + __shfl_xor(colsum, 32);
       const int key = tile0 + col;
       const float score = key < u.n ? tot / (float)min(u.wp, u.n - key) : 0.f;
@@ -251,7 +272,7 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
         s = s * fast_exp2(m - nm) + o.y * fast_exp2(o.x - nm);
         m = nm;
       }
-      a.partials[((int64_t)blockIdx.y * a.nspans + blockIdx.x) * a.rows_pad + r] = make_float2(m, s);
+      a.partials[((int64_t)by * a.nspans + bx) * a.rows_pad + r] = make_float2(m, s);
     }
   }
 }
