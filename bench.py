@@ -8,7 +8,8 @@ d = 128, bf16), one 32768-token sequence, observation window 32, T = 1 %, m = 4,
 its inputs in the 256 MB Infinity Cache left there by the previous one.  Inputs are synthetic
 (paper_2502_16886_amd.workloads) and resident in HBM before timing starts.
 
-Prints one JSON line (see the design doc for the fields).
+Prints one JSON line: throughput, the dominant kernel's roofline figures, the CPU oracle timed
+on the same workload, and the score-ranking and single-stream variants.
 """
 from __future__ import annotations
 
@@ -89,8 +90,8 @@ def main():
     ap.add_argument("--graph", type=int, default=1, help="replay the timed steps from a HIP graph (1) or launch eagerly (0)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build is single-GPU by design (units are independent; see DESIGN.md); "
-              "run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU (the units of a layer are independent and would shard by "
+              "KV head, sequence or layer without communication); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np

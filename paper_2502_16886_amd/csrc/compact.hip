@@ -25,7 +25,7 @@ namespace {
 #endif
 constexpr int kRowsPerBlock = RFKV_COMPACT_ROWS;
 constexpr int kUnroll = RFKV_COMPACT_UNROLL;
-constexpr int kUniformPrefixUnits = 256;   // up to here every thread sums the earlier kept counts itself
+constexpr int kUniformPrefixUnits = 16;    // up to here every thread sums the earlier kept counts itself
 
 __device__ __forceinline__ int64_t block_sum_i64(int64_t v, int64_t* sh /*[4]*/) {
 #pragma unroll

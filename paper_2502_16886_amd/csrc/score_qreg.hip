@@ -59,16 +59,21 @@ __device__ __forceinline__ void read_tile_frags(uint4* kf, const unsigned char* 
 
 // PASS 1: per-row (reference exponent, sum) partials of this workgroup's span.
 // PASS 2: scores (and per-tile squared sums) of this workgroup's span.
-template <typename T, int D, int RT_T, int PASS>
-__global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs a) {
+// QREG:   window-query fragments in registers (4 wavefronts, two tile buffers each, the second
+//         set reusing the query staging area) or, for more than 4 row tiles, read from LDS at every
+//         use (8 wavefronts, one tile buffer each).
+template <typename T, int D, int RT_T, int PASS, bool QREG>
+__global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_kernel(ScoreArgs a) {
   using S = Shape<T, D>;
+  constexpr int kWaves = QREG ? 4 : 8;
+  constexpr int kThreads = kWaves * 64;
   constexpr int kTileBytes = 32 * S::kRowBytes;
   constexpr int kLoads = kTileBytes / 1024;            // direct-to-LDS instructions per tile
   constexpr int kQStage = RT_T * 32 * S::kLdsRowBytes;
-  constexpr int kBytesB = 4 * kTileBytes > kQStage ? 4 * kTileBytes : kQStage;
-  // distinct LDS objects, so that reads of the row tables are known not to touch the tile buffers
-  __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * kTileBytes];     // tile buffers, even tiles
-  __shared__ __attribute__((aligned(1024))) unsigned char smem_b[kBytesB];          // Q staging, then odd tiles
+  constexpr int kBytesB = (!QREG || kWaves * kTileBytes < kQStage) ? kQStage : kWaves * kTileBytes;
+  // distinct LDS objects, so that reads of the tables are known not to touch the tile buffers
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * kTileBytes];   // tile buffers
+  __shared__ __attribute__((aligned(1024))) unsigned char smem_b[kBytesB];   // queries (QREG: then odd tiles)
   __shared__ __attribute__((aligned(16))) float bsm[RT_T * 32];      // pass 2: exponent offset per row
   __shared__ __attribute__((aligned(16))) int rlast_s[RT_T * 32];    // pass 2: last visible key per row
   // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2.
@@ -93,23 +98,25 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
   const int col = lane & 31, hi = lane >> 5;
   const float c = a.c;
   const float kNegInf = -__builtin_inff();
-  unsigned char* kbuf0 = smem + wave * kTileBytes;     // this wavefront's two tile buffers
-  unsigned char* kbuf1 = smem_b + wave * kTileBytes;
+  unsigned char* kbuf0 = smem + wave * kTileBytes;     // this wavefront's tile buffer(s)
+  unsigned char* kbuf1 = QREG ? smem_b + wave * kTileBytes : kbuf0;
   const unsigned char* kunit = static_cast<const unsigned char*>(a.k) +
                                ((int64_t)u.s0 * a.k_stride_tok + (int64_t)u.h * a.k_stride_head) * T::kBytes;
   const int64_t tok_bytes = a.k_stride_tok * T::kBytes;
   const int first_masked_key = u.n - u.wp + 1;         // keys below are visible to every row
+  constexpr int kStep = kWaves * 32;                   // keys the workgroup consumes per iteration
 
   // window queries (row r = t * G + g of this KV head) pass through LDS once per workgroup: issue
   // their loads, then the first key tile's, and wait for the queries only (loads return in order)
   constexpr int kCpr = S::kRowBytes / 16;
-  constexpr int kQPerThread = RT_T * 32 * kCpr / kBlockThreads;
+  constexpr int kQPerThread = RT_T * 32 * kCpr / kThreads;
+  static_assert(kQPerThread * kThreads == RT_T * 32 * kCpr, "query staging must divide evenly");
   uint4 qv[kQPerThread];
   {
     const unsigned char* qbase = static_cast<const unsigned char*>(a.q);
 #pragma unroll
     for (int j = 0; j < kQPerThread; ++j) {
-      const int i = threadIdx.x + j * kBlockThreads;
+      const int i = threadIdx.x + j * kThreads;
       const int r = i / kCpr;
       const int ch = i - r * kCpr;
       qv[j] = make_uint4(0, 0, 0, 0);
@@ -125,21 +132,24 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
   if (tile0 < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0, u.n, kbuf0, lane);
 #pragma unroll
   for (int j = 0; j < kQPerThread; ++j) {
-    const int i = threadIdx.x + j * kBlockThreads;
+    const int i = threadIdx.x + j * kThreads;
     const int r = i / kCpr;
     *reinterpret_cast<uint4*>(smem_b + r * S::kLdsRowBytes + (i - r * kCpr) * 16) = qv[j];
   }
   __syncthreads();
-  uint4 qf[RT_T][S::kChunks];                          // fragments of all row tiles, for the whole kernel
+  constexpr int kQRegTiles = QREG ? RT_T : 1;
+  uint4 qf[kQRegTiles][S::kChunks];                    // QREG: fragments of all row tiles, for the whole kernel
+  if (QREG) {
 #pragma unroll
-  for (int rt = 0; rt < RT_T; ++rt) {
-    const unsigned char* qrow = smem_b + (rt * 32 + col) * S::kLdsRowBytes + hi * S::kHalfBytes;
+    for (int rt = 0; rt < kQRegTiles; ++rt) {
+      const unsigned char* qrow = smem_b + (rt * 32 + col) * S::kLdsRowBytes + hi * S::kHalfBytes;
 #pragma unroll
-    for (int ch = 0; ch < S::kChunks; ++ch) qf[rt][ch] = *reinterpret_cast<const uint4*>(qrow + ch * 16);
+      for (int ch = 0; ch < S::kChunks; ++ch) qf[rt][ch] = *reinterpret_cast<const uint4*>(qrow + ch * 16);
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();                                   // the staging area becomes the second buffer set
+    if (tile0 + kStep < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + kStep, u.n, kbuf1, lane);
   }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __syncthreads();                                     // the staging area becomes the second buffer set
-  if (tile0 + 4 * 32 < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + 4 * 32, u.n, kbuf1, lane);
 
   float mc[RT_T], l[RT_T];
   int rowlast[RT_T];
@@ -152,7 +162,7 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
       rowlast[rt] = r < u.rows ? u.n - u.wp + r / a.group : -1;
     }
   } else {
-    for (int r = threadIdx.x; r < RT_T * 32; r += kBlockThreads) {
+    for (int r = threadIdx.x; r < RT_T * 32; r += kThreads) {
       bsm[r] = r < a.rows_pad ? a.bvec[(int64_t)by * a.rows_pad + r] : __builtin_inff();
       rlast_s[r] = r < u.rows ? u.n - u.wp + r / a.group : -1;
     }
@@ -160,15 +170,16 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
   }
   float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
 
-  for (int it = 0; tile0 < span_end; tile0 += 4 * 32, ++it) {
+  for (int it = 0; tile0 < span_end; tile0 += kStep, ++it) {
     uint4 kf[S::kChunks];
-    unsigned char* kbuf = (it & 1) ? kbuf1 : kbuf0;
+    unsigned char* kbuf = (QREG && (it & 1)) ? kbuf1 : kbuf0;
     // loads complete in issue order: once at most one tile's worth is outstanding, this tile has landed
-    if (tile0 + 4 * 32 < span_end) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads) : "memory");
+    if (QREG && tile0 + kStep < span_end) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads) : "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     read_tile_frags<T, D>(kf, kbuf, col, hi);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // fragments are in registers: the buffer is free
-    if (tile0 + 8 * 32 < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + 8 * 32, u.n, kbuf, lane);
+    constexpr int kAhead = QREG ? 2 * kStep : kStep;
+    if (tile0 + kAhead < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + kAhead, u.n, kbuf, lane);
     const bool masked = tile0 + 32 > first_masked_key;
 
     // Logits of one row tile against this key tile.  Row tiles past the unit's rows hold zero
@@ -178,9 +189,13 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
-      for (int ch = 0; ch < S::kChunks; ++ch)
-        acc = PASS == 1 ? mma_chunk<T>(kf[ch], qf[rt][ch], acc)      // keys x rows: a lane owns one row
-                        : mma_chunk<T>(qf[rt][ch], kf[ch], acc);     // rows x keys: a lane owns one key
+      for (int ch = 0; ch < S::kChunks; ++ch) {
+        const uint4 q = QREG ? qf[QREG ? rt : 0][ch]
+                             : *reinterpret_cast<const uint4*>(smem_b + (rt * 32 + col) * S::kLdsRowBytes +
+                                                               hi * S::kHalfBytes + ch * 16);
+        acc = PASS == 1 ? mma_chunk<T>(kf[ch], q, acc)      // keys x rows: a lane owns one row
+                        : mma_chunk<T>(q, kf[ch], acc);     // rows x keys: a lane owns one key
+      }
       return acc;
     };
     // The MFMA chain of row tile rt + 1 is issued before the softmax arithmetic of row tile rt, so the
@@ -257,16 +272,16 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
     }
     __syncthreads();                                   // every wavefront is done with its tile buffer
     constexpr int kRows32 = RT_T * 32;
-    float2* red = reinterpret_cast<float2*>(smem);     // [4 waves][kRows32]
+    float2* red = reinterpret_cast<float2*>(smem);     // [kWaves][kRows32]
     if (hi == 0) {
 #pragma unroll
       for (int rt = 0; rt < RT_T; ++rt) red[wave * kRows32 + rt * 32 + col] = make_float2(mc[rt], l[rt]);
     }
     __syncthreads();
-    for (int r = threadIdx.x; r < u.row_tiles * 32; r += kBlockThreads) {
+    for (int r = threadIdx.x; r < u.row_tiles * 32; r += kThreads) {
       float m = red[r].x, s = red[r].y;
 #pragma unroll
-      for (int w = 1; w < 4; ++w) {
+      for (int w = 1; w < kWaves; ++w) {
         const float2 o = red[w * kRows32 + r];
         const float nm = fmaxf(m, o.x);
         s = s * fast_exp2(m - nm) + o.y * fast_exp2(o.x - nm);
@@ -277,33 +292,41 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_qreg_kernel(ScoreArgs 
   }
 }
 
-template <typename T, int D, int RT_T>
-hipError_t launch_qreg_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
+template <typename T, int D, int RT_T, bool QREG>
+hipError_t launch_stream_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const dim3 grid(g.nspans, g.units);
-  const size_t lds = 0;                                 // all LDS of these kernels is static
-  hipLaunchKernelGGL((score_qreg_kernel<T, D, RT_T, 1>), grid, dim3(kBlockThreads), lds, stream, a);
+  const dim3 block(QREG ? 256 : 512);
+  hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 1, QREG>), grid, block, 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (marks) marks->after(kKernelStats);
   e = launch_score_merge(g, a, stream);
   if (e != hipSuccess) return e;
   if (marks) marks->after(kKernelMerge);
-  hipLaunchKernelGGL((score_qreg_kernel<T, D, RT_T, 2>), grid, dim3(kBlockThreads), lds, stream, a);
+  hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 2, QREG>), grid, block, 0, stream, a);
   e = hipGetLastError();
   if (marks && e == hipSuccess) marks->after(kKernelReduce);
   return e;
 }
 
+// Static LDS of the LDS-resident-query variant with 8 row tiles: queries + 8 tile buffers.
 template <typename T, int D>
-hipError_t launch_qreg_rt(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
+constexpr bool qlds8_fits() {
+  return 8 * 32 * Shape<T, D>::kLdsRowBytes + 8 * 32 * Shape<T, D>::kRowBytes + 4096 <= 64 * 1024 * 2 + 28 * 1024;
+}
+
+template <typename T, int D>
+hipError_t launch_stream_rt(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const int rt = g.rows_pad / 32;
-  if (rt <= 1) return launch_qreg_typed<T, D, 1>(g, a, stream, marks);
-  if (rt <= 2) return launch_qreg_typed<T, D, 2>(g, a, stream, marks);
+  if (rt <= 1) return launch_stream_typed<T, D, 1, true>(g, a, stream, marks);
+  if (rt <= 2) return launch_stream_typed<T, D, 2, true>(g, a, stream, marks);
   if constexpr (Shape<T, D>::kChunks * 4 <= 32) {
-    return launch_qreg_typed<T, D, 4>(g, a, stream, marks);
-  } else {
-    return hipErrorInvalidValue;
+    if (rt <= 4) return launch_stream_typed<T, D, 4, true>(g, a, stream, marks);
   }
+  if constexpr (qlds8_fits<T, D>()) {
+    if (rt <= 8) return launch_stream_typed<T, D, 8, false>(g, a, stream, marks);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace
@@ -312,17 +335,19 @@ bool score_qreg_covers(const Geometry& g, bool bf16) {
   const int rt = g.rows_pad / 32;
   const int chunks = g.head_dim * g.elem_bytes / 32;    // 16-byte chunks of half a row
   (void)bf16;
-  return rt <= 4 && rt * chunks <= 32;
+  if (rt <= 2) return true;
+  if (rt <= 4 && chunks * 4 <= 32) return true;
+  return rt <= 8 && chunks <= 8;                        // LDS-resident queries: 256-byte rows only
 }
 
 hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream,
                              const Marks* marks) {
   if (bf16) {
-    if (g.head_dim == 64) return launch_qreg_rt<Bf16, 64>(g, a, stream, marks);
-    return launch_qreg_rt<Bf16, 128>(g, a, stream, marks);
+    if (g.head_dim == 64) return launch_stream_rt<Bf16, 64>(g, a, stream, marks);
+    return launch_stream_rt<Bf16, 128>(g, a, stream, marks);
   }
-  if (g.head_dim == 64) return launch_qreg_rt<Fp32, 64>(g, a, stream, marks);
-  return launch_qreg_rt<Fp32, 128>(g, a, stream, marks);
+  if (g.head_dim == 64) return launch_stream_rt<Fp32, 64>(g, a, stream, marks);
+  return launch_stream_rt<Fp32, 128>(g, a, stream, marks);
 }
 
 }  // namespace rfkv
