@@ -23,7 +23,7 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = False, extra_flags=(), out_path: str | None = None) -> str:
+def build(verbose: bool = False, extra_flags=(), out_path: str | None = None, csrc_dir: str | None = None) -> str:
     """Compile every source for gfx950 and link the shared library.  Always recompiles.
     `extra_flags` / `out_path` build a tuning variant (e.g. -DRFKV_COMPACT_ROWS=32) elsewhere."""
     objdir = os.path.join(PKG_DIR, "_build") if out_path is None else out_path + ".obj"
@@ -31,7 +31,7 @@ def build(verbose: bool = False, extra_flags=(), out_path: str | None = None) ->
     procs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc(), *HIP_FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc(), *HIP_FLAGS, *extra_flags, "-c", os.path.join(csrc_dir or CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

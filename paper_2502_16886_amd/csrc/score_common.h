@@ -115,6 +115,38 @@ __device__ __forceinline__ void stage_q(const ScoreArgs& a, const Unit& u, unsig
   }
 }
 
+// Issue the direct-to-LDS loads of the 32-key tile starting at `tile0` (keys past the end of the
+// sequence re-read the last key; their logits are masked later).
+template <typename T, int D>
+__device__ __forceinline__ void issue_tile_load(const unsigned char* kunit, int64_t tok_bytes, int tile0, int n,
+                                                unsigned char* buf, int lane) {
+  using S = Shape<T, D>;
+  constexpr int kCpr = S::kRowBytes / 16;               // 16-byte chunks per key row
+  constexpr int kSw = (kCpr < 16 ? kCpr : 16) - 1;
+  constexpr int kLoads = 32 * kCpr / 64;                // instructions per tile, 1 KB each
+#pragma unroll
+  for (int j = 0; j < kLoads; ++j) {
+    const int slot = j * 64 + lane;
+    const int r = slot / kCpr;
+    const int chunk = (slot % kCpr) ^ (r & kSw);
+    const unsigned char* src = kunit + (int64_t)min(tile0 + r, n - 1) * tok_bytes + chunk * 16;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(buf + j * 1024), 16, 0, 0);
+  }
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void read_tile_frags(uint4* kf, const unsigned char* buf, int col, int hi) {
+  using S = Shape<T, D>;
+  constexpr int kCpr = S::kRowBytes / 16;
+  constexpr int kSw = (kCpr < 16 ? kCpr : 16) - 1;
+#pragma unroll
+  for (int ch = 0; ch < S::kChunks; ++ch) {
+    const int slot = col * kCpr + ((hi * S::kChunks + ch) ^ (col & kSw));
+    kf[ch] = *reinterpret_cast<const uint4*>(buf + slot * 16);
+  }
+}
+
 }  // namespace
 
 // defined in score.hip
@@ -122,5 +154,4 @@ hipError_t launch_score_merge(const Geometry& g, const ScoreArgs& a, hipStream_t
 // defined in score_qreg.hip: the register-resident-Q kernels and the shapes they cover
 bool score_qreg_covers(const Geometry& g, bool bf16);
 hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks);
-
 }  // namespace rfkv

@@ -25,38 +25,6 @@
 namespace rfkv {
 namespace {
 
-// Issue the direct-to-LDS loads of the 32-key tile starting at `tile0` (keys past the end of the
-// sequence re-read the last key; their logits are masked later).
-template <typename T, int D>
-__device__ __forceinline__ void issue_tile_load(const unsigned char* kunit, int64_t tok_bytes, int tile0, int n,
-                                                unsigned char* buf, int lane) {
-  using S = Shape<T, D>;
-  constexpr int kCpr = S::kRowBytes / 16;               // 16-byte chunks per key row
-  constexpr int kSw = (kCpr < 16 ? kCpr : 16) - 1;
-  constexpr int kLoads = 32 * kCpr / 64;                // instructions per tile, 1 KB each
-#pragma unroll
-  for (int j = 0; j < kLoads; ++j) {
-    const int slot = j * 64 + lane;
-    const int r = slot / kCpr;
-    const int chunk = (slot % kCpr) ^ (r & kSw);
-    const unsigned char* src = kunit + (int64_t)min(tile0 + r, n - 1) * tok_bytes + chunk * 16;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)(buf + j * 1024), 16, 0, 0);
-  }
-}
-
-template <typename T, int D>
-__device__ __forceinline__ void read_tile_frags(uint4* kf, const unsigned char* buf, int col, int hi) {
-  using S = Shape<T, D>;
-  constexpr int kCpr = S::kRowBytes / 16;
-  constexpr int kSw = (kCpr < 16 ? kCpr : 16) - 1;
-#pragma unroll
-  for (int ch = 0; ch < S::kChunks; ++ch) {
-    const int slot = col * kCpr + ((hi * S::kChunks + ch) ^ (col & kSw));
-    kf[ch] = *reinterpret_cast<const uint4*>(buf + slot * 16);
-  }
-}
-
 // PASS 1: per-row (reference exponent, sum) partials of this workgroup's span.
 // PASS 2: scores (and per-tile squared sums) of this workgroup's span.
 // QREG:   window-query fragments in registers (4 wavefronts, two tile buffers each, the second
@@ -76,19 +44,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   __shared__ __attribute__((aligned(1024))) unsigned char smem_b[kBytesB];   // queries (QREG: then odd tiles)
   __shared__ __attribute__((aligned(16))) float bsm[RT_T * 32];      // pass 2: exponent offset per row
   __shared__ __attribute__((aligned(16))) int rlast_s[RT_T * 32];    // pass 2: last visible key per row
-  // Workgroups are handed to the 8 XCDs round-robin in launch order, and each XCD has its own L2.
-  // The second pass walks the (span, unit) items backwards in groups of 8, keeping each item on the
-  // XCD that streamed it in the first pass: what that pass read last is still in that L2.
-  int bx = blockIdx.x, by = blockIdx.y;
-  if (PASS == 2) {
-    const int total = gridDim.x * gridDim.y;
-    if ((total & 7) == 0) {
-      const int lin = by * gridDim.x + bx;
-      const int rev = (total / 8 - 1 - lin / 8) * 8 + (lin & 7);
-      by = rev / gridDim.x;
-      bx = rev - by * gridDim.x;
-    }
-  }
+  const int bx = blockIdx.x, by = blockIdx.y;
   const Unit u = load_unit(a, by);
   const int span_begin = bx * a.span;
   if (span_begin >= u.n) return;                       // uniform for the whole workgroup
