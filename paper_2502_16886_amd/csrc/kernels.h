@@ -64,6 +64,7 @@ struct SelectArgs {
   int32_t from_scores;    // the tile sums are not there yet: form them from the scores first
   int32_t n_kv_heads, n_sink, min_keep, rank_mode;
   float threshold;
+  int32_t lds_floats;     // set by launch_select: floats of dynamic LDS the select kernel may use
 };
 
 enum CompactSource { kSrcPositionDesc = 0, kSrcPaddedIdx = 1, kSrcPackedIdx = 2 };

@@ -24,6 +24,7 @@ namespace {
 constexpr int kT = kSelectThreads;
 constexpr int kWaves = kT / 64;
 constexpr int kBuckets = 2048;
+constexpr int kMaxLdsFloats = 32768 + 4;           // scores of one unit held in LDS by the score ranking
 
 struct Pred {
   double total;     // P_n as a double
@@ -56,26 +57,33 @@ __device__ __forceinline__ V wave_inclusive_scan(V v, int lane) {
   return v;
 }
 
-// Exclusive scan over the 1024 threads (thread order); returns the exclusive prefix and the total.
-template <typename V>
-__device__ __forceinline__ V block_exclusive_scan(V v, V* wave_tot /*[kWaves+1] LDS*/, V* total) {
+// Exclusive scan of two values over the 1024 threads (thread order) behind one pair of barriers;
+// x and y become the exclusive prefixes, *tot_x and *tot_y the totals.
+__device__ __forceinline__ void block_exclusive_scan2(uint64_t& x, uint64_t& y, uint64_t (*wave_tot)[2] /*[kWaves] LDS*/,
+                                                      uint64_t* tot_x, uint64_t* tot_y) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const V inc = wave_inclusive_scan(v, lane);
+  const uint64_t ix = wave_inclusive_scan(x, lane), iy = wave_inclusive_scan(y, lane);
   __syncthreads();
-  if (lane == 63) wave_tot[wave] = inc;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    V run = 0;
-    for (int w = 0; w < kWaves; ++w) {
-      const V t = wave_tot[w];
-      wave_tot[w] = run;
-      run += t;
-    }
-    wave_tot[kWaves] = run;
+  if (lane == 63) {
+    wave_tot[wave][0] = ix;
+    wave_tot[wave][1] = iy;
   }
   __syncthreads();
-  *total = wave_tot[kWaves];
-  return wave_tot[wave] + inc - v;
+  uint64_t ox = 0, oy = 0, tx = 0, ty = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const uint64_t wx = wave_tot[w][0], wy = wave_tot[w][1];
+    if (w < wave) {
+      ox += wx;
+      oy += wy;
+    }
+    tx += wx;
+    ty += wy;
+  }
+  x = ox + ix - x;
+  y = oy + iy - y;
+  *tot_x = tx;
+  *tot_y = ty;
 }
 
 __device__ __forceinline__ double block_sum_double(double v, double* wave_tot) {
@@ -88,6 +96,20 @@ __device__ __forceinline__ double block_sum_double(double v, double* wave_tot) {
   double t = 0.0;
   for (int w = 0; w < kWaves; ++w) t += wave_tot[w];      // same order in every thread
   return t;
+}
+
+// Four consecutive scores from one 16-byte load.  `al` is the unit's score pointer moved back to
+// a 16-byte boundary (by `mis` floats), q the first of the four as an index from `al`; the
+// unit's scores are al[mis .. span).  A vector that is not wholly inside falls back to guarded
+// scalar loads (never touching memory outside the unit); entries outside read as 0.
+__device__ __forceinline__ float4 load_scores4(const float* al, int q, int mis, int span) {
+  if (q >= mis && q + 4 <= span) return *reinterpret_cast<const float4*>(al + q);
+  float4 v;
+  v.x = (q + 0 >= mis && q + 0 < span) ? al[q + 0] : 0.f;
+  v.y = (q + 1 >= mis && q + 1 < span) ? al[q + 1] : 0.f;
+  v.z = (q + 2 >= mis && q + 2 < span) ? al[q + 2] : 0.f;
+  v.w = (q + 3 >= mis && q + 3 < span) ? al[q + 3] : 0.f;
+  return v;
 }
 
 // Per-tile squared-score sums straight from a score array (used when scoring did not run in
@@ -134,12 +156,226 @@ struct PredF {
   }
 };
 
+struct SelectShared {
+  uint64_t (*scan)[2];    // [kWaves][2]
+  uint32_t* cnt;          // [kBuckets]
+  uint64_t* mass;         // [kBuckets]
+  int* i;                 // [8]
+  uint64_t* u64;          // [2]
+};
+
+// Score ranking of one unit by the whole workgroup; returns the kept count and writes the retained
+// positions (ascending) to idx_pad.  Positions are dealt out in 256-position chunks (one aligned
+// 4-vector per lane), each wavefront owning a contiguous run of chunks.  A unit that fits the
+// `lds_floats` floats at `lds` is copied there once and every pass reads it from LDS; a longer
+// one is read from memory again in every pass.
+__device__ __forceinline__ int score_rank(const float* s, int n, double inv, float threshold, int min_keep,
+                                          int32_t* idx_pad, float* lds, int lds_floats, const SelectShared& sh) {
+  constexpr int kChunkBatch = 4;                   // loads in flight per lane
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int mis = (int)((reinterpret_cast<uintptr_t>(s) >> 2) & 3);
+  const float* al = s - mis;
+  const int span = n + mis;
+  const int nchunks = (span + 255) / 256;
+  const int cpw = (nchunks + kWaves - 1) / kWaves;
+  const int c0 = min(nchunks, wave * cpw), c1 = min(nchunks, c0 + cpw);
+  const bool resident = span <= lds_floats;        // uniform over the workgroup
+
+  if (resident) {
+    constexpr int kFill = 8;
+    for (int base = 0; base < span; base += kT * 4 * kFill) {
+      float4 v[kFill];
+#pragma unroll
+      for (int j = 0; j < kFill; ++j) {
+        const int q = base + (j * kT + tid) * 4;
+        v[j] = q < span ? load_scores4(al, q, mis, span) : make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int j = 0; j < kFill; ++j) {
+        const int q = base + (j * kT + tid) * 4;
+        if (q < span) *reinterpret_cast<float4*>(lds + q) = v[j];
+      }
+    }
+    __syncthreads();
+  }
+  auto load_chunk = [&](int c) -> float4 {
+    const int q = c * 256 + lane * 4;
+    if (c >= c1 || q >= span) return make_float4(0.f, 0.f, 0.f, 0.f);
+    return resident ? *reinterpret_cast<const float4*>(lds + q) : load_scores4(al, q, mis, span);
+  };
+  // f(c, v): once per chunk c of this wavefront's run with the lane's vector v (uniform per wavefront)
+  auto for_each_chunk = [&](auto f) {
+    for (int c = c0; c < c1; c += kChunkBatch) {
+      float4 v[kChunkBatch];
+#pragma unroll
+      for (int j = 0; j < kChunkBatch; ++j) v[j] = load_chunk(c + j);
+#pragma unroll
+      for (int j = 0; j < kChunkBatch; ++j)
+        if (c + j < c1) f(c + j, v[j]);
+    }
+  };
+
+  Pred pred{0.0, (double)threshold, min_keep};
+  uint32_t prefix = 0;                             // decided high bits of the cut key
+  int64_t cnt_above = 0;
+  uint64_t mass_above = 0;
+  const int shifts[3] = {21, 10, 0};
+  const int widths[3] = {11, 11, 10};
+  int done_bits = 0;
+  uint32_t cut_cnt = 0;
+  uint64_t cut_mass = 0;
+  for (int pass = 0; pass < 3; ++pass) {
+    const int shift = shifts[pass], width = widths[pass];
+    const int nb = 1 << width;
+    for (int d = tid; d < kBuckets; d += kT) {
+      sh.cnt[d] = 0;
+      sh.mass[d] = 0;
+    }
+    if (tid == 0) sh.i[1] = 0;
+    __syncthreads();
+    for_each_chunk([&](int c, const float4& v) {
+      const float f[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int i = c * 256 + lane * 4 + e - mis;
+        const uint32_t key = order_key(f[e]);
+        if (i >= 0 && i < n && (done_bits == 0 || (key >> (32 - done_bits)) == prefix)) {
+          const uint32_t d = (key >> shift) & (nb - 1);
+          atomicAdd(&sh.cnt[d], 1u);
+          atomicAdd(reinterpret_cast<unsigned long long*>(&sh.mass[d]), (unsigned long long)quantise(f[e], inv));
+        }
+      }
+    });
+    __syncthreads();
+    // suffix sums over buckets in descending digit order: thread t owns digits nb-1-2t, nb-2-2t
+    const int d_hi = nb - 1 - 2 * tid, d_lo = d_hi - 1;
+    const uint32_t c_hi = d_hi >= 0 ? sh.cnt[d_hi] : 0, c_lo = d_lo >= 0 ? sh.cnt[d_lo] : 0;
+    const uint64_t m_hi = d_hi >= 0 ? sh.mass[d_hi] : 0, m_lo = d_lo >= 0 ? sh.mass[d_lo] : 0;
+    uint64_t tot_c, tot_m, ex_c = (uint64_t)c_hi + c_lo, ex_m = m_hi + m_lo;
+    block_exclusive_scan2(ex_c, ex_m, sh.scan, &tot_c, &tot_m);
+    if (pass == 0) {
+      // the first histogram holds every position: its mass is P_n exactly
+      pred.total = (double)tot_m;
+      if (!pred(n, tot_m)) {                       // min_keep >= n (or no mass): keep everything
+        if (idx_pad)
+          for (int i = tid; i < n; i += kT) idx_pad[i] = i;
+        return n;
+      }
+    }
+    // crossing bucket: predicate false before it, true once it is included
+    if (d_hi >= 0) {
+      const int64_t n0 = cnt_above + (int64_t)ex_c;
+      const uint64_t m0 = mass_above + ex_m;
+      const bool p0 = pred(n0, m0);
+      const bool p1 = pred(n0 + c_hi, m0 + m_hi);
+      if (!p0 && p1 && c_hi > 0) {
+        sh.i[1] = d_hi;
+        sh.u64[0] = (uint64_t)n0;
+        sh.u64[1] = m0;
+      } else if (d_lo >= 0 && !p1) {
+        const bool p2 = pred(n0 + c_hi + c_lo, m0 + m_hi + m_lo);
+        if (p2 && c_lo > 0) {
+          sh.i[1] = d_lo;
+          sh.u64[0] = (uint64_t)(n0 + c_hi);
+          sh.u64[1] = m0 + m_hi;
+        }
+      }
+    }
+    __syncthreads();
+    const int d_cut = sh.i[1];
+    cnt_above = (int64_t)sh.u64[0];
+    mass_above = sh.u64[1];
+    cut_cnt = sh.cnt[d_cut];
+    cut_mass = sh.mass[d_cut];
+    prefix = (prefix << width) | (uint32_t)d_cut;
+    done_bits += width;
+    __syncthreads();
+  }
+  // all cut_cnt elements of the final bucket share one value: take the fewest that cross
+  const uint64_t q_each = cut_mass / (cut_cnt ? cut_cnt : 1u);
+  if (tid == 0) {
+    int lo = 1, hi = (int)cut_cnt;                 // pred is true at hi
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (pred(cnt_above + mid, mass_above + (uint64_t)mid * q_each)) hi = mid;
+      else lo = mid + 1;
+    }
+    sh.i[2] = lo;
+  }
+  __syncthreads();
+  const uint32_t ties = (uint32_t)sh.i[2];
+  const int kept = (int)cnt_above + (int)ties;
+  if (!idx_pad) return kept;
+
+  // Emit the retained positions in ascending order: every wavefront counts what its run of chunks
+  // retains, the counts of the wavefronts before it give its starting offset, then it writes
+  // chunk by chunk with a prefix over lanes.  Of the positions tying the cut score the lowest
+  // `ties` are kept.  Bit e of gt / eq: the lane's e-th position is above / at the cut key.
+  auto classify = [&](int c, const float4& v, uint32_t& gt, uint32_t& eq) {
+    const float f[4] = {v.x, v.y, v.z, v.w};
+    gt = eq = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int i = c * 256 + lane * 4 + e - mis;
+      const bool valid = i >= 0 && i < n;
+      const uint32_t key = order_key(f[e]);
+      gt |= (uint32_t)(valid && key > prefix) << e;
+      eq |= (uint32_t)(valid && key == prefix) << e;
+    }
+  };
+  uint32_t n_gt = 0, n_eq = 0;
+  for_each_chunk([&](int c, const float4& v) {
+    uint32_t gt, eq;
+    classify(c, v, gt, eq);
+    n_gt += __popc(gt);
+    n_eq += __popc(eq);
+  });
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    n_gt += __shfl_xor(n_gt, d);
+    n_eq += __shfl_xor(n_eq, d);
+  }
+  if (lane == 0) {
+    sh.cnt[2 * wave] = n_gt;
+    sh.cnt[2 * wave + 1] = n_eq;
+  }
+  __syncthreads();
+  uint32_t g_run = 0, e_run = 0;
+  for (int w = 0; w < wave; ++w) {
+    g_run += sh.cnt[2 * w];
+    e_run += sh.cnt[2 * w + 1];
+  }
+  for_each_chunk([&](int c, const float4& v) {
+    uint32_t gt, eq;
+    classify(c, v, gt, eq);
+    const uint32_t packed = ((uint32_t)__popc(gt) << 16) | (uint32_t)__popc(eq);
+    const uint32_t inc = wave_inclusive_scan(packed, lane);
+    const uint32_t tot = __shfl(inc, 63);
+    uint32_t g = g_run + ((inc - packed) >> 16), e = e_run + ((inc - packed) & 0xffffu);
+    const int i0 = c * 256 + lane * 4 - mis;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (gt & (1u << k)) {
+        idx_pad[g + min(e, ties)] = i0 + k;
+        ++g;
+      } else if (eq & (1u << k)) {
+        if (e < ties) idx_pad[g + e] = i0 + k;
+        ++e;
+      }
+    }
+    g_run += tot >> 16;
+    e_run += tot & 0xffffu;
+  });
+  return kept;
+}
+
 __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
-  __shared__ uint64_t sh_scan[kWaves + 1];
+  __shared__ uint64_t sh_scan[kWaves][2];
   __shared__ double sh_dbl[kWaves];
-  __shared__ double sh_incl[kT];
   __shared__ uint32_t sh_cnt[kBuckets];
   __shared__ uint64_t sh_mass[kBuckets];
+  extern __shared__ __attribute__((aligned(16))) float sh_scores[];        // score ranking: a unit's scores
+  double* sh_incl = reinterpret_cast<double*>(sh_mass);                    // [kT], position ranking only
   __shared__ int sh_i[8];
   __shared__ uint64_t sh_u64[2];
 
@@ -291,130 +527,8 @@ __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
       for (int i = tid; i < n; i += kT) idx_pad[i] = i;
   } else if (by_score) {
     // ---------------- score ranking: radix select of the cut value
-    uint64_t mine = 0;
-    for (int i = tid; i < n; i += kT) mine += quantise(s[i], inv);
-    uint64_t total;
-    block_exclusive_scan<uint64_t>(mine, sh_scan, &total);
-    const Pred pred{(double)total, (double)a.threshold, a.min_keep};
-    if (!pred(n, total)) {
-      kept = n;                                    // T <= 0 (or min_keep >= n): keep everything
-      if (idx_pad)
-        for (int i = tid; i < n; i += kT) idx_pad[i] = i;
-    } else {
-      uint32_t prefix = 0;                         // decided high bits of the cut key
-      int64_t cnt_above = 0;
-      uint64_t mass_above = 0;
-      const int shifts[3] = {21, 10, 0};
-      const int widths[3] = {11, 11, 10};
-      int done_bits = 0;
-      uint32_t cut_cnt = 0;
-      uint64_t cut_mass = 0;
-      for (int pass = 0; pass < 3; ++pass) {
-        const int shift = shifts[pass], width = widths[pass];
-        const int nb = 1 << width;
-        for (int d = tid; d < kBuckets; d += kT) {
-          sh_cnt[d] = 0;
-          sh_mass[d] = 0;
-        }
-        if (tid == 0) sh_i[1] = 0;
-        __syncthreads();
-        for (int i = tid; i < n; i += kT) {
-          const float v = s[i];
-          const uint32_t key = order_key(v);
-          if (done_bits == 0 || (key >> (32 - done_bits)) == prefix) {
-            const uint32_t d = (key >> shift) & (nb - 1);
-            atomicAdd(&sh_cnt[d], 1u);
-            atomicAdd(reinterpret_cast<unsigned long long*>(&sh_mass[d]), (unsigned long long)quantise(v, inv));
-          }
-        }
-        __syncthreads();
-        // suffix sums over buckets in descending digit order: thread t owns digits nb-1-2t, nb-2-2t
-        const int d_hi = nb - 1 - 2 * tid, d_lo = d_hi - 1;
-        const uint32_t c_hi = d_hi >= 0 ? sh_cnt[d_hi] : 0, c_lo = d_lo >= 0 ? sh_cnt[d_lo] : 0;
-        const uint64_t m_hi = d_hi >= 0 ? sh_mass[d_hi] : 0, m_lo = d_lo >= 0 ? sh_mass[d_lo] : 0;
-        uint64_t tot_c, tot_m;
-        const uint64_t ex_c = block_exclusive_scan<uint64_t>((uint64_t)c_hi + c_lo, sh_scan, &tot_c);
-        const uint64_t ex_m = block_exclusive_scan<uint64_t>(m_hi + m_lo, sh_scan, &tot_m);
-        // crossing bucket: predicate false before it, true once it is included
-        if (d_hi >= 0) {
-          const int64_t c0 = cnt_above + (int64_t)ex_c;
-          const uint64_t m0 = mass_above + ex_m;
-          const bool p0 = pred(c0, m0);
-          const bool p1 = pred(c0 + c_hi, m0 + m_hi);
-          if (!p0 && p1 && c_hi > 0) {
-            sh_i[1] = d_hi;
-            sh_u64[0] = (uint64_t)c0;
-            sh_u64[1] = m0;
-          } else if (d_lo >= 0 && !p1) {
-            const bool p2 = pred(c0 + c_hi + c_lo, m0 + m_hi + m_lo);
-            if (p2 && c_lo > 0) {
-              sh_i[1] = d_lo;
-              sh_u64[0] = (uint64_t)(c0 + c_hi);
-              sh_u64[1] = m0 + m_hi;
-            }
-          }
-        }
-        __syncthreads();
-        const int d_cut = sh_i[1];
-        cnt_above = (int64_t)sh_u64[0];
-        mass_above = sh_u64[1];
-        cut_cnt = sh_cnt[d_cut];
-        cut_mass = sh_mass[d_cut];
-        prefix = (prefix << width) | (uint32_t)d_cut;
-        done_bits += width;
-        __syncthreads();
-      }
-      // all cut_cnt elements of the final bucket share one value: take the fewest that cross
-      const uint64_t q_each = cut_mass / (cut_cnt ? cut_cnt : 1u);
-      if (tid == 0) {
-        int lo = 1, hi = (int)cut_cnt;             // pred is true at hi
-        while (lo < hi) {
-          const int mid = (lo + hi) >> 1;
-          if (pred(cnt_above + mid, mass_above + (uint64_t)mid * q_each)) hi = mid;
-          else lo = mid + 1;
-        }
-        sh_i[2] = lo;
-      }
-      __syncthreads();
-      const int ties = sh_i[2];
-      kept = (int)cnt_above + ties;
-
-      // emit retained positions in ascending order
-      if (idx_pad) {
-        constexpr int kItems = 8;
-        uint32_t carry_gt = 0, carry_eq = 0;
-        for (int base = 0; base < n; base += kT * kItems) {
-          const int p0 = base + tid * kItems;
-          uint32_t gt = 0, eq = 0;
-          uint32_t keys[kItems];
-#pragma unroll
-          for (int j = 0; j < kItems; ++j) {
-            const int p = p0 + j;
-            keys[j] = p < n ? order_key(s[p]) : 0u;
-            gt += (p < n && keys[j] > prefix);
-            eq += (p < n && keys[j] == prefix);
-          }
-          uint64_t tot;
-          const uint64_t ex = block_exclusive_scan<uint64_t>(((uint64_t)gt << 32) | eq, sh_scan, &tot);
-          uint32_t g_run = carry_gt + (uint32_t)(ex >> 32), e_run = carry_eq + (uint32_t)ex;
-#pragma unroll
-          for (int j = 0; j < kItems; ++j) {
-            const int p = p0 + j;
-            if (p < n) {
-              if (keys[j] > prefix) {
-                idx_pad[g_run + min(e_run, (uint32_t)ties)] = p;
-                ++g_run;
-              } else if (keys[j] == prefix) {
-                if (e_run < (uint32_t)ties) idx_pad[g_run + e_run] = p;
-                ++e_run;
-              }
-            }
-          }
-          carry_gt += (uint32_t)(tot >> 32);
-          carry_eq += (uint32_t)tot;
-        }
-      }
-    }
+    SelectShared sh{sh_scan, sh_cnt, sh_mass, sh_i, sh_u64};
+    kept = score_rank(s, n, inv, a.threshold, a.min_keep, idx_pad, sh_scores, a.lds_floats, sh);
   }
 
   if (tid == 0) {
@@ -435,7 +549,21 @@ hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t str
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(select_kernel, dim3(g.units), dim3(kT), 0, stream, a);
+  // Score ranking keeps a unit's scores in LDS when the longest sequence fits (with up to three
+  // floats of alignment slack); otherwise units that fit what is there use it and the rest stream.
+  SelectArgs args = a;
+  args.lds_floats = 0;
+  if (a.rank_mode == 1 && a.threshold > 0.f) {
+    const int64_t want = ((int64_t)g.max_seqlen + 3 + 3) / 4 * 4;
+    args.lds_floats = (int32_t)(want < kMaxLdsFloats ? want : kMaxLdsFloats);
+  }
+  const size_t dyn = (size_t)args.lds_floats * sizeof(float);
+  if (dyn > 32 * 1024) {                           // beyond the default limit on static + dynamic LDS
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(select_kernel, dim3(g.units), dim3(kT), dyn, stream, args);
   return hipGetLastError();
 }
 
