@@ -33,6 +33,16 @@ Workspace carve_workspace(const Geometry& g, void* base) {
 
 namespace {
 
+// Score rows per KV head as the kernels lay them out: a multiple of 32, and up to 256 one of the
+// sizes the streaming kernels are instantiated for (1, 2, 4 or 8 row tiles), so that a kernel's
+// row tiles and the per-row tables in the workspace always coincide.
+int64_t padded_rows(int64_t rows) {
+  const int64_t r32 = (rows + 31) / 32 * 32;
+  if (r32 > 64 && r32 <= 128) return 128;
+  if (r32 > 128 && r32 <= 256) return 256;
+  return r32;
+}
+
 // keys one score workgroup covers: enough workgroups to fill 256 CUs a few times over, but long
 // enough that staging the window queries (once per workgroup) stays a small part of its traffic
 int32_t choose_span(int64_t total_tokens, int32_t n_kv_heads) {
@@ -59,7 +69,7 @@ rfkv_status check_params(const rfkv_params* p) {
   if ((int64_t)p->batch * p->n_kv_heads > RFKV_MAX_UNITS) return RFKV_UNSUPPORTED;
   const int eb = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
   // the window queries of one unit must fit in LDS next to the per-row tables
-  const int64_t rows_pad = (rows + 31) / 32 * 32;
+  const int64_t rows_pad = padded_rows(rows);
   if (rows_pad * (p->head_dim * eb + 16 + 8) > 156 * 1024) return RFKV_UNSUPPORTED;
   return RFKV_OK;
 }
@@ -102,7 +112,7 @@ Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len, con
   g.head_dim = p->head_dim;
   g.window = p->window;
   g.units = p->batch * p->n_kv_heads;
-  g.rows_pad = (p->window * g.group + 31) / 32 * 32;
+  g.rows_pad = (int32_t)padded_rows((int64_t)p->window * g.group);
   g.span = choose_span(total, p->n_kv_heads);
   g.nspans = (max_len + g.span - 1) / g.span;
   g.max_seqlen = max_len;

@@ -37,12 +37,13 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   constexpr int kThreads = kWaves * 64;
   constexpr int kTileBytes = 32 * S::kRowBytes;
   constexpr int kLoads = kTileBytes / 1024;            // direct-to-LDS instructions per tile
-  constexpr int kQStage = RT_T * 32 * S::kLdsRowBytes;
-  constexpr int kBytesB = (!QREG || kWaves * kTileBytes < kQStage) ? kQStage : kWaves * kTileBytes;
-  // distinct LDS objects, so that reads of the tables are known not to touch the tile buffers
+  // distinct LDS objects, so that reads of one are known not to touch a buffer with loads in flight
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * kTileBytes];   // tile buffers
-  __shared__ __attribute__((aligned(1024))) unsigned char smem_b[kBytesB];   // queries (QREG: then odd tiles)
-  __shared__ __attribute__((aligned(16))) float bsm[RT_T * 32];      // pass 2: exponent offset per row
+  // QREG: the window queries on their way to registers, then the odd tiles; otherwise nothing
+  __shared__ __attribute__((aligned(1024))) unsigned char smem_b[QREG ? kWaves * kTileBytes : 1024];
+  // !QREG: the window queries, padded rows, for the whole kernel
+  __shared__ __attribute__((aligned(16))) unsigned char qsm[QREG ? 16 : RT_T * 32 * S::kLdsRowBytes];
+  __shared__ __attribute__((aligned(256))) float bsm[RT_T * 32 < 64 ? 64 : RT_T * 32];   // pass 2: exponent offset per row
   __shared__ __attribute__((aligned(16))) int rlast_s[RT_T * 32];    // pass 2: last visible key per row
   const int bx = blockIdx.x, by = blockIdx.y;
   const Unit u = load_unit(a, by);
@@ -62,51 +63,10 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   const int first_masked_key = u.n - u.wp + 1;         // keys below are visible to every row
   constexpr int kStep = kWaves * 32;                   // keys the workgroup consumes per iteration
 
-  // window queries (row r = t * G + g of this KV head) pass through LDS once per workgroup: issue
-  // their loads, then the first key tile's, and wait for the queries only (loads return in order)
-  constexpr int kCpr = S::kRowBytes / 16;
-  constexpr int kQPerThread = RT_T * 32 * kCpr / kThreads;
-  static_assert(kQPerThread * kThreads == RT_T * 32 * kCpr, "query staging must divide evenly");
-  uint4 qv[kQPerThread];
-  {
-    const unsigned char* qbase = static_cast<const unsigned char*>(a.q);
-#pragma unroll
-    for (int j = 0; j < kQPerThread; ++j) {
-      const int i = threadIdx.x + j * kThreads;
-      const int r = i / kCpr;
-      const int ch = i - r * kCpr;
-      qv[j] = make_uint4(0, 0, 0, 0);
-      if (r < u.rows) {
-        const int t = r / a.group;
-        const int g = r - t * a.group;
-        const int64_t off = (int64_t)(u.q0 + t) * a.q_stride_row + (int64_t)(u.h * a.group + g) * a.q_stride_head;
-        qv[j] = *reinterpret_cast<const uint4*>(qbase + off * T::kBytes + ch * 16);
-      }
-    }
-  }
   int tile0 = span_begin + wave * 32;
-  if (tile0 < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0, u.n, kbuf0, lane);
-#pragma unroll
-  for (int j = 0; j < kQPerThread; ++j) {
-    const int i = threadIdx.x + j * kThreads;
-    const int r = i / kCpr;
-    *reinterpret_cast<uint4*>(smem_b + r * S::kLdsRowBytes + (i - r * kCpr) * 16) = qv[j];
-  }
-  __syncthreads();
+  const TileLoader<T, D> tiles(kunit, tok_bytes, u.n, lane);
   constexpr int kQRegTiles = QREG ? RT_T : 1;
   uint4 qf[kQRegTiles][S::kChunks];                    // QREG: fragments of all row tiles, for the whole kernel
-  if (QREG) {
-#pragma unroll
-    for (int rt = 0; rt < kQRegTiles; ++rt) {
-      const unsigned char* qrow = smem_b + (rt * 32 + col) * S::kLdsRowBytes + hi * S::kHalfBytes;
-#pragma unroll
-      for (int ch = 0; ch < S::kChunks; ++ch) qf[rt][ch] = *reinterpret_cast<const uint4*>(qrow + ch * 16);
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __syncthreads();                                   // the staging area becomes the second buffer set
-    if (tile0 + kStep < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + kStep, u.n, kbuf1, lane);
-  }
-
   float mc[RT_T], l[RT_T];
   int rowlast[RT_T];
   if (PASS == 1) {
@@ -117,25 +77,108 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
       const int r = rt * 32 + col;
       rowlast[rt] = r < u.rows ? u.n - u.wp + r / a.group : -1;
     }
-  } else {
-    for (int r = threadIdx.x; r < RT_T * 32; r += kThreads) {
-      bsm[r] = r < a.rows_pad ? a.bvec[(int64_t)by * a.rows_pad + r] : __builtin_inff();
-      rlast_s[r] = r < u.rows ? u.n - u.wp + r / a.group : -1;
+  }
+  if constexpr (QREG) {
+    // Everything the loop needs arrives by direct-to-LDS loads, issued at once: the first key tile
+    // (the bulk: memory is busy from the start), pass 2's per-row exponent offsets (64 per
+    // wavefront) and one row tile of window queries per wavefront into the second buffer set.
+    // No register depends on a load, so the compiler adds no wait of its own.
+    static_assert(RT_T <= kWaves && RT_T * 32 <= kWaves * 64, "one query tile and 64 offsets per wavefront");
+    if (tile0 < span_end) tiles.issue(tile0, kbuf0);
+    if (PASS == 2) {
+      if (threadIdx.x < RT_T * 32)
+        lds_write_b32(rlast_s + threadIdx.x,
+                      (uint32_t)((int)threadIdx.x < u.rows ? u.n - u.wp + (int)threadIdx.x / a.group : -1));
+      if (wave * 64 < RT_T * 32) {
+        const float* src = a.bvec + (int64_t)by * a.rows_pad + min(wave * 64 + lane, a.rows_pad - 1);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(bsm + wave * 64), 4, 0, 0);
+      }
     }
+    if (wave < RT_T) issue_q_tile_load<T, D>(a, u, wave, smem_b + wave * kTileBytes, lane);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    lds_writes_done();
     __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < RT_T; ++rt) read_tile_frags<T, D>(qf[rt], smem_b + rt * kTileBytes, col, hi);
+    __syncthreads();                                   // the query tiles become the second buffer set
+    if (tile0 + kStep < span_end) tiles.issue(tile0 + kStep, kbuf1);
+  } else {
+    // The window queries (row r = t * G + g of this KV head) and pass 2's per-row exponent offsets
+    // are staged before the first key tile is requested: with a direct-to-LDS load in flight the
+    // compiler makes every use of an ordinarily loaded register wait for all loads.
+    float bmine = __builtin_inff();
+    if (PASS == 2 && threadIdx.x < RT_T * 32 && (int)threadIdx.x < a.rows_pad)
+      bmine = a.bvec[(int64_t)by * a.rows_pad + threadIdx.x];
+    constexpr int kCpr = S::kRowBytes / 16;
+    constexpr int kQPerThread = RT_T * 32 * kCpr / kThreads;
+    static_assert(kQPerThread * kThreads == RT_T * 32 * kCpr, "query staging must divide evenly");
+    static_assert(kThreads % kCpr == 0, "a thread keeps its chunk column from one piece to the next");
+    uint4 qv[kQPerThread];
+    {
+      // thread's piece j: row r0 + j * kRowStep, chunk ch.  (t, g) = (r / G, r % G) advance without
+      // a division per piece; rows past the unit's last are loaded from the last row (so that no
+      // load hangs on a branch) and zeroed when they are staged.
+      const unsigned char* qbase = static_cast<const unsigned char*>(a.q);
+      constexpr int kRowStep = kThreads / kCpr;
+      const int ch = threadIdx.x % kCpr;
+      const int dt = kRowStep / a.group, dg = kRowStep - dt * a.group;
+      int r = threadIdx.x / kCpr;
+      int t = r / a.group, g = r - t * a.group;
+      const int t_last = (u.rows - 1) / a.group, g_last = (u.rows - 1) - t_last * a.group;
+#pragma unroll
+      for (int j = 0; j < kQPerThread; ++j) {
+        const bool in = r < u.rows;
+        const int tt = in ? t : t_last, gg = in ? g : g_last;
+        const int64_t off = (int64_t)(u.q0 + tt) * a.q_stride_row + (int64_t)(u.h * a.group + gg) * a.q_stride_head;
+        qv[j] = *reinterpret_cast<const uint4*>(qbase + off * T::kBytes + ch * 16);
+        r += kRowStep;
+        t += dt;
+        g += dg;
+        if (g >= a.group) {
+          g -= a.group;
+          ++t;
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < kQPerThread; ++j) {
+      const int i = threadIdx.x + j * kThreads;
+      const int r = i / kCpr;
+      const uint4 v = r < u.rows ? qv[j] : make_uint4(0, 0, 0, 0);
+      lds_write_b128(qsm + r * S::kLdsRowBytes + (i - r * kCpr) * 16, v);
+    }
+    if (PASS == 2) {
+      static_assert(RT_T * 32 <= kThreads, "one table entry per thread");
+      if (threadIdx.x < RT_T * 32) {
+        const int r = threadIdx.x;
+        lds_write_b32(bsm + r, __float_as_uint(bmine));
+        lds_write_b32(rlast_s + r, (uint32_t)(r < u.rows ? u.n - u.wp + r / a.group : -1));
+      }
+    }
+    lds_writes_done();
+    __syncthreads();
+    if (tile0 < span_end) tiles.issue(tile0, kbuf0);
   }
   float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
 
+  // From here on the loop counts the loads and stores in flight itself.  Per iteration a wavefront
+  // issues the kLoads loads of one tile and, in pass 2, kStores stores (scores, tile sum).
+  constexpr int kStores = PASS == 2 ? 2 : 0;
   for (int it = 0; tile0 < span_end; tile0 += kStep, ++it) {
     uint4 kf[S::kChunks];
     unsigned char* kbuf = (QREG && (it & 1)) ? kbuf1 : kbuf0;
-    // loads complete in issue order: once at most one tile's worth is outstanding, this tile has landed
-    if (QREG && tile0 + kStep < span_end) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads) : "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    read_tile_frags<T, D>(kf, kbuf, col, hi);
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // fragments are in registers: the buffer is free
+    // Loads and stores complete in issue order.  Behind this tile's loads there are at most the next
+    // tile's loads and (from the second iteration on) the stores of the iteration before.
+    if (QREG && tile0 + kStep < span_end) {
+      if (it == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads) : "memory");
+      else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads + kStores) : "memory");
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    read_tile_frags<T, D>(kf, kbuf, col, hi);          // complete on return: the buffer is free
     constexpr int kAhead = QREG ? 2 * kStep : kStep;
-    if (tile0 + kAhead < span_end) issue_tile_load<T, D>(kunit, tok_bytes, tile0 + kAhead, u.n, kbuf, lane);
+    if (tile0 + kAhead < span_end) tiles.issue(tile0 + kAhead, kbuf);
     const bool masked = tile0 + 32 > first_masked_key;
 
     // Logits of one row tile against this key tile.  Row tiles past the unit's rows hold zero
@@ -147,7 +190,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
 #pragma unroll
       for (int ch = 0; ch < S::kChunks; ++ch) {
         const uint4 q = QREG ? qf[QREG ? rt : 0][ch]
-                             : *reinterpret_cast<const uint4*>(smem_b + (rt * 32 + col) * S::kLdsRowBytes +
+                             : *reinterpret_cast<const uint4*>(qsm + (rt * 32 + col) * S::kLdsRowBytes +
                                                                hi * S::kHalfBytes + ch * 16);
         acc = PASS == 1 ? mma_chunk<T>(kf[ch], q, acc)      // keys x rows: a lane owns one row
                         : mma_chunk<T>(q, kf[ch], acc);     // rows x keys: a lane owns one key
@@ -217,6 +260,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
       if (lane == 0) a.tile_sq[(int64_t)u.h * a.tiles_total + u.tile_base + (tile0 >> 5)] = tsq;
     }
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no load may still be writing LDS from here on
   if (PASS == 1) {
     // the two half-waves hold disjoint keys of the same rows; then the four wavefronts
 #pragma unroll
