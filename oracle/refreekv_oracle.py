@@ -19,7 +19,9 @@ Everything here is written from the paper's definitions, slowly and plainly:
   within T of the full norm (Eq. 1), in the masked-norm *definition* form and in
   the cumulative square-sum form (Eq. 3);
 * compaction             -- gather of the retained K/V rows (Alg. 1, last steps),
-  emitted in ascending original position.
+  emitted in ascending original position;
+* decode attention       -- softmax(q K_c^T / sqrt(d)) V_c of new queries over the compacted
+  ragged cache, and the same over the full cache with evicted positions masked.
 
 All floating point is float64.  Inputs arrive already upcast (bf16/fp32 -> fp64
 is exact), so the oracle sees the same values the GPU sees.
@@ -29,7 +31,9 @@ against a library softmax, the full n x n attention matrix on tiny inputs,
 closed forms of the budget rule (uniform / one-hot / geometric / two-level),
 definition-form == cumsum-form, exhaustive subset search for the score ranking,
 literal prefix enumeration for the position ranking, T = 0 / T >= 1 limits,
-and attention over the compacted cache == masked full attention.  The paper
+attention over the compacted cache == masked full attention, and the decode
+attention against a library scaled-dot-product attention, a single-key cache and an
+all-equal-keys cache.  The paper
 prints no worked numeric example of the rule, so there is no paper-value pin;
 results on the paper's real datasets/models are parity-unpinned.
 """
@@ -244,6 +248,48 @@ def attention_output(q_new, k_rows, v_rows, scale, keep_mask=None):
     logits = logits - logits.max(axis=1, keepdims=True)
     e = np.exp(logits)
     return (e / e.sum(axis=1, keepdims=True)) @ np.asarray(v_rows, np.float64)
+
+
+def oracle_decode_attention(q_new, k_c, v_c, out_offsets, n_q_heads, n_kv_heads, scale=None):
+    """Attention of new queries over the compacted ragged cache (the consumer of Alg. 1's
+    compressed K / V; Sec. 4.3 measures its cost): q_new [B, n_new, Hq, d]; the retained rows
+    of unit u = b * Hkv + h are k_c / v_c [out_offsets[u] : out_offsets[u + 1]].  Every new
+    query sees the whole cache of its sequence and nothing else.  Returns float64
+    [B, n_new, Hq, d]; a unit without rows gives zeros."""
+    q_new = np.asarray(q_new, np.float64)
+    B, n_new, Hq, d = q_new.shape
+    G = n_q_heads // n_kv_heads
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    out = np.zeros((B, n_new, Hq, d))
+    for b in range(B):
+        for h in range(n_kv_heads):
+            u = b * n_kv_heads + h
+            lo, hi = int(out_offsets[u]), int(out_offsets[u + 1])
+            if hi == lo:
+                continue
+            for g in range(G):
+                out[b, :, h * G + g, :] = attention_output(q_new[b, :, h * G + g, :], k_c[lo:hi], v_c[lo:hi], scale)
+    return out
+
+
+def oracle_masked_attention(q_new, k, v, cu_seqlens, keep_mask, n_q_heads, n_kv_heads, scale=None):
+    """The same attention over the uncompressed cache with the evicted positions masked to
+    -inf: k, v [N, Hkv, d] packed, keep_mask [Hkv, N] bool.  By the permutation invariance of
+    attention it equals oracle_decode_attention on the compacted rows."""
+    q_new = np.asarray(q_new, np.float64)
+    B, n_new, Hq, d = q_new.shape
+    G = n_q_heads // n_kv_heads
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    out = np.zeros((B, n_new, Hq, d))
+    for b in range(B):
+        s, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        for h in range(n_kv_heads):
+            m = np.asarray(keep_mask[h, s:e], bool)
+            if not m.any():
+                continue
+            for g in range(G):
+                out[b, :, h * G + g, :] = attention_output(q_new[b, :, h * G + g, :], k[s:e, h], v[s:e, h], scale, m)
+    return out
 
 
 def cut_robustness(scores_unit, rank_mode, n_sink, T, rel=1e-3):

@@ -172,3 +172,25 @@ def make_layer(cfg_id, layer: int = 0, cfg: Config | None = None, lengths=None) 
         q, k, v = f32_to_bf16_bits(q), f32_to_bf16_bits(k), f32_to_bf16_bits(v)
     return Layer(cfg, q, k, v, cu, dict(cfg_id=cfg_id, layer=layer, seed=seed, x_sink=x_sinks,
                                         lengths=lens))
+
+
+def make_new_queries(cfg_id, layer: int = 0, n_new: int = 64, cfg: Config | None = None, lengths=None) -> np.ndarray:
+    """Queries of `n_new` decode positions per sequence, [B, n_new, Hq, d] in the configuration's
+    storage type (bf16 as uint16 bit patterns): N(0,1) plus the component the window queries of
+    the same layer share, so that the new queries look at the cache the way the window did."""
+    cfg = cfg or CONFIGS[cfg_id]
+    seed = 1000 * (cfg_id if isinstance(cfg_id, int) else 9) + layer
+    lens = np.asarray(lengths if lengths is not None else seq_lengths(cfg, cfg_id), dtype=np.int64)
+    B = len(lens)
+    Hq, Hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    G = Hq // Hkv
+    q = np.empty((B, n_new, Hq, d), dtype=np.float32)
+    for b in range(B):
+        qb = _rng(seed, 10 * b + 6).standard_normal((n_new, Hq, d), dtype=np.float32)
+        if cfg.q_shared:
+            e = _rng(seed, 10 * b + 5).standard_normal((Hkv, d))      # the same draw make_layer uses
+            e /= np.linalg.norm(e, axis=1, keepdims=True)
+            qb += np.repeat(cfg.q_shared * np.sqrt(d) * e, G, axis=0).astype(np.float32)[None]
+        q[b] = qb
+    return f32_to_bf16_bits(q) if cfg.dtype == "bf16" else q
+
