@@ -177,6 +177,41 @@ RFKV_API rfkv_status rfkv_compress_layer_timed(const rfkv_params* params, const 
                                 int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream,
                                 float* kernel_ms_host);
 
+/*
+ * Decode attention over the compacted cache -- the consumer of Alg. 1's compressed K / V (the
+ * paper's efficiency comparison, Sec. 4.3, is between attention over the pruned and over the full
+ * cache).  n_new new queries per sequence attend to every retained position of their sequence
+ * and to nothing else (no attention among the new positions):
+ *   out[b, j, hq, :] = softmax_i(scale * q_new[b, j, hq] . k_c[o_u + i]) . v_c[o_u + i],
+ *   u = b * n_kv_heads + hq / G, o_u = out_offsets[u], i in [0, kept_u).
+ * bf16 storage only (RFKV_UNSUPPORTED otherwise); n_new * G <= RFKV_MAX_DECODE_ROWS.
+ *   q_new        device, bf16 [B, n_new, Hq, d] contiguous
+ *   k_c, v_c     device, bf16 [rows, d] contiguous as written by rfkv_compact / rfkv_compress_layer
+ *   out_offsets  device, int64 [B * Hkv + 1] as written by rfkv_select / rfkv_compress_layer
+ *   out          device, float [B, n_new, Hq, d]; a unit with no rows gives zeros
+ *   ws           device scratch of at least rfkv_decode_workspace_bytes(...)
+ * cu_seqlens_host bounds the unit lengths (kept_u <= n_b) for the launch geometry; the kept
+ * counts themselves are read on the device only.  Probabilities are rounded to bf16 for the
+ * value product (fp32 accumulation), like the stored values themselves.
+ */
+enum { RFKV_MAX_DECODE_ROWS = 256 };
+RFKV_API size_t rfkv_decode_workspace_bytes(const rfkv_params* params, int32_t n_new, int32_t max_seqlen);
+RFKV_API rfkv_status rfkv_decode_attention(const rfkv_params* params, const void* q_new, int32_t n_new,
+                                  const void* k_c, const void* v_c, const int32_t* cu_seqlens_host,
+                                  const int64_t* out_offsets, float* out, void* ws, size_t ws_bytes,
+                                  void* stream);
+
+/*
+ * The same attention over the uncompressed cache with the evicted positions masked to -inf: the
+ * baseline rfkv_decode_attention is timed against, and by the permutation invariance of attention
+ * the same result.  k, v through params' k_/v_stride_*; keep_mask device, uint8 [Hkv, N], non-zero
+ * = retained.  Other arguments as above.
+ */
+RFKV_API rfkv_status rfkv_masked_attention(const rfkv_params* params, const void* q_new, int32_t n_new,
+                                  const void* k, const void* v, const int32_t* cu_seqlens_host,
+                                  const int32_t* cu_seqlens_dev, const uint8_t* keep_mask, float* out,
+                                  void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

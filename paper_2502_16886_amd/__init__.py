@@ -5,4 +5,5 @@ seeded synthetic inputs; `build` compiles the library with hipcc.
 """
 from . import binding, workloads  # noqa: F401
 from .binding import (RfkvError, RfkvParams, make_params, rfkv_compact, rfkv_compress_layer,  # noqa: F401
-                      rfkv_score, rfkv_select, rfkv_version, rfkv_workspace_bytes)
+                      rfkv_decode_attention, rfkv_decode_workspace_bytes, rfkv_masked_attention, rfkv_score,
+                      rfkv_select, rfkv_version, rfkv_workspace_bytes)

@@ -79,13 +79,20 @@ def load_library() -> ctypes.CDLL:
     lib.rfkv_compress_layer.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     lib.rfkv_compress_layer_timed.restype = ctypes.c_int
     lib.rfkv_compress_layer_timed.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp, vp]
+    lib.rfkv_decode_workspace_bytes.restype = sz
+    lib.rfkv_decode_workspace_bytes.argtypes = [P, i32, i32]
+    lib.rfkv_decode_attention.restype = ctypes.c_int
+    lib.rfkv_decode_attention.argtypes = [P, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.rfkv_masked_attention.restype = ctypes.c_int
+    lib.rfkv_masked_attention.argtypes = [P, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
     return lib
 
 
 EXPORTED_SYMBOLS = ("rfkv_version", "rfkv_status_string", "rfkv_last_device_error", "rfkv_workspace_bytes",
                     "rfkv_score", "rfkv_select", "rfkv_compact", "rfkv_compress_layer",
-                    "rfkv_compress_layer_timed")
+                    "rfkv_compress_layer_timed", "rfkv_decode_workspace_bytes", "rfkv_decode_attention",
+                    "rfkv_masked_attention")
 KERNEL_NAMES = ("score_stats", "score_merge", "score_reduce", "select", "compact")
 
 
@@ -170,6 +177,26 @@ def rfkv_compress_layer_timed(params, q_win, k, v, cu_host, cu_dev, scores_opt, 
         _ptr(kept), _ptr(out_offsets), _ptr(idx_opt), _ptr(k_out), _ptr(v_out), int(out_capacity_rows), _ptr(ws),
         int(ws_bytes), _stream(stream), ctypes.cast(ms, ctypes.c_void_p))
     return _check(st, "rfkv_compress_layer_timed", check), list(ms)
+
+
+def rfkv_decode_workspace_bytes(params, n_new: int, max_seqlen: int) -> int:
+    return int(load_library().rfkv_decode_workspace_bytes(ctypes.byref(params), int(n_new), int(max_seqlen)))
+
+
+def rfkv_decode_attention(params, q_new, n_new, k_c, v_c, cu_host, out_offsets, out, ws, ws_bytes, stream=None,
+                          check=True) -> int:
+    st = load_library().rfkv_decode_attention(ctypes.byref(params), _ptr(q_new), int(n_new), _ptr(k_c), _ptr(v_c),
+                                              _ptr(cu_host), _ptr(out_offsets), _ptr(out), _ptr(ws), int(ws_bytes),
+                                              _stream(stream))
+    return _check(st, "rfkv_decode_attention", check)
+
+
+def rfkv_masked_attention(params, q_new, n_new, k, v, cu_host, cu_dev, keep_mask, out, ws, ws_bytes, stream=None,
+                          check=True) -> int:
+    st = load_library().rfkv_masked_attention(ctypes.byref(params), _ptr(q_new), int(n_new), _ptr(k), _ptr(v),
+                                              _ptr(cu_host), _ptr(cu_dev), _ptr(keep_mask), _ptr(out), _ptr(ws),
+                                              int(ws_bytes), _stream(stream))
+    return _check(st, "rfkv_masked_attention", check)
 
 
 # ----------------------------------------------------------------------------

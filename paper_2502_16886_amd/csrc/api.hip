@@ -298,6 +298,112 @@ rfkv_status rfkv_compact(const rfkv_params* params, const void* k, const void* v
   return device_status(launch_compact(g, c, static_cast<hipStream_t>(stream)));
 }
 
+// Launch geometry of the decode attention: enough spans to give every CU a workgroup, none
+// shorter than 128 keys.
+static void decode_geometry(const rfkv_params* p, int32_t n_new, int32_t max_len, DecodeArgs* a) {
+  const int units = p->batch * p->n_kv_heads;
+  a->n_q_heads = p->n_q_heads;
+  a->n_kv_heads = p->n_kv_heads;
+  a->group = p->n_q_heads / p->n_kv_heads;
+  a->n_new = n_new;
+  a->rows = n_new * a->group;
+  a->rows_pad = a->rows <= 128 ? 128 : 256;
+  a->head_dim = p->head_dim;
+  int splits = units > 0 ? (256 + units - 1) / units : 1;
+  const int most = (max_len + 127) / 128;
+  if (splits > most) splits = most;
+  if (splits < 1) splits = 1;
+  a->span = ((max_len + splits - 1) / splits + 31) / 32 * 32;
+  if (a->span < 32) a->span = 32;
+  a->nsplits = (max_len + a->span - 1) / a->span;
+  if (a->nsplits < 1) a->nsplits = 1;
+  a->c = scale_times_log2e(p);
+}
+
+static size_t decode_ws_bytes(const rfkv_params* p, const DecodeArgs& a) {
+  const size_t slots = (size_t)p->batch * p->n_kv_heads * a.nsplits * a.rows_pad;
+  return slots * a.head_dim * sizeof(float) + slots * sizeof(float2) + 256;
+}
+
+static rfkv_status decode_check(const rfkv_params* p, int32_t n_new) {
+  const rfkv_status st = check_params(p);
+  if (st != RFKV_OK) return st;
+  if (n_new < 0) return RFKV_INVALID_ARG;
+  if (p->dtype != RFKV_DTYPE_BF16) return RFKV_UNSUPPORTED;
+  if ((int64_t)n_new * (p->n_q_heads / p->n_kv_heads) > RFKV_MAX_DECODE_ROWS) return RFKV_UNSUPPORTED;
+  return RFKV_OK;
+}
+
+static rfkv_status decode_impl(const rfkv_params* params, const void* q_new, int32_t n_new, const void* k,
+                               const void* v, const int32_t* cu_host, const int32_t* cu_dev,
+                               const int64_t* out_offsets, const uint8_t* keep_mask, bool masked, float* out,
+                               void* ws, size_t ws_bytes, void* stream) {
+  rfkv_status st = decode_check(params, n_new);
+  if (st != RFKV_OK) return st;
+  if (!cu_host || cu_host[0] != 0) return RFKV_INVALID_ARG;
+  int32_t max_len = 0;
+  for (int b = 0; b < params->batch; ++b) {
+    const int64_t len = (int64_t)cu_host[b + 1] - cu_host[b];
+    if (len < 0) return RFKV_INVALID_ARG;
+    if (len > max_len) max_len = (int32_t)len;
+  }
+  if (params->batch == 0 || n_new == 0) return RFKV_OK;
+  if (!out || !aligned16(out) || !aligned16(q_new) || !aligned16(ws)) return RFKV_INVALID_ARG;
+  if (masked) {
+    if (!cu_dev || !keep_mask) return RFKV_INVALID_ARG;
+    if ((st = check_strides(params, false, true, true)) != RFKV_OK) return st;
+  } else if (!out_offsets) {
+    return RFKV_INVALID_ARG;
+  }
+  if (max_len > 0 && (!aligned16(k) || !aligned16(v))) return RFKV_INVALID_ARG;
+  DecodeArgs a{};
+  decode_geometry(params, n_new, max_len, &a);
+  if (ws_bytes < decode_ws_bytes(params, a)) return RFKV_WORKSPACE_TOO_SMALL;
+  a.q = q_new;
+  a.k = k;
+  a.v = v;
+  a.out = out;
+  a.total_tokens = cu_host[params->batch];
+  const size_t slots = (size_t)params->batch * params->n_kv_heads * a.nsplits * a.rows_pad;
+  a.part_o = static_cast<float*>(ws);
+  a.part_ml = reinterpret_cast<float2*>(static_cast<unsigned char*>(ws) + slots * a.head_dim * sizeof(float));
+  if (masked) {
+    a.cu = cu_dev;
+    a.mask = keep_mask;
+    a.k_stride_tok = params->k_stride_tok;
+    a.k_stride_head = params->k_stride_head;
+    a.v_stride_tok = params->v_stride_tok;
+    a.v_stride_head = params->v_stride_head;
+  } else {
+    a.offsets = out_offsets;
+    a.k_stride_tok = a.v_stride_tok = params->head_dim;
+    a.k_stride_head = a.v_stride_head = 0;
+  }
+  return device_status(launch_decode_attention(a, params->batch * params->n_kv_heads, masked,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+size_t rfkv_decode_workspace_bytes(const rfkv_params* params, int32_t n_new, int32_t max_seqlen) {
+  if (decode_check(params, n_new) != RFKV_OK || max_seqlen < 0) return 0;
+  DecodeArgs a{};
+  decode_geometry(params, n_new, max_seqlen, &a);
+  return decode_ws_bytes(params, a);
+}
+
+rfkv_status rfkv_decode_attention(const rfkv_params* params, const void* q_new, int32_t n_new, const void* k_c,
+                                  const void* v_c, const int32_t* cu_seqlens_host, const int64_t* out_offsets,
+                                  float* out, void* ws, size_t ws_bytes, void* stream) {
+  return decode_impl(params, q_new, n_new, k_c, v_c, cu_seqlens_host, nullptr, out_offsets, nullptr, false, out, ws,
+                     ws_bytes, stream);
+}
+
+rfkv_status rfkv_masked_attention(const rfkv_params* params, const void* q_new, int32_t n_new, const void* k,
+                                  const void* v, const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
+                                  const uint8_t* keep_mask, float* out, void* ws, size_t ws_bytes, void* stream) {
+  return decode_impl(params, q_new, n_new, k, v, cu_seqlens_host, cu_seqlens_dev, nullptr, keep_mask, true, out, ws,
+                     ws_bytes, stream);
+}
+
 static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_win, const void* k, const void* v,
                                 const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores_opt,
                                 int32_t* kept, int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,

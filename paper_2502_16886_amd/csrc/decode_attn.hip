@@ -1,0 +1,390 @@
+// Attention of a block of new queries over the compacted ragged cache, and the same over the
+// uncompressed cache with the evicted positions masked (the consumer of Alg. 1's compressed K / V;
+// Sec. 4.3 compares the two costs).  bf16 storage, fp32 softmax and accumulation, fp32 output.
+//
+// One workgroup (4 wavefronts) takes one span of keys of one unit (sequence, KV head) and all
+// M = n_new * G query rows of that KV head (row = j * G + g), 32 * RTW rows per wavefront:
+//
+//   S^T = K Q^T   32x32x16 bf16 MFMA, keys along M, rows along N: a lane owns one query row and
+//                 16 of the tile's 32 keys, so the softmax statistics are in-lane (plus one
+//                 exchange between the two half-waves).
+//   O^T = V^T P^T the probabilities, rounded to bf16, are already in B-operand layout (row =
+//                 lane, keys in registers); V^T fragments (one value column, 8 keys) are read
+//                 from the row-major LDS tile two bytes at a time (ds_read_u16).  The accumulator keeps the
+//                 lane <-> row mapping, so the online-softmax rescale is lane-local too.
+//
+// K and V tiles (32 keys each) arrive by direct-to-LDS loads, kStages tiles deep, every wavefront
+// issuing a quarter of each tile; one barrier per tile hands a landed tile to all wavefronts and
+// frees the oldest buffer.  Partial results (reference exponent, sum, unnormalised O) per span
+// are merged by a second kernel.
+#include "kernels.h"
+#include "score_common.h"
+
+namespace rfkv {
+namespace {
+
+constexpr int kStages = 4;
+
+template <int D>
+struct DShape {
+  static constexpr int kRowBytes = D * 2;
+  static constexpr int kCpr = kRowBytes / 16;            // 16-byte chunks per row
+  static constexpr int kTileBytes = 32 * kRowBytes;
+  static constexpr int kLoads = kTileBytes / 1024;        // direct-to-LDS instructions per tile
+  static constexpr int kPerWave = kLoads / 4;             // ... per wavefront
+  static constexpr int kRowStep = 64 / kCpr;              // rows per instruction
+  static constexpr int kChunks = kRowBytes / 32;          // 16-byte chunks of half a row (MFMA steps of S)
+  static constexpr int kDT = D / 32;                      // 32-column tiles of the output
+  static_assert(kPerWave >= 1, "a tile has at least four load instructions");
+};
+
+// Eight bf16 of one value column for MFMA step S of the O^T product: element e is key
+// 16 S + 8 (e / 4) + 4 hi + e % 4 of the tile (the keys whose probabilities the lane's B operand
+// holds in the same order); `addr` already points at the lane's column in key row 4 hi.
+// RB = bytes per key row.  Two column tiles at once; complete on return.  Every element is read
+// into a register of its own and the pairs are merged afterwards (16-bit loads into register
+// halves do not keep the other half on this hardware).
+template <int RB, int S>
+__device__ __forceinline__ void lds_read_vt_x2(uint4* out, const uint32_t* addr) {
+  uint32_t r[16];
+  asm volatile(
+      "ds_read_u16 %0, %16 offset:%18\n\tds_read_u16 %1, %16 offset:%19\n\t"
+      "ds_read_u16 %2, %16 offset:%20\n\tds_read_u16 %3, %16 offset:%21\n\t"
+      "ds_read_u16 %4, %16 offset:%22\n\tds_read_u16 %5, %16 offset:%23\n\t"
+      "ds_read_u16 %6, %16 offset:%24\n\tds_read_u16 %7, %16 offset:%25\n\t"
+      "ds_read_u16 %8, %17 offset:%18\n\tds_read_u16 %9, %17 offset:%19\n\t"
+      "ds_read_u16 %10, %17 offset:%20\n\tds_read_u16 %11, %17 offset:%21\n\t"
+      "ds_read_u16 %12, %17 offset:%22\n\tds_read_u16 %13, %17 offset:%23\n\t"
+      "ds_read_u16 %14, %17 offset:%24\n\tds_read_u16 %15, %17 offset:%25\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7]),
+        "=&v"(r[8]), "=&v"(r[9]), "=&v"(r[10]), "=&v"(r[11]), "=&v"(r[12]), "=&v"(r[13]), "=&v"(r[14]), "=&v"(r[15])
+      : "v"(addr[0]), "v"(addr[1]), "n"((16 * S + 0) * RB), "n"((16 * S + 1) * RB), "n"((16 * S + 2) * RB),
+        "n"((16 * S + 3) * RB), "n"((16 * S + 8) * RB), "n"((16 * S + 9) * RB), "n"((16 * S + 10) * RB),
+        "n"((16 * S + 11) * RB)
+      : "memory");
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+    out[t] = make_uint4(r[8 * t] | (r[8 * t + 1] << 16), r[8 * t + 2] | (r[8 * t + 3] << 16),
+                        r[8 * t + 4] | (r[8 * t + 5] << 16), r[8 * t + 6] | (r[8 * t + 7] << 16));
+}
+
+__device__ __forceinline__ uint32_t lds_read_b32_now(const void* p) {
+  uint32_t r;
+  asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(r) : "v"(lds_offset(p)) : "memory");
+  return r;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 v;
+  v[0] = (__bf16)lo;
+  v[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+struct DUnit {
+  int b, h;
+  int64_t row0;      // first key row of the unit in k / v (packed row or token index)
+  int len;           // keys of the unit
+};
+
+template <bool MASKED>
+__device__ __forceinline__ DUnit load_dunit(const DecodeArgs& a, int unit) {
+  DUnit u;
+  u.b = unit / a.n_kv_heads;
+  u.h = unit - u.b * a.n_kv_heads;
+  if (MASKED) {
+    u.row0 = a.cu[u.b];
+    u.len = a.cu[u.b + 1] - (int)u.row0;
+  } else {
+    u.row0 = a.offsets[unit];
+    u.len = (int)(a.offsets[unit + 1] - u.row0);
+  }
+  return u;
+}
+
+template <int D, int RTW, bool MASKED>
+__global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
+  using S = DShape<D>;
+  using KS = Shape<Bf16, D>;
+  // dynamic LDS: kStages key tiles, kStages value tiles, then (MASKED) 64 mask words per stage and wavefront
+  extern __shared__ __attribute__((aligned(1024))) unsigned char dsm[];
+  unsigned char* ksm = dsm;
+  unsigned char* vsm = dsm + kStages * S::kTileBytes;
+  uint32_t* msm = reinterpret_cast<uint32_t*>(dsm + 2 * kStages * S::kTileBytes);
+  const int bx = blockIdx.x, unit = blockIdx.y;
+  const DUnit u = load_dunit<MASKED>(a, unit);
+  const int span_begin = bx * a.span;
+  if (span_begin >= u.len) return;                       // uniform for the whole workgroup
+  const int span_end = min(u.len, span_begin + a.span);
+  const int ntiles = (span_end - span_begin + 31) >> 5;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = lane & 31, hi = lane >> 5;
+  const float c = a.c;
+  const float kNegInf = -__builtin_inff();
+
+  // ---- query fragments (B operand of S^T): ordinary loads, complete before any tile is requested
+  uint4 qf[RTW][S::kChunks];
+  {
+    const unsigned char* qbase = static_cast<const unsigned char*>(a.q);
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt) {
+      const int row = (wave * RTW + rt) * 32 + col;
+      const int rr = min(row, a.rows - 1);
+      const int j = rr / a.group, g = rr - j * a.group;
+      const int64_t off = (((int64_t)u.b * a.n_new + j) * a.n_q_heads + (int64_t)u.h * a.group + g) * D;
+      const uint4* src = reinterpret_cast<const uint4*>(qbase + off * 2 + hi * KS::kHalfBytes);
+#pragma unroll
+      for (int ch = 0; ch < S::kChunks; ++ch) qf[rt][ch] = row < a.rows ? src[ch] : make_uint4(0, 0, 0, 0);
+    }
+  }
+  // force the fragments into registers now (the loads must not drift below the first tile request)
+#pragma unroll
+  for (int rt = 0; rt < RTW; ++rt)
+#pragma unroll
+    for (int ch = 0; ch < S::kChunks; ++ch) {
+      u32x4 t = __builtin_bit_cast(u32x4, qf[rt][ch]);
+      asm volatile("" : "+v"(t));
+      qf[rt][ch] = __builtin_bit_cast(uint4, t);
+    }
+
+  const unsigned char* kunit = static_cast<const unsigned char*>(a.k) +
+                               (u.row0 * a.k_stride_tok + (int64_t)u.h * a.k_stride_head) * 2;
+  const unsigned char* vunit = static_cast<const unsigned char*>(a.v) +
+                               (u.row0 * a.v_stride_tok + (int64_t)u.h * a.v_stride_head) * 2;
+  const int64_t k_tok = a.k_stride_tok * 2, v_tok = a.v_stride_tok * 2;
+  const unsigned char* munit = MASKED ? a.mask + (int64_t)u.h * a.total_tokens + u.row0 : nullptr;
+
+  // This wavefront's share of tile `t` (tile index within the span) into stage t % kStages.
+  auto issue_tile = [&](int t) {
+    const int tile0 = span_begin + t * 32;
+    const int st = t % kStages;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));                         // recomputed per tile rather than held in registers
+    const int rl = ln / S::kCpr, cl = ln % S::kCpr;
+#pragma unroll
+    for (int jj = 0; jj < S::kPerWave; ++jj) {
+      const int j = wave * S::kPerWave + jj;
+      const int r = j * S::kRowStep + rl;                // key row within the tile
+      const int64_t key = min(tile0 + r, u.len - 1);
+      const int kchunk = cl ^ (r & ((S::kCpr < 16 ? S::kCpr : 16) - 1));
+      const int vchunk = cl ^ (((r >> 2) & 1) << 2);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kunit + key * k_tok + kchunk * 16),
+                                       (__attribute__((address_space(3))) void*)(ksm + st * S::kTileBytes + j * 1024),
+                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vunit + key * v_tok + vchunk * 16),
+                                       (__attribute__((address_space(3))) void*)(vsm + st * S::kTileBytes + j * 1024),
+                                       16, 0, 0);
+    }
+    if (MASKED) {
+      // one byte per lane: key tile0 + (lane % 32); lands as one dword per lane
+      const int64_t key = min(tile0 + (ln & 31), u.len - 1);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(munit + key),
+                                       (__attribute__((address_space(3))) void*)(msm + (st * 4 + wave) * 64), 1, 0, 0);
+    }
+  };
+  constexpr int kPerTile = 2 * S::kPerWave + (MASKED ? 1 : 0);     // loads one wavefront issues per tile
+
+  float m_run[RTW], l_run[RTW];
+  f32x16 o[RTW][S::kDT];
+#pragma unroll
+  for (int rt = 0; rt < RTW; ++rt) {
+    m_run[rt] = kNegInf;
+    l_run[rt] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < S::kDT; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) o[rt][dt][i] = 0.f;
+  }
+
+#pragma unroll
+  for (int t = 0; t < kStages - 1; ++t)
+    if (t < ntiles) issue_tile(t);
+
+  for (int t = 0; t < ntiles; ++t) {
+    // tiles t+1 .. t+kStages-2 (those that exist) are behind tile t in this wavefront's load queue
+    const int behind = min(kStages - 2, ntiles - 1 - t);
+    if (behind >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * kPerTile) : "memory");
+    else if (behind == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kPerTile) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // every wavefront's share of tile t has landed and everyone is done with tile t-1.  The bare
+    // barrier: the landed data was waited for above, and a fence here would wait for the tiles in flight
+    __builtin_amdgcn_s_barrier();
+    if (t + kStages - 1 < ntiles) issue_tile(t + kStages - 1);       // into the stage tile t-1 used
+
+    const int st = t % kStages;
+    const int tile0 = span_begin + t * 32;
+    const unsigned char* kbuf = ksm + st * S::kTileBytes;
+    const unsigned char* vbuf = vsm + st * S::kTileBytes;
+    uint4 kf[S::kChunks];
+    read_tile_frags<Bf16, D>(kf, kbuf, col, hi);
+
+    uint32_t keep_bits = 0xffffffffu;                    // bit i: key tile0 + i takes part
+    if (MASKED) {
+      const uint32_t mword = lds_read_b32_now(msm + (st * 4 + wave) * 64 + (lane & 31));
+      keep_bits = (uint32_t)__ballot((mword & 0xffu) != 0 && lane < 32);
+    }
+    if (tile0 + 32 > u.len) keep_bits &= (1u << (u.len - tile0)) - 1u;      // 1 <= len - tile0 <= 31 here
+    const bool all_in = keep_bits == 0xffffffffu;        // uniform
+
+    uint4 pf[RTW][2];                                    // probabilities, B operand of the two O^T steps
+    float alpha[RTW];
+    bool rescale = false;
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt) {
+      f32x16 acc;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+      for (int ch = 0; ch < S::kChunks; ++ch) acc = mma_chunk<Bf16>(kf[ch], qf[rt][ch], acc);
+      // value i of this lane: key tile0 + 8 (i / 4) + 4 hi + i % 4, row = lane's row
+      float x[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) x[i] = acc[i] * c;
+      if (!all_in) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int kk = (i >> 2) * 8 + hi * 4 + (i & 3);
+          if (!((keep_bits >> kk) & 1u)) x[i] = kNegInf;
+        }
+      }
+      float tmax = x[0];
+#pragma unroll
+      for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, x[i]);
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m_run[rt], tmax);
+      const float m_use = m_new == kNegInf ? 0.f : m_new;          // nothing visible yet: every term is 0
+      alpha[rt] = fast_exp2(m_run[rt] - m_use);
+      float p[16], sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        p[i] = fast_exp2(x[i] - m_use);
+        sum += p[i];
+      }
+      l_run[rt] = l_run[rt] * alpha[rt] + sum;
+      m_run[rt] = m_new;
+      rescale = rescale || alpha[rt] != 1.f;
+      pf[rt][0] = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+      pf[rt][1] = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),
+                             pack_bf16(p[14], p[15]));
+    }
+    if (__any(rescale)) {                                 // rare once the largest logits have been seen
+#pragma unroll
+      for (int rt = 0; rt < RTW; ++rt)
+#pragma unroll
+        for (int dt = 0; dt < S::kDT; ++dt)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) o[rt][dt][i] *= alpha[rt];
+    }
+
+    // O^T += V^T P^T.  Lane (col, hi) of the A operand: value column dt * 32 + col, keys as above.
+    uint32_t vaddr[S::kDT];
+    {
+      int cc = col;
+      asm volatile("" : "+v"(cc));
+      const uint32_t vb = lds_offset(vbuf) + 4 * hi * S::kRowBytes + (cc & 7) * 2;
+#pragma unroll
+      for (int dt = 0; dt < S::kDT; ++dt) vaddr[dt] = vb + (((dt * 4 + (cc >> 3)) ^ (hi << 2)) << 4);
+    }
+    uint4 vf[S::kDT];
+#pragma unroll
+    for (int dt = 0; dt < S::kDT; dt += 2) lds_read_vt_x2<S::kRowBytes, 0>(vf + dt, vaddr + dt);
+#pragma unroll
+    for (int dt = 0; dt < S::kDT; ++dt)
+#pragma unroll
+      for (int rt = 0; rt < RTW; ++rt) o[rt][dt] = mma_chunk<Bf16>(vf[dt], pf[rt][0], o[rt][dt]);
+#pragma unroll
+    for (int dt = 0; dt < S::kDT; dt += 2) lds_read_vt_x2<S::kRowBytes, 1>(vf + dt, vaddr + dt);
+#pragma unroll
+    for (int dt = 0; dt < S::kDT; ++dt)
+#pragma unroll
+      for (int rt = 0; rt < RTW; ++rt) o[rt][dt] = mma_chunk<Bf16>(vf[dt], pf[rt][1], o[rt][dt]);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  // ---- partial result of this span: (reference exponent, sum) and unnormalised O per row
+  const int64_t pbase = ((int64_t)unit * a.nsplits + bx) * a.rows_pad;
+#pragma unroll
+  for (int rt = 0; rt < RTW; ++rt) {
+    const int row = (wave * RTW + rt) * 32 + col;
+    const float l_tot = l_run[rt] + __shfl_xor(l_run[rt], 32);
+    if (hi == 0) a.part_ml[pbase + row] = make_float2(m_run[rt], l_tot);
+    float* orow = a.part_o + (pbase + row) * D;
+#pragma unroll
+    for (int dt = 0; dt < S::kDT; ++dt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        // accumulator values 4 q4 .. 4 q4 + 3: value columns dt * 32 + 8 q4 + 4 hi + 0..3
+        const float4 v4 = make_float4(o[rt][dt][4 * q4], o[rt][dt][4 * q4 + 1], o[rt][dt][4 * q4 + 2],
+                                      o[rt][dt][4 * q4 + 3]);
+        *reinterpret_cast<float4*>(orow + dt * 32 + 8 * q4 + 4 * hi) = v4;
+      }
+  }
+}
+
+// Merge of the per-span partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// One thread per (row, four value columns); grid (ceil(rows * D / 4 / 256), units).
+template <bool MASKED>
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
+  const int unit = blockIdx.y;
+  const DUnit u = load_dunit<MASKED>(a, unit);
+  const int D = a.head_dim;
+  const int quads = D / 4;
+  const int item = blockIdx.x * 256 + threadIdx.x;
+  const int row = item / quads, qd = item - row * quads;
+  if (row >= a.rows) return;
+  const int j = row / a.group, g = row - j * a.group;
+  float* dst = a.out + ((((int64_t)u.b * a.n_new + j) * a.n_q_heads + (int64_t)u.h * a.group + g) * D + qd * 4);
+  const int nsp = (u.len + a.span - 1) / a.span;
+  const int64_t pbase = (int64_t)unit * a.nsplits * a.rows_pad;
+  float M = -__builtin_inff();
+  for (int s = 0; s < nsp; ++s) M = fmaxf(M, a.part_ml[pbase + (int64_t)s * a.rows_pad + row].x);
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float den = 0.f;
+  if (M != -__builtin_inff()) {
+    for (int s = 0; s < nsp; ++s) {
+      const float2 ml = a.part_ml[pbase + (int64_t)s * a.rows_pad + row];
+      const float w = fast_exp2(ml.x - M);
+      const float4 o4 = *reinterpret_cast<const float4*>(a.part_o + (pbase + (int64_t)s * a.rows_pad + row) * D + qd * 4);
+      acc.x += w * o4.x;
+      acc.y += w * o4.y;
+      acc.z += w * o4.z;
+      acc.w += w * o4.w;
+      den += w * ml.y;
+    }
+  }
+  const float inv = den > 0.f ? 1.f / den : 0.f;          // a unit without visible keys gives zeros
+  *reinterpret_cast<float4*>(dst) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+}
+
+template <int D, int RTW, bool MASKED>
+hipError_t launch_attn(const DecodeArgs& a, int units, hipStream_t stream) {
+  const size_t lds = 2 * kStages * DShape<D>::kTileBytes + (MASKED ? kStages * 4 * 64 * sizeof(uint32_t) : 0);
+  const hipError_t e = allow_lds(decode_attn_kernel<D, RTW, MASKED>, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((decode_attn_kernel<D, RTW, MASKED>), dim3(a.nsplits, units), dim3(256), lds, stream, a);
+  return hipGetLastError();
+}
+
+template <int D, bool MASKED>
+hipError_t launch_typed(const DecodeArgs& a, int units, hipStream_t stream) {
+  const dim3 block(256);
+  hipError_t e = a.rows_pad <= 128 ? launch_attn<D, 1, MASKED>(a, units, stream) : launch_attn<D, 2, MASKED>(a, units, stream);
+  if (e != hipSuccess) return e;
+  const int items = a.rows * (D / 4);
+  hipLaunchKernelGGL(decode_merge_kernel<MASKED>, dim3((items + 255) / 256, units), block, 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_decode_attention(const DecodeArgs& a, int units, bool masked, hipStream_t stream) {
+  if (units == 0 || a.rows == 0) return hipSuccess;
+  if (a.head_dim == 128) return masked ? launch_typed<128, true>(a, units, stream) : launch_typed<128, false>(a, units, stream);
+  if (a.head_dim == 64) return masked ? launch_typed<64, true>(a, units, stream) : launch_typed<64, false>(a, units, stream);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace rfkv

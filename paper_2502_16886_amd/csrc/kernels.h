@@ -87,6 +87,24 @@ struct CompactArgs {
   int32_t n_kv_heads, units, row_bytes, source;
 };
 
+// Attention of new queries over the compacted cache (offsets != null) or over the full cache
+// with a keep mask (cu, mask != null).
+struct DecodeArgs {
+  const void* q;            // [B, n_new, Hq, d] bf16
+  const void* k;
+  const void* v;
+  const int64_t* offsets;   // compacted: first row of every unit, [units + 1]
+  const int32_t* cu;        // masked: cu_seqlens
+  const uint8_t* mask;      // masked: [Hkv][N], non-zero = retained
+  float* out;               // [B, n_new, Hq, d]
+  float* part_o;            // [units][nsplits][rows_pad][d]  unnormalised partial outputs
+  float2* part_ml;          // [units][nsplits][rows_pad]     (reference exponent, sum)
+  int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;   // elements
+  int64_t total_tokens;
+  int32_t n_q_heads, n_kv_heads, group, n_new, rows, rows_pad, span, nsplits, head_dim;
+  float c;                  // softmax scale * log2(e)
+};
+
 // Optional per-kernel timing: events recorded on the launch stream between kernels.
 enum KernelId { kKernelStats = 0, kKernelMerge, kKernelReduce, kKernelSelect, kKernelCompact, kNumKernels };
 struct Marks {
@@ -99,5 +117,6 @@ hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStr
                         const Marks* marks = nullptr);
 hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t stream);
 hipError_t launch_compact(const Geometry& g, const CompactArgs& a, hipStream_t stream);
+hipError_t launch_decode_attention(const DecodeArgs& a, int units, bool masked, hipStream_t stream);
 
 }  // namespace rfkv

@@ -1,0 +1,165 @@
+"""GPU parity of the decode attention over the compacted ragged cache (rfkv_decode_attention) and of
+its masked full-cache baseline (rfkv_masked_attention) against the float64 oracle.
+
+Tolerance.  The kernels keep the softmax in fp32 and round each probability to bf16 before the
+value product (the values themselves are bf16).  Rounding a probability changes it by at most
+2^-8 relative (bf16 keeps 8 significant bits), so an output element can move by at most
+2^-8 * sum_i p_i |v_i| -- a quantity the
+oracle itself provides (the same attention applied to |V|).  The tests allow that bound (plus 5 %
+and 1e-5 for the fp32 arithmetic); measured errors are several times smaller.
+"""
+import numpy as np
+import pytest
+
+import rfkv_harness as H
+from oracle import refreekv_oracle as O
+from paper_2502_16886_amd import binding as B
+from paper_2502_16886_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+P_ROUNDING = 2.0 ** -8        # half a unit in the last place of an 8-bit significand
+
+
+def _bound(q_new, k_rows, v_rows, offs_or_mask, Hq, Hkv, masked, cu=None):
+    """2^-8 * attention(|V|): the most an output can move when every probability is rounded to bf16."""
+    if masked:
+        return P_ROUNDING * O.oracle_masked_attention(q_new, k_rows, np.abs(v_rows), cu, offs_or_mask, Hq, Hkv)
+    return P_ROUNDING * O.oracle_decode_attention(q_new, k_rows, np.abs(v_rows), offs_or_mask, Hq, Hkv)
+
+
+def _check(got, ref, bound, what):
+    err = np.abs(got.astype(np.float64) - ref)
+    tol = 1.05 * bound + 1e-5
+    worst = float((err / tol).max()) if err.size else 0.0
+    assert worst <= 1.0, f"{what}: error reaches {worst:.2f} of the bf16-probability bound (max abs err {err.max():.3e})"
+    return worst
+
+
+def _run_decode(dl, q_new_bits, n_new):
+    import torch
+    c = dl.layer.cfg
+    q = H.to_device(q_new_bits, c.dtype)
+    out = torch.full((dl.batch, n_new, c.n_q_heads, c.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+    ws_bytes = B.rfkv_decode_workspace_bytes(dl.params, n_new, dl.max_len)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    B.rfkv_decode_attention(dl.params, q, n_new, dl.buf.k_out, dl.buf.v_out, dl.cu_host, dl.buf.out_offsets, out, ws,
+                            ws_bytes)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _run_masked(dl, q_new_bits, n_new, keep_mask):
+    import torch
+    c = dl.layer.cfg
+    q = H.to_device(q_new_bits, c.dtype)
+    out = torch.full((dl.batch, n_new, c.n_q_heads, c.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+    ws_bytes = B.rfkv_decode_workspace_bytes(dl.params, n_new, dl.max_len)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+    mask = torch.from_numpy(np.ascontiguousarray(keep_mask.astype(np.uint8))).cuda()
+    B.rfkv_masked_attention(dl.params, q, n_new, dl.k, dl.v, dl.cu_host, dl.cu_dev, mask, out, ws, ws_bytes)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
+def _keep_mask(layer, res):
+    """[Hkv, N] bool from the GPU's own retained index lists."""
+    Hkv = layer.cfg.n_kv_heads
+    N = int(layer.cu_seqlens[-1])
+    keep = np.zeros((Hkv, N), bool)
+    for u, b, h, s, e in H.unit_slices(layer):
+        o, cnt = int(res["out_offsets"][u]), int(res["kept"][u])
+        keep[h, s + res["idx"][o:o + cnt]] = True
+    return keep
+
+
+SMALL = [
+    # (Hq, Hkv, d, lens, n_new, threshold)
+    (8, 2, 128, (300, 33, 1, 77), 5, 0.05),
+    (4, 4, 64, (513, 64), 64, 0.02),            # G = 1, 64 rows
+    (28, 4, 128, (1000,), 36, 0.01),            # G = 7: 252 rows, two row tiles per wavefront
+    (32, 8, 128, (2049, 5), 64, 0.3),           # 256 rows, harsh threshold (short caches)
+    (8, 8, 64, (31, 32, 33), 1, 0.0),           # T = 0: the whole cache; one query
+]
+
+
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: f"Hq{c[0]}_Hkv{c[1]}_d{c[2]}_new{c[4]}")
+@pytest.mark.parametrize("rank_mode", [B.RANK_POSITION, B.RANK_SCORE], ids=["position", "score"])
+def test_decode_small_shapes(case, rank_mode):
+    Hq, Hkv, d, lens, n_new, T = case
+    cfg = W.Config("t", 1, Hq, Hkv, d, 16, "bf16", batch=len(lens), context=max(lens), threshold=T)
+    layer = W.make_layer(7, 0, cfg=cfg, lengths=lens)
+    qn = W.make_new_queries(7, 0, n_new=n_new, cfg=cfg, lengths=lens)
+    dl = H.DeviceLayer(layer, rank_mode=rank_mode)
+    dl.compress()
+    res = dl.results()
+    got = _run_decode(dl, qn, n_new)
+    qf = W.to_f64(qn, "bf16")
+    k_c, v_c = W.to_f64(res["k_out"], "bf16"), W.to_f64(res["v_out"], "bf16")
+    ref = O.oracle_decode_attention(qf, k_c, v_c, res["out_offsets"], Hq, Hkv)
+    bound = _bound(qf, k_c, v_c, res["out_offsets"], Hq, Hkv, masked=False)
+    assert np.isfinite(got).all()
+    _check(got, ref, bound, "compacted")
+    # the masked baseline over the full cache gives the same attention
+    keep = _keep_mask(layer, res)
+    got_m = _run_masked(dl, qn, n_new, keep)
+    assert np.isfinite(got_m).all()
+    _check(got_m, ref, bound, "masked")
+
+
+def test_decode_empty_sequences_and_zero_queries():
+    cfg = W.Config("t", 1, 8, 2, 128, 16, "bf16", batch=3, context=64)
+    lens = (0, 40, 0)
+    layer = W.make_layer(7, 1, cfg=cfg, lengths=lens)
+    qn = W.make_new_queries(7, 1, n_new=3, cfg=cfg, lengths=lens)
+    dl = H.DeviceLayer(layer)
+    dl.compress()
+    res = dl.results()
+    got = _run_decode(dl, qn, 3)
+    assert np.all(got[0] == 0) and np.all(got[2] == 0) and np.abs(got[1]).max() > 0
+    ref = O.oracle_decode_attention(W.to_f64(qn, "bf16"), W.to_f64(res["k_out"], "bf16"), W.to_f64(res["v_out"], "bf16"),
+                                    res["out_offsets"], 8, 2)
+    assert np.abs(got - ref).max() < 2e-2
+    # n_new = 0 is a no-op
+    import torch
+    out = torch.empty(0, device="cuda")
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    assert B.rfkv_decode_attention(dl.params, dl.q, 0, dl.buf.k_out, dl.buf.v_out, dl.cu_host, dl.buf.out_offsets,
+                                   out, ws, 16) == 0
+
+
+def test_decode_rejects_what_it_does_not_cover():
+    import torch
+    p32 = B.make_params(1, 8, 2, 64, 16, "fp32")
+    assert B.rfkv_decode_workspace_bytes(p32, 4, 100) == 0
+    p = B.make_params(1, 32, 8, 128, 32, "bf16")
+    assert B.rfkv_decode_workspace_bytes(p, 65, 100) == 0           # 65 * 4 rows > 256
+    cu = np.array([0, 100], np.int32)
+    t = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    st = B.rfkv_decode_attention(p, t, 65, t, t, cu, t, t, t, 4096, check=False)
+    assert st == B.RFKV_UNSUPPORTED
+    st = B.rfkv_decode_attention(p, t, 4, t, t, cu, t, t, t, 16, check=False)
+    assert st == B.RFKV_WORKSPACE_TOO_SMALL
+
+
+def test_decode_full_size_config4():
+    """Config 4 (131072 tokens, 64 new queries): every output of the compacted path against the
+    oracle, the masked baseline on the same inputs, in the launch configuration bench.py times."""
+    layer = W.make_layer(4, 0)
+    cfg = layer.cfg
+    n_new = 64
+    qn = W.make_new_queries(4, 0, n_new=n_new)
+    dl = H.DeviceLayer(layer, kv_layout="head_major")
+    dl.compress()
+    res = dl.results()
+    got = _run_decode(dl, qn, n_new)
+    qf = W.to_f64(qn, "bf16")
+    k_c, v_c = W.to_f64(res["k_out"], "bf16"), W.to_f64(res["v_out"], "bf16")
+    ref = O.oracle_decode_attention(qf, k_c, v_c, res["out_offsets"], cfg.n_q_heads, cfg.n_kv_heads)
+    bound = _bound(qf, k_c, v_c, res["out_offsets"], cfg.n_q_heads, cfg.n_kv_heads, masked=False)
+    w1 = _check(got, ref, bound, "compacted")
+    keep = _keep_mask(layer, res)
+    got_m = _run_masked(dl, qn, n_new, keep)
+    w2 = _check(got_m, ref, bound, "masked")
+    print(f"config 4 decode: retained {res['kept'].sum() / (8 * 131072):.3f}, worst error / bound: "
+          f"compacted {w1:.2f}, masked {w2:.2f}")
