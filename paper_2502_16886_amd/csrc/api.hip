@@ -298,9 +298,9 @@ rfkv_status rfkv_compact(const rfkv_params* params, const void* k, const void* v
   return device_status(launch_compact(g, c, static_cast<hipStream_t>(stream)));
 }
 
-// Launch geometry of the decode attention: enough spans to give every CU a workgroup, none
-// shorter than 128 keys.
-static void decode_geometry(const rfkv_params* p, int32_t n_new, int32_t max_len, DecodeArgs* a) {
+// Launch geometry of the decode attention: one work item per workgroup the chip holds at once
+// (256 CUs, one workgroup each), plus one spare slot per unit for the planner's rounding.
+static void decode_geometry(const rfkv_params* p, int32_t n_new, DecodeArgs* a) {
   const int units = p->batch * p->n_kv_heads;
   a->n_q_heads = p->n_q_heads;
   a->n_kv_heads = p->n_kv_heads;
@@ -309,20 +309,24 @@ static void decode_geometry(const rfkv_params* p, int32_t n_new, int32_t max_len
   a->rows = n_new * a->group;
   a->rows_pad = a->rows <= 128 ? 128 : 256;
   a->head_dim = p->head_dim;
-  int splits = units > 0 ? (256 + units - 1) / units : 1;
-  const int most = (max_len + 127) / 128;
-  if (splits > most) splits = most;
-  if (splits < 1) splits = 1;
-  a->span = ((max_len + splits - 1) / splits + 31) / 32 * 32;
-  if (a->span < 32) a->span = 32;
-  a->nsplits = (max_len + a->span - 1) / a->span;
-  if (a->nsplits < 1) a->nsplits = 1;
+  a->target_items = a->rows_pad <= 128 ? 512 : 256;
+  a->max_items = a->target_items + units;
   a->c = scale_times_log2e(p);
 }
 
-static size_t decode_ws_bytes(const rfkv_params* p, const DecodeArgs& a) {
-  const size_t slots = (size_t)p->batch * p->n_kv_heads * a.nsplits * a.rows_pad;
-  return slots * a.head_dim * sizeof(float) + slots * sizeof(float2) + 256;
+struct DecodeWs {
+  size_t part_o, part_ml, items, item_begin, bytes;
+};
+static DecodeWs decode_ws(const rfkv_params* p, const DecodeArgs& a) {
+  const size_t units = (size_t)p->batch * p->n_kv_heads;
+  const size_t slots = (size_t)a.max_items * a.rows_pad;
+  DecodeWs w;
+  w.part_o = 0;
+  w.part_ml = w.part_o + slots * a.head_dim * sizeof(float);
+  w.items = w.part_ml + slots * sizeof(float2);
+  w.item_begin = w.items + (size_t)a.max_items * sizeof(int4);
+  w.bytes = (w.item_begin + (units + 1) * sizeof(int32_t) + 255) / 256 * 256;
+  return w;
 }
 
 static rfkv_status decode_check(const rfkv_params* p, int32_t n_new) {
@@ -357,16 +361,19 @@ static rfkv_status decode_impl(const rfkv_params* params, const void* q_new, int
   }
   if (max_len > 0 && (!aligned16(k) || !aligned16(v))) return RFKV_INVALID_ARG;
   DecodeArgs a{};
-  decode_geometry(params, n_new, max_len, &a);
-  if (ws_bytes < decode_ws_bytes(params, a)) return RFKV_WORKSPACE_TOO_SMALL;
+  decode_geometry(params, n_new, &a);
+  const DecodeWs w = decode_ws(params, a);
+  if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
   a.q = q_new;
   a.k = k;
   a.v = v;
   a.out = out;
   a.total_tokens = cu_host[params->batch];
-  const size_t slots = (size_t)params->batch * params->n_kv_heads * a.nsplits * a.rows_pad;
-  a.part_o = static_cast<float*>(ws);
-  a.part_ml = reinterpret_cast<float2*>(static_cast<unsigned char*>(ws) + slots * a.head_dim * sizeof(float));
+  unsigned char* base = static_cast<unsigned char*>(ws);
+  a.part_o = reinterpret_cast<float*>(base + w.part_o);
+  a.part_ml = reinterpret_cast<float2*>(base + w.part_ml);
+  a.items = reinterpret_cast<int4*>(base + w.items);
+  a.item_begin = reinterpret_cast<int32_t*>(base + w.item_begin);
   if (masked) {
     a.cu = cu_dev;
     a.mask = keep_mask;
@@ -386,8 +393,8 @@ static rfkv_status decode_impl(const rfkv_params* params, const void* q_new, int
 size_t rfkv_decode_workspace_bytes(const rfkv_params* params, int32_t n_new, int32_t max_seqlen) {
   if (decode_check(params, n_new) != RFKV_OK || max_seqlen < 0) return 0;
   DecodeArgs a{};
-  decode_geometry(params, n_new, max_seqlen, &a);
-  return decode_ws_bytes(params, a);
+  decode_geometry(params, n_new, &a);
+  return decode_ws(params, a).bytes;
 }
 
 rfkv_status rfkv_decode_attention(const rfkv_params* params, const void* q_new, int32_t n_new, const void* k_c,

@@ -2,21 +2,24 @@
 // uncompressed cache with the evicted positions masked (the consumer of Alg. 1's compressed K / V;
 // Sec. 4.3 compares the two costs).  bf16 storage, fp32 softmax and accumulation, fp32 output.
 //
-// One workgroup (4 wavefronts) takes one span of keys of one unit (sequence, KV head) and all
-// M = n_new * G query rows of that KV head (row = j * G + g), 32 * RTW rows per wavefront:
+// The kept counts differ from unit to unit and are known on the device only, so a one-workgroup
+// planning kernel first cuts every unit's keys into work items of nearly equal length (about as
+// many items as the launch has workgroups to keep every CU busy once).  One workgroup (4
+// wavefronts) then takes one item -- a contiguous range of keys of one unit (sequence, KV head) --
+// and all M = n_new * G query rows of that KV head (row = j * G + g), 32 * RTW rows per wavefront:
 //
 //   S^T = K Q^T   32x32x16 bf16 MFMA, keys along M, rows along N: a lane owns one query row and
 //                 16 of the tile's 32 keys, so the softmax statistics are in-lane (plus one
 //                 exchange between the two half-waves).
 //   O^T = V^T P^T the probabilities, rounded to bf16, are already in B-operand layout (row =
 //                 lane, keys in registers); V^T fragments (one value column, 8 keys) are read
-//                 from the row-major LDS tile two bytes at a time (ds_read_u16).  The accumulator keeps the
+//                 from the row-major LDS tile by the LDS transpose read (ds_read_b64_tr_b16).  The accumulator keeps the
 //                 lane <-> row mapping, so the online-softmax rescale is lane-local too.
 //
 // K and V tiles (32 keys each) arrive by direct-to-LDS loads, kStages tiles deep, every wavefront
 // issuing a quarter of each tile; one barrier per tile hands a landed tile to all wavefronts and
-// frees the oldest buffer.  Partial results (reference exponent, sum, unnormalised O) per span
-// are merged by a second kernel.
+// frees the oldest buffer.  Partial results (reference exponent, sum, unnormalised O) per item
+// are merged by a last kernel.
 #include "kernels.h"
 #include "score_common.h"
 
@@ -38,35 +41,43 @@ struct DShape {
   static_assert(kPerWave >= 1, "a tile has at least four load instructions");
 };
 
-// Eight bf16 of one value column for MFMA step S of the O^T product: element e is key
-// 16 S + 8 (e / 4) + 4 hi + e % 4 of the tile (the keys whose probabilities the lane's B operand
-// holds in the same order); `addr` already points at the lane's column in key row 4 hi.
-// RB = bytes per key row.  Two column tiles at once; complete on return.  Every element is read
-// into a register of its own and the pairs are merged afterwards (16-bit loads into register
-// halves do not keep the other half on this hardware).
+// V^T fragments for MFMA step S of the O^T product, by the LDS transpose read: element e of lane
+// (col, hi) is key 16 S + 8 (e / 4) + 4 hi + e % 4 of the tile (the keys whose probabilities the
+// lane's B operand holds in the same order), value column dt * 32 + col.  One ds_read_b64_tr_b16
+// hands a group of 16 lanes a transposed 4 keys x 16 columns block: lane j of the group points at
+// the 8 bytes (key j / 4, columns 4 (j % 4) ..), lane i receives column i of the four keys.  Two
+// reads (keys +0..3 and +8..11) make one fragment.  `addr[dt]` is the lane's pointer for column
+// tile dt at key row 4 hi; RB = bytes per key row.  Complete on return.
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+template <int RB, int S>
+__device__ __forceinline__ void lds_read_vt_x4(uint4* out, const uint32_t* addr) {
+  u32x2 a0, b0, a1, b1, a2, b2, a3, b3;
+  asm volatile(
+      "ds_read_b64_tr_b16 %0, %8 offset:%12\n\tds_read_b64_tr_b16 %1, %8 offset:%13\n\t"
+      "ds_read_b64_tr_b16 %2, %9 offset:%12\n\tds_read_b64_tr_b16 %3, %9 offset:%13\n\t"
+      "ds_read_b64_tr_b16 %4, %10 offset:%12\n\tds_read_b64_tr_b16 %5, %10 offset:%13\n\t"
+      "ds_read_b64_tr_b16 %6, %11 offset:%12\n\tds_read_b64_tr_b16 %7, %11 offset:%13\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(a0), "=&v"(b0), "=&v"(a1), "=&v"(b1), "=&v"(a2), "=&v"(b2), "=&v"(a3), "=&v"(b3)
+      : "v"(addr[0]), "v"(addr[1]), "v"(addr[2]), "v"(addr[3]), "n"((16 * S) * RB), "n"((16 * S + 8) * RB)
+      : "memory");
+  out[0] = make_uint4(a0[0], a0[1], b0[0], b0[1]);
+  out[1] = make_uint4(a1[0], a1[1], b1[0], b1[1]);
+  out[2] = make_uint4(a2[0], a2[1], b2[0], b2[1]);
+  out[3] = make_uint4(a3[0], a3[1], b3[0], b3[1]);
+}
 template <int RB, int S>
 __device__ __forceinline__ void lds_read_vt_x2(uint4* out, const uint32_t* addr) {
-  uint32_t r[16];
+  u32x2 a0, b0, a1, b1;
   asm volatile(
-      "ds_read_u16 %0, %16 offset:%18\n\tds_read_u16 %1, %16 offset:%19\n\t"
-      "ds_read_u16 %2, %16 offset:%20\n\tds_read_u16 %3, %16 offset:%21\n\t"
-      "ds_read_u16 %4, %16 offset:%22\n\tds_read_u16 %5, %16 offset:%23\n\t"
-      "ds_read_u16 %6, %16 offset:%24\n\tds_read_u16 %7, %16 offset:%25\n\t"
-      "ds_read_u16 %8, %17 offset:%18\n\tds_read_u16 %9, %17 offset:%19\n\t"
-      "ds_read_u16 %10, %17 offset:%20\n\tds_read_u16 %11, %17 offset:%21\n\t"
-      "ds_read_u16 %12, %17 offset:%22\n\tds_read_u16 %13, %17 offset:%23\n\t"
-      "ds_read_u16 %14, %17 offset:%24\n\tds_read_u16 %15, %17 offset:%25\n\t"
+      "ds_read_b64_tr_b16 %0, %4 offset:%6\n\tds_read_b64_tr_b16 %1, %4 offset:%7\n\t"
+      "ds_read_b64_tr_b16 %2, %5 offset:%6\n\tds_read_b64_tr_b16 %3, %5 offset:%7\n\t"
       "s_waitcnt lgkmcnt(0)"
-      : "=&v"(r[0]), "=&v"(r[1]), "=&v"(r[2]), "=&v"(r[3]), "=&v"(r[4]), "=&v"(r[5]), "=&v"(r[6]), "=&v"(r[7]),
-        "=&v"(r[8]), "=&v"(r[9]), "=&v"(r[10]), "=&v"(r[11]), "=&v"(r[12]), "=&v"(r[13]), "=&v"(r[14]), "=&v"(r[15])
-      : "v"(addr[0]), "v"(addr[1]), "n"((16 * S + 0) * RB), "n"((16 * S + 1) * RB), "n"((16 * S + 2) * RB),
-        "n"((16 * S + 3) * RB), "n"((16 * S + 8) * RB), "n"((16 * S + 9) * RB), "n"((16 * S + 10) * RB),
-        "n"((16 * S + 11) * RB)
+      : "=&v"(a0), "=&v"(b0), "=&v"(a1), "=&v"(b1)
+      : "v"(addr[0]), "v"(addr[1]), "n"((16 * S) * RB), "n"((16 * S + 8) * RB)
       : "memory");
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-    out[t] = make_uint4(r[8 * t] | (r[8 * t + 1] << 16), r[8 * t + 2] | (r[8 * t + 3] << 16),
-                        r[8 * t + 4] | (r[8 * t + 5] << 16), r[8 * t + 6] | (r[8 * t + 7] << 16));
+  out[0] = make_uint4(a0[0], a0[1], b0[0], b0[1]);
+  out[1] = make_uint4(a1[0], a1[1], b1[0], b1[1]);
 }
 
 __device__ __forceinline__ uint32_t lds_read_b32_now(const void* p) {
@@ -104,8 +115,65 @@ __device__ __forceinline__ DUnit load_dunit(const DecodeArgs& a, int unit) {
   return u;
 }
 
+// Work items: item_begin[u] .. item_begin[u + 1] are unit u's; items[i] = {unit, first key, end key, -}.
+// Keys are handed out in chunks of kChunkKeys; every item gets at most C chunks, C chosen so that
+// the items number about `a.target_items` (never more than target_items + units, the launch's grid).
+constexpr int kChunkKeys = 256;
+
+template <bool MASKED>
+__global__ __launch_bounds__(1024) void decode_plan_kernel(DecodeArgs a, int units) {
+  __shared__ long long sh_tot[16];
+  __shared__ int sh_scan[17];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // total chunks
+  long long mine = 0;
+  for (int u = tid; u < units; u += 1024) mine += (load_dunit<MASKED>(a, u).len + kChunkKeys - 1) / kChunkKeys;
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d);
+  if (lane == 0) sh_tot[wave] = mine;
+  __syncthreads();
+  long long total = 0;
+  for (int w = 0; w < 16; ++w) total += sh_tot[w];
+  const int C = (int)max(1ll, (total + a.target_items - 1) / a.target_items);
+  // items per unit, exclusive prefix over units in batches of 1024
+  int carry = 0;
+  for (int base = 0; base < units; base += 1024) {
+    const int u = base + tid;
+    int len = 0, cnt = 0;
+    if (u < units) {
+      len = load_dunit<MASKED>(a, u).len;
+      const int chunks = (len + kChunkKeys - 1) / kChunkKeys;
+      cnt = (chunks + C - 1) / C;
+    }
+    int inc = cnt;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(inc, d);
+      if (lane >= d) inc += o;
+    }
+    __syncthreads();
+    if (lane == 63) sh_scan[wave] = inc;
+    __syncthreads();
+    int off = carry, tot = 0;
+    for (int w = 0; w < 16; ++w) {
+      if (w < wave) off += sh_scan[w];
+      tot += sh_scan[w];
+    }
+    const int first = off + inc - cnt;
+    if (u < units) {
+      a.item_begin[u] = first;
+      for (int i = 0; i < cnt; ++i)
+        a.items[first + i] = make_int4(u, i * C * kChunkKeys, min(len, (i + 1) * C * kChunkKeys), 0);
+    }
+    carry += tot;
+  }
+  if (tid == 0) a.item_begin[units] = carry;
+  // unused grid slots
+  for (int i = carry + tid; i < a.max_items; i += 1024) a.items[i] = make_int4(-1, 0, 0, 0);
+}
+
 template <int D, int RTW, bool MASKED>
-__global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(256, RTW == 1 ? 2 : 1) void decode_attn_kernel(DecodeArgs a) {
   using S = DShape<D>;
   using KS = Shape<Bf16, D>;
   // dynamic LDS: kStages key tiles, kStages value tiles, then (MASKED) 64 mask words per stage and wavefront
@@ -113,11 +181,12 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
   unsigned char* ksm = dsm;
   unsigned char* vsm = dsm + kStages * S::kTileBytes;
   uint32_t* msm = reinterpret_cast<uint32_t*>(dsm + 2 * kStages * S::kTileBytes);
-  const int bx = blockIdx.x, unit = blockIdx.y;
+  const int bx = blockIdx.x;
+  const int4 item = a.items[bx];
+  const int unit = item.x;
+  if (unit < 0) return;                                  // uniform for the whole workgroup
   const DUnit u = load_dunit<MASKED>(a, unit);
-  const int span_begin = bx * a.span;
-  if (span_begin >= u.len) return;                       // uniform for the whole workgroup
-  const int span_end = min(u.len, span_begin + a.span);
+  const int span_begin = item.y, span_end = item.z;      // 0 <= begin < end <= u.len
   const int ntiles = (span_end - span_begin + 31) >> 5;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -158,29 +227,53 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
   const unsigned char* munit = MASKED ? a.mask + (int64_t)u.h * a.total_tokens + u.row0 : nullptr;
 
   // This wavefront's share of tile `t` (tile index within the span) into stage t % kStages.
-  auto issue_tile = [&](int t) {
-    const int tile0 = span_begin + t * 32;
-    const int st = t % kStages;
-    int ln = lane;
-    asm volatile("" : "+v"(ln));                         // recomputed per tile rather than held in registers
-    const int rl = ln / S::kCpr, cl = ln % S::kCpr;
+  // per-lane parts of the tile addresses: instruction jj of this wavefront fetches row r_jj of the
+  // tile, K chunk cl ^ (r & kSw), V chunk cl ^ (bit 2 of r) << 2 (the layouts the fragment reads expect)
+  const int rl = lane / S::kCpr, cl = lane % S::kCpr;
+  uint32_t koff[S::kPerWave], voff[S::kPerWave];
 #pragma unroll
-    for (int jj = 0; jj < S::kPerWave; ++jj) {
-      const int j = wave * S::kPerWave + jj;
-      const int r = j * S::kRowStep + rl;                // key row within the tile
-      const int64_t key = min(tile0 + r, u.len - 1);
-      const int kchunk = cl ^ (r & ((S::kCpr < 16 ? S::kCpr : 16) - 1));
-      const int vchunk = cl ^ (((r >> 2) & 1) << 2);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kunit + key * k_tok + kchunk * 16),
-                                       (__attribute__((address_space(3))) void*)(ksm + st * S::kTileBytes + j * 1024),
-                                       16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vunit + key * v_tok + vchunk * 16),
-                                       (__attribute__((address_space(3))) void*)(vsm + st * S::kTileBytes + j * 1024),
-                                       16, 0, 0);
+  for (int jj = 0; jj < S::kPerWave; ++jj) {
+    const int r = (wave * S::kPerWave + jj) * S::kRowStep + rl;
+    koff[jj] = (uint32_t)(r * k_tok) + (uint32_t)((cl ^ (r & ((S::kCpr < 16 ? S::kCpr : 16) - 1))) << 4);
+    voff[jj] = (uint32_t)(r * v_tok) + (uint32_t)((cl ^ (((r >> 2) & 1) << 2)) << 4);
+  }
+  auto issue_tile = [&](int t) {
+    const int tile0 = __builtin_amdgcn_readfirstlane(span_begin + t * 32);
+    const int st = t % kStages;
+    if (tile0 + 32 <= u.len) {
+      // interior tile: a scalar base per tile plus the per-lane offsets
+      const unsigned char* kb = kunit + (int64_t)tile0 * k_tok;
+      const unsigned char* vb = vunit + (int64_t)tile0 * v_tok;
+#pragma unroll
+      for (int jj = 0; jj < S::kPerWave; ++jj) {
+        const int j = wave * S::kPerWave + jj;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + koff[jj]),
+                                         (__attribute__((address_space(3))) void*)(ksm + st * S::kTileBytes + j * 1024),
+                                         16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vb + voff[jj]),
+                                         (__attribute__((address_space(3))) void*)(vsm + st * S::kTileBytes + j * 1024),
+                                         16, 0, 0);
+      }
+    } else {
+      // the unit's last tile: rows past the end repeat the last key (masked out below)
+#pragma unroll
+      for (int jj = 0; jj < S::kPerWave; ++jj) {
+        const int j = wave * S::kPerWave + jj;
+        const int r = j * S::kRowStep + rl;
+        const int64_t key = min(tile0 + r, u.len - 1);
+        const int kchunk = cl ^ (r & ((S::kCpr < 16 ? S::kCpr : 16) - 1));
+        const int vchunk = cl ^ (((r >> 2) & 1) << 2);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kunit + key * k_tok + kchunk * 16),
+                                         (__attribute__((address_space(3))) void*)(ksm + st * S::kTileBytes + j * 1024),
+                                         16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vunit + key * v_tok + vchunk * 16),
+                                         (__attribute__((address_space(3))) void*)(vsm + st * S::kTileBytes + j * 1024),
+                                         16, 0, 0);
+      }
     }
     if (MASKED) {
       // one byte per lane: key tile0 + (lane % 32); lands as one dword per lane
-      const int64_t key = min(tile0 + (ln & 31), u.len - 1);
+      const int64_t key = min(tile0 + (lane & 31), u.len - 1);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(munit + key),
                                        (__attribute__((address_space(3))) void*)(msm + (st * 4 + wave) * 64), 1, 0, 0);
     }
@@ -232,17 +325,22 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
     uint4 pf[RTW][2];                                    // probabilities, B operand of the two O^T steps
     float alpha[RTW];
     bool rescale = false;
+    // the MFMA chains of all row tiles interleaved, so that none waits for its own previous step
+    f32x16 sacc[RTW];
+#pragma unroll
+    for (int rt = 0; rt < RTW; ++rt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[rt][i] = 0.f;
+#pragma unroll
+    for (int ch = 0; ch < S::kChunks; ++ch)
+#pragma unroll
+      for (int rt = 0; rt < RTW; ++rt) sacc[rt] = mma_chunk<Bf16>(kf[ch], qf[rt][ch], sacc[rt]);
 #pragma unroll
     for (int rt = 0; rt < RTW; ++rt) {
-      f32x16 acc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-      for (int ch = 0; ch < S::kChunks; ++ch) acc = mma_chunk<Bf16>(kf[ch], qf[rt][ch], acc);
       // value i of this lane: key tile0 + 8 (i / 4) + 4 hi + i % 4, row = lane's row
       float x[16];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) x[i] = acc[i] * c;
+      for (int i = 0; i < 16; ++i) x[i] = sacc[rt][i];
       if (!all_in) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -253,14 +351,14 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
       float tmax = x[0];
 #pragma unroll
       for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, x[i]);
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * c;                 // c > 0: scaling commutes with the maximum
       const float m_new = fmaxf(m_run[rt], tmax);
       const float m_use = m_new == kNegInf ? 0.f : m_new;          // nothing visible yet: every term is 0
       alpha[rt] = fast_exp2(m_run[rt] - m_use);
       float p[16], sum = 0.f;
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        p[i] = fast_exp2(x[i] - m_use);
+        p[i] = fast_exp2(__builtin_fmaf(x[i], c, -m_use));
         sum += p[i];
       }
       l_run[rt] = l_run[rt] * alpha[rt] + sum;
@@ -282,21 +380,24 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
     // O^T += V^T P^T.  Lane (col, hi) of the A operand: value column dt * 32 + col, keys as above.
     uint32_t vaddr[S::kDT];
     {
-      int cc = col;
-      asm volatile("" : "+v"(cc));
-      const uint32_t vb = lds_offset(vbuf) + 4 * hi * S::kRowBytes + (cc & 7) * 2;
+      // lane 16 g + j points at key row 4 hi + j / 4, columns (g % 2) * 16 + 4 (j % 4) .. of tile dt
+      int ln = lane;
+      asm volatile("" : "+v"(ln));
+      const int j = ln & 15, half = (ln >> 4) & 1;
+      const uint32_t vb = lds_offset(vbuf) + (4 * hi + (j >> 2)) * S::kRowBytes + (half * 2 + ((j & 3) >> 1)) * 16 +
+                          (j & 1) * 8;
 #pragma unroll
-      for (int dt = 0; dt < S::kDT; ++dt) vaddr[dt] = vb + (((dt * 4 + (cc >> 3)) ^ (hi << 2)) << 4);
+      for (int dt = 0; dt < S::kDT; ++dt) vaddr[dt] = vb + ((dt ^ hi) << 6);
     }
     uint4 vf[S::kDT];
-#pragma unroll
-    for (int dt = 0; dt < S::kDT; dt += 2) lds_read_vt_x2<S::kRowBytes, 0>(vf + dt, vaddr + dt);
+    if constexpr (S::kDT == 4) lds_read_vt_x4<S::kRowBytes, 0>(vf, vaddr);
+    else lds_read_vt_x2<S::kRowBytes, 0>(vf, vaddr);
 #pragma unroll
     for (int dt = 0; dt < S::kDT; ++dt)
 #pragma unroll
       for (int rt = 0; rt < RTW; ++rt) o[rt][dt] = mma_chunk<Bf16>(vf[dt], pf[rt][0], o[rt][dt]);
-#pragma unroll
-    for (int dt = 0; dt < S::kDT; dt += 2) lds_read_vt_x2<S::kRowBytes, 1>(vf + dt, vaddr + dt);
+    if constexpr (S::kDT == 4) lds_read_vt_x4<S::kRowBytes, 1>(vf, vaddr);
+    else lds_read_vt_x2<S::kRowBytes, 1>(vf, vaddr);
 #pragma unroll
     for (int dt = 0; dt < S::kDT; ++dt)
 #pragma unroll
@@ -305,7 +406,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
   // ---- partial result of this span: (reference exponent, sum) and unnormalised O per row
-  const int64_t pbase = ((int64_t)unit * a.nsplits + bx) * a.rows_pad;
+  const int64_t pbase = (int64_t)bx * a.rows_pad;
 #pragma unroll
   for (int rt = 0; rt < RTW; ++rt) {
     const int row = (wave * RTW + rt) * 32 + col;
@@ -324,7 +425,7 @@ __global__ __launch_bounds__(256, 1) void decode_attn_kernel(DecodeArgs a) {
   }
 }
 
-// Merge of the per-span partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
+// Merge of the per-item partials: out = sum_s 2^(m_s - M) O_s / sum_s 2^(m_s - M) l_s.
 // One thread per (row, four value columns); grid (ceil(rows * D / 4 / 256), units).
 template <bool MASKED>
 __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
@@ -337,8 +438,8 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
   if (row >= a.rows) return;
   const int j = row / a.group, g = row - j * a.group;
   float* dst = a.out + ((((int64_t)u.b * a.n_new + j) * a.n_q_heads + (int64_t)u.h * a.group + g) * D + qd * 4);
-  const int nsp = (u.len + a.span - 1) / a.span;
-  const int64_t pbase = (int64_t)unit * a.nsplits * a.rows_pad;
+  const int nsp = a.item_begin[unit + 1] - a.item_begin[unit];
+  const int64_t pbase = (int64_t)a.item_begin[unit] * a.rows_pad;
   float M = -__builtin_inff();
   for (int s = 0; s < nsp; ++s) M = fmaxf(M, a.part_ml[pbase + (int64_t)s * a.rows_pad + row].x);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -364,14 +465,18 @@ hipError_t launch_attn(const DecodeArgs& a, int units, hipStream_t stream) {
   const size_t lds = 2 * kStages * DShape<D>::kTileBytes + (MASKED ? kStages * 4 * 64 * sizeof(uint32_t) : 0);
   const hipError_t e = allow_lds(decode_attn_kernel<D, RTW, MASKED>, lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((decode_attn_kernel<D, RTW, MASKED>), dim3(a.nsplits, units), dim3(256), lds, stream, a);
+  (void)units;
+  hipLaunchKernelGGL((decode_attn_kernel<D, RTW, MASKED>), dim3(a.max_items), dim3(256), lds, stream, a);
   return hipGetLastError();
 }
 
 template <int D, bool MASKED>
 hipError_t launch_typed(const DecodeArgs& a, int units, hipStream_t stream) {
   const dim3 block(256);
-  hipError_t e = a.rows_pad <= 128 ? launch_attn<D, 1, MASKED>(a, units, stream) : launch_attn<D, 2, MASKED>(a, units, stream);
+  hipLaunchKernelGGL(decode_plan_kernel<MASKED>, dim3(1), dim3(1024), 0, stream, a, units);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  e = a.rows_pad <= 128 ? launch_attn<D, 1, MASKED>(a, units, stream) : launch_attn<D, 2, MASKED>(a, units, stream);
   if (e != hipSuccess) return e;
   const int items = a.rows * (D / 4);
   hipLaunchKernelGGL(decode_merge_kernel<MASKED>, dim3((items + 255) / 256, units), block, 0, stream, a);
