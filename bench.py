@@ -70,6 +70,53 @@ def read_traffic(kernel, workload):
     return None
 
 
+def time_decode_attention(torch, np, H, B, W, cfg_id=4, n_new=64, reps=20):
+    """Consumer of the compressed cache: attention of `n_new` new queries over the compacted ragged
+    cache of one layer of config 4 (131072 tokens), next to masked attention over the full cache."""
+    layer = W.make_layer(cfg_id, 0)
+    cfg = layer.cfg
+    qn = W.make_new_queries(cfg_id, 0, n_new=n_new)
+    dl = H.DeviceLayer(layer, kv_layout="head_major")
+    dl.compress()
+    res = dl.results()
+    N, Hkv, d = dl.N, cfg.n_kv_heads, cfg.head_dim
+    kept_rows = int(res["out_offsets"][-1])
+    keep = np.zeros((Hkv, N), np.uint8)
+    for u, b, h, s0, e0 in H.unit_slices(layer):
+        o, c = int(res["out_offsets"][u]), int(res["kept"][u])
+        keep[h, s0 + res["idx"][o:o + c]] = 1
+    mask = torch.from_numpy(keep).cuda()
+    q = H.to_device(qn, cfg.dtype)
+    out = torch.empty((dl.batch, n_new, cfg.n_q_heads, d), dtype=torch.float32, device="cuda")
+    ws_bytes = B.rfkv_decode_workspace_bytes(dl.params, n_new, dl.max_len)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    b = dl.buf
+    t_c = timed(lambda: B.rfkv_decode_attention(dl.params, q, n_new, b.k_out, b.v_out, dl.cu_host, b.out_offsets, out,
+                                                ws, ws_bytes))
+    t_m = timed(lambda: B.rfkv_masked_attention(dl.params, q, n_new, dl.k, dl.v, dl.cu_host, dl.cu_dev, mask, out, ws,
+                                                ws_bytes))
+    flop_per_key = 4 * n_new * (cfg.n_q_heads // Hkv) * d          # QK^T and PV, multiply-add = 2
+    return {"workload": f"{cfg.name}: {N} tokens, {n_new} new queries, position ranking, T={cfg.threshold}",
+            "retained_fraction": round(kept_rows / (N * Hkv), 4),
+            "compacted_ms": round(t_c, 5), "masked_full_ms": round(t_m, 5), "speedup": round(t_m / t_c, 3),
+            "compacted_kv_GBps": round(2 * kept_rows * d * 2 / (t_c * 1e-3) / 1e9, 1),
+            "compacted_mfma_TFLOPs": round(flop_per_key * kept_rows / (t_c * 1e-3) / 1e12, 1),
+            "masked_mfma_TFLOPs": round(flop_per_key * N * Hkv / (t_m * 1e-3) / 1e12, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -85,7 +132,10 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 128 MiB device copy a few times (a kernel of known traffic, for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--decode", type=int, default=1,
+                    help="also time the decode attention of 64 new queries over the compacted cache of the "
+                         "long-context workload (config 4) against masked attention over the full cache (0 = skip)")
+    ap.add_argument("--streams", type=int, default=4,
                     help="HIP streams the steps are spread over (layers are independent; step i runs on stream i %% S)")
     ap.add_argument("--graph", type=int, default=1, help="replay the timed steps from a HIP graph (1) or launch eagerly (0)")
     args = ap.parse_args()
@@ -238,21 +288,28 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
             cores = os.cpu_count() or 1
-        L0 = host_layers[0]
-        qf, kf = L0.f64("q_win"), L0.f64("k")
         t = time.perf_counter()
-        out = O.oracle_compress_layer(qf, kf, L0.k, L0.v, L0.cu_seqlens, cfg.n_q_heads, cfg.n_kv_heads, cfg.window,
-                                      n_sink=cfg.n_sink, T=H.threshold_as_float32(cfg.threshold),
-                                      rank_mode=O.RANK_POSITION, form="cumsum")
-        dt = time.perf_counter() - t
+        outs = []
+        for L in host_layers:
+            outs.append(O.oracle_compress_layer(L.f64("q_win"), L.f64("k"), L.k, L.v, L.cu_seqlens, cfg.n_q_heads,
+                                                cfg.n_kv_heads, cfg.window, n_sink=cfg.n_sink,
+                                                T=H.threshold_as_float32(cfg.threshold), rank_mode=O.RANK_POSITION,
+                                                form="cumsum"))
+        dt = (time.perf_counter() - t) / len(host_layers)
+        out = outs[0]
         # the run doubles as a last parity check of the benchmarked launch configuration
         dl = dls[B.RANK_POSITION][0]
         dl.compress(None)
         gpu = dl.results()
         agree = bool(np.array_equal(gpu["kept"], out["kept"]))
         cpu = {"value": round(N / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"1 layer of the same workload ({N} tokens, all {cfg.n_kv_heads} KV heads), float64 numpy, "
-                         f"{dt:.2f} s", "kept_counts_match_gpu": agree}
+               "sample": f"{len(host_layers)} layers of the same workload ({N} tokens, all {cfg.n_kv_heads} KV heads "
+                         f"each, upcast to float64 included), float64 numpy, {dt:.2f} s per layer",
+               "kept_counts_match_gpu": agree}
+
+    decode = None
+    if args.decode:
+        decode = time_decode_attention(torch, np, H, B, W)
 
     if args.calibrate_copy:
         src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -275,6 +332,7 @@ def main():
                    "input_generation_s": round(gen_s, 1)},
         "percent_peak_hbm": round(100 * roofline["pipeline_frac"], 2),
         "roofline": roofline, "cpu_baseline": cpu, "score_ranking": score_mode, "single_stream": single,
+        "decode_attention": decode,
     }
     print(json.dumps(line))
 
