@@ -58,6 +58,9 @@ def load_library() -> ctypes.CDLL:
         raise FileNotFoundError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2502_16886_amd.build` "
             "(there is no CPU fallback for the compression pass)")
+    # torch ships its own HIP runtime; it has to be in the process before librfkv.so is mapped, or
+    # the library binds to a second copy of the runtime and its launches fail on torch's streams
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     P = ctypes.POINTER(RfkvParams)
     vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
