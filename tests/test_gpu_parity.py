@@ -48,6 +48,11 @@ def test_config0_tiny_fp32(mode):
     ("fp32", 4, 4, 64, 1, [260]),                   # the paper's k = 1
     ("bf16", 32, 8, 128, 64, [40, 2100]),           # n < window for the first sequence; 256 rows
     ("bf16", 4, 1, 128, 5, [3, 2, 4, 70]),          # n <= m (sinks) and odd window
+    ("bf16", 8, 2, 128, 24, [900, 20]),             # 96 rows: padded to the 4-row-tile kernels
+    ("bf16", 8, 2, 128, 40, [1100]),                # 160 rows: padded to the 8-row-tile kernels
+    ("bf16", 8, 2, 64, 72, [700, 300]),             # 288 rows: beyond the streaming kernels
+    ("fp32", 8, 2, 64, 32, [640, 33]),              # fp32 d = 64, 128 rows
+    ("bf16", 16, 4, 64, 32, [2050]),                # bf16 d = 64, 128 rows
 ])
 def test_small_shapes(mode, dtype, Hq, Hkv, d, w, lens):
     cfg = small_cfg(dtype, Hq, Hkv, d, w, batch=len(lens))
