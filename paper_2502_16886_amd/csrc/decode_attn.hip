@@ -23,10 +23,27 @@
 #include "kernels.h"
 #include "score_common.h"
 
+// Tunables of the 256-row decode workgroup (rows per wavefront / 32, 32-key tiles per stage).
+// Measured on config 4 (64 new queries, attention + merge): 4 wavefronts x 64 rows, 1 tile per stage
+// 276 us; 8 x 32 rows, 1 tile 208 us; 8 x 32 rows, 2 tiles 193 us; 4 x 64 rows, 2 tiles 254 us.
+#ifndef RFKV_DECODE_RTW
+#define RFKV_DECODE_RTW 1
+#endif
+#ifndef RFKV_DECODE_KT
+#define RFKV_DECODE_KT 2
+#endif
+#ifndef RFKV_DECODE_KT_SMALL
+#define RFKV_DECODE_KT_SMALL 1
+#endif
+
 namespace rfkv {
 namespace {
 
-constexpr int kStages = 4;
+// Shape of a decode workgroup: W wavefronts of 32 * RTW query rows each; a pipeline stage holds
+// KT 32-key tiles of K and of V; kStagesFor stages of them are in flight / in use.
+constexpr int stages_for(int kt) { return kt == 1 ? 4 : 3; }
+// tiles per stage, raised where a stage would otherwise hold fewer load instructions than wavefronts
+constexpr int kt_for(int d, int w, int kt) { return kt * (d / 16) < w ? w / (d / 16) : kt; }
 
 template <int D>
 struct DShape {
@@ -34,11 +51,9 @@ struct DShape {
   static constexpr int kCpr = kRowBytes / 16;            // 16-byte chunks per row
   static constexpr int kTileBytes = 32 * kRowBytes;
   static constexpr int kLoads = kTileBytes / 1024;        // direct-to-LDS instructions per tile
-  static constexpr int kPerWave = kLoads / 4;             // ... per wavefront
   static constexpr int kRowStep = 64 / kCpr;              // rows per instruction
   static constexpr int kChunks = kRowBytes / 32;          // 16-byte chunks of half a row (MFMA steps of S)
   static constexpr int kDT = D / 32;                      // 32-column tiles of the output
-  static_assert(kPerWave >= 1, "a tile has at least four load instructions");
 };
 
 // V^T fragments for MFMA step S of the O^T product, by the LDS transpose read: element e of lane
@@ -172,22 +187,27 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(DecodeArgs a, int uni
   for (int i = carry + tid; i < a.max_items; i += 1024) a.items[i] = make_int4(-1, 0, 0, 0);
 }
 
-template <int D, int RTW, bool MASKED>
-__global__ __launch_bounds__(256, RTW == 1 ? 2 : 1) void decode_attn_kernel(DecodeArgs a) {
+template <int D, int RTW, int W, int KT, bool MASKED>
+__global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_attn_kernel(DecodeArgs a) {
   using S = DShape<D>;
   using KS = Shape<Bf16, D>;
-  // dynamic LDS: kStages key tiles, kStages value tiles, then (MASKED) 64 mask words per stage and wavefront
+  constexpr int kStages = stages_for(KT);
+  constexpr int kStageBytes = KT * S::kTileBytes;        // K (or V) bytes of one stage
+  constexpr int kStageLoads = KT * S::kLoads;            // direct-to-LDS instructions per stage and tensor
+  constexpr int kPerWave = kStageLoads / W;              // ... per wavefront
+  static_assert(kPerWave >= 1 && kPerWave * W == kStageLoads, "the wavefronts share a stage's loads evenly");
+  // dynamic LDS: kStages key stages, kStages value stages, then (MASKED) 64 mask words per stage and wavefront
   extern __shared__ __attribute__((aligned(1024))) unsigned char dsm[];
   unsigned char* ksm = dsm;
-  unsigned char* vsm = dsm + kStages * S::kTileBytes;
-  uint32_t* msm = reinterpret_cast<uint32_t*>(dsm + 2 * kStages * S::kTileBytes);
+  unsigned char* vsm = dsm + kStages * kStageBytes;
+  uint32_t* msm = reinterpret_cast<uint32_t*>(dsm + 2 * kStages * kStageBytes);
   const int bx = blockIdx.x;
   const int4 item = a.items[bx];
   const int unit = item.x;
   if (unit < 0) return;                                  // uniform for the whole workgroup
   const DUnit u = load_dunit<MASKED>(a, unit);
   const int span_begin = item.y, span_end = item.z;      // 0 <= begin < end <= u.len
-  const int ntiles = (span_end - span_begin + 31) >> 5;
+  const int ntiles = (span_end - span_begin + 32 * KT - 1) / (32 * KT);      // stages' worth of keys
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, hi = lane >> 5;
@@ -226,59 +246,60 @@ __global__ __launch_bounds__(256, RTW == 1 ? 2 : 1) void decode_attn_kernel(Deco
   const int64_t k_tok = a.k_stride_tok * 2, v_tok = a.v_stride_tok * 2;
   const unsigned char* munit = MASKED ? a.mask + (int64_t)u.h * a.total_tokens + u.row0 : nullptr;
 
-  // This wavefront's share of tile `t` (tile index within the span) into stage t % kStages.
-  // per-lane parts of the tile addresses: instruction jj of this wavefront fetches row r_jj of the
-  // tile, K chunk cl ^ (r & kSw), V chunk cl ^ (bit 2 of r) << 2 (the layouts the fragment reads expect)
+  // This wavefront's share of stage-load `t` (32 * KT keys from span_begin + t * 32 * KT) into stage
+  // t % kStages.  Per-lane parts of the addresses: instruction jj of this wavefront fetches row r_jj
+  // of the stage, K chunk cl ^ (r & kSw), V chunk cl ^ (bit 2 of r) << 2 (the layouts the fragment
+  // reads expect; a 32-key tile is kLoads consecutive instructions, so tiles stay contiguous in LDS)
   const int rl = lane / S::kCpr, cl = lane % S::kCpr;
-  uint32_t koff[S::kPerWave], voff[S::kPerWave];
+  uint32_t koff[kPerWave], voff[kPerWave];
 #pragma unroll
-  for (int jj = 0; jj < S::kPerWave; ++jj) {
-    const int r = (wave * S::kPerWave + jj) * S::kRowStep + rl;
+  for (int jj = 0; jj < kPerWave; ++jj) {
+    const int r = (wave * kPerWave + jj) * S::kRowStep + rl;
     koff[jj] = (uint32_t)(r * k_tok) + (uint32_t)((cl ^ (r & ((S::kCpr < 16 ? S::kCpr : 16) - 1))) << 4);
     voff[jj] = (uint32_t)(r * v_tok) + (uint32_t)((cl ^ (((r >> 2) & 1) << 2)) << 4);
   }
   auto issue_tile = [&](int t) {
-    const int tile0 = __builtin_amdgcn_readfirstlane(span_begin + t * 32);
+    const int tile0 = __builtin_amdgcn_readfirstlane(span_begin + t * 32 * KT);
     const int st = t % kStages;
-    if (tile0 + 32 <= u.len) {
+    if (tile0 + 32 * KT <= u.len) {
       // interior tile: a scalar base per tile plus the per-lane offsets
       const unsigned char* kb = kunit + (int64_t)tile0 * k_tok;
       const unsigned char* vb = vunit + (int64_t)tile0 * v_tok;
 #pragma unroll
-      for (int jj = 0; jj < S::kPerWave; ++jj) {
-        const int j = wave * S::kPerWave + jj;
+      for (int jj = 0; jj < kPerWave; ++jj) {
+        const int j = wave * kPerWave + jj;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + koff[jj]),
-                                         (__attribute__((address_space(3))) void*)(ksm + st * S::kTileBytes + j * 1024),
+                                         (__attribute__((address_space(3))) void*)(ksm + st * kStageBytes + j * 1024),
                                          16, 0, 0);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vb + voff[jj]),
-                                         (__attribute__((address_space(3))) void*)(vsm + st * S::kTileBytes + j * 1024),
+                                         (__attribute__((address_space(3))) void*)(vsm + st * kStageBytes + j * 1024),
                                          16, 0, 0);
       }
     } else {
       // the unit's last tile: rows past the end repeat the last key (masked out below)
 #pragma unroll
-      for (int jj = 0; jj < S::kPerWave; ++jj) {
-        const int j = wave * S::kPerWave + jj;
+      for (int jj = 0; jj < kPerWave; ++jj) {
+        const int j = wave * kPerWave + jj;
         const int r = j * S::kRowStep + rl;
         const int64_t key = min(tile0 + r, u.len - 1);
         const int kchunk = cl ^ (r & ((S::kCpr < 16 ? S::kCpr : 16) - 1));
         const int vchunk = cl ^ (((r >> 2) & 1) << 2);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kunit + key * k_tok + kchunk * 16),
-                                         (__attribute__((address_space(3))) void*)(ksm + st * S::kTileBytes + j * 1024),
+                                         (__attribute__((address_space(3))) void*)(ksm + st * kStageBytes + j * 1024),
                                          16, 0, 0);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vunit + key * v_tok + vchunk * 16),
-                                         (__attribute__((address_space(3))) void*)(vsm + st * S::kTileBytes + j * 1024),
+                                         (__attribute__((address_space(3))) void*)(vsm + st * kStageBytes + j * 1024),
                                          16, 0, 0);
       }
     }
     if (MASKED) {
-      // one byte per lane: key tile0 + (lane % 32); lands as one dword per lane
-      const int64_t key = min(tile0 + (lane & 31), u.len - 1);
+      // one byte per lane: key tile0 + lane (lanes past the stage's keys repeat); one dword per lane
+      const int64_t key = min(tile0 + (lane & (32 * KT - 1)), u.len - 1);
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(munit + key),
-                                       (__attribute__((address_space(3))) void*)(msm + (st * 4 + wave) * 64), 1, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(msm + (st * W + wave) * 64), 1, 0, 0);
     }
   };
-  constexpr int kPerTile = 2 * S::kPerWave + (MASKED ? 1 : 0);     // loads one wavefront issues per tile
+  constexpr int kPerTile = 2 * kPerWave + (MASKED ? 1 : 0);        // loads one wavefront issues per stage
 
   float m_run[RTW], l_run[RTW];
   f32x16 o[RTW][S::kDT];
@@ -308,17 +329,21 @@ __global__ __launch_bounds__(256, RTW == 1 ? 2 : 1) void decode_attn_kernel(Deco
     if (t + kStages - 1 < ntiles) issue_tile(t + kStages - 1);       // into the stage tile t-1 used
 
     const int st = t % kStages;
-    const int tile0 = span_begin + t * 32;
-    const unsigned char* kbuf = ksm + st * S::kTileBytes;
-    const unsigned char* vbuf = vsm + st * S::kTileBytes;
+    unsigned long long stage_keep = ~0ull;               // bit i: key (stage start + i) takes part
+    if (MASKED) {
+      const uint32_t mword = lds_read_b32_now(msm + (st * W + wave) * 64 + lane);
+      stage_keep = __ballot((mword & 0xffu) != 0);
+    }
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+    const int tile0 = span_begin + (t * KT + kt) * 32;
+    if (KT > 1 && tile0 >= span_end) break;              // uniform: the span ended inside this stage
+    const unsigned char* kbuf = ksm + st * kStageBytes + kt * S::kTileBytes;
+    const unsigned char* vbuf = vsm + st * kStageBytes + kt * S::kTileBytes;
     uint4 kf[S::kChunks];
     read_tile_frags<Bf16, D>(kf, kbuf, col, hi);
 
-    uint32_t keep_bits = 0xffffffffu;                    // bit i: key tile0 + i takes part
-    if (MASKED) {
-      const uint32_t mword = lds_read_b32_now(msm + (st * 4 + wave) * 64 + (lane & 31));
-      keep_bits = (uint32_t)__ballot((mword & 0xffu) != 0 && lane < 32);
-    }
+    uint32_t keep_bits = (uint32_t)(stage_keep >> (32 * kt));              // bit i: key tile0 + i takes part
     if (tile0 + 32 > u.len) keep_bits &= (1u << (u.len - tile0)) - 1u;      // 1 <= len - tile0 <= 31 here
     const bool all_in = keep_bits == 0xffffffffu;        // uniform
 
@@ -402,6 +427,7 @@ __global__ __launch_bounds__(256, RTW == 1 ? 2 : 1) void decode_attn_kernel(Deco
     for (int dt = 0; dt < S::kDT; ++dt)
 #pragma unroll
       for (int rt = 0; rt < RTW; ++rt) o[rt][dt] = mma_chunk<Bf16>(vf[dt], pf[rt][1], o[rt][dt]);
+    }   // kt
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
@@ -440,46 +466,71 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
   float* dst = a.out + ((((int64_t)u.b * a.n_new + j) * a.n_q_heads + (int64_t)u.h * a.group + g) * D + qd * 4);
   const int nsp = a.item_begin[unit + 1] - a.item_begin[unit];
   const int64_t pbase = (int64_t)a.item_begin[unit] * a.rows_pad;
+  const float2* ml = a.part_ml + pbase + row;
+  const float* po = a.part_o + (pbase + row) * D + qd * 4;
+  const int64_t ml_step = a.rows_pad, po_step = (int64_t)a.rows_pad * D;
   float M = -__builtin_inff();
-  for (int s = 0; s < nsp; ++s) M = fmaxf(M, a.part_ml[pbase + (int64_t)s * a.rows_pad + row].x);
+  for (int s = 0; s < nsp; ++s) M = fmaxf(M, ml[s * ml_step].x);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float den = 0.f;
   if (M != -__builtin_inff()) {
-    for (int s = 0; s < nsp; ++s) {
-      const float2 ml = a.part_ml[pbase + (int64_t)s * a.rows_pad + row];
-      const float w = fast_exp2(ml.x - M);
-      const float4 o4 = *reinterpret_cast<const float4*>(a.part_o + (pbase + (int64_t)s * a.rows_pad + row) * D + qd * 4);
+    // four items at a time, their loads issued together
+    int s = 0;
+    for (; s + 4 <= nsp; s += 4) {
+      float2 m4[4];
+      float4 o4[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        m4[j] = ml[(s + j) * ml_step];
+        o4[j] = *reinterpret_cast<const float4*>(po + (s + j) * po_step);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float w = fast_exp2(m4[j].x - M);
+        acc.x += w * o4[j].x;
+        acc.y += w * o4[j].y;
+        acc.z += w * o4[j].z;
+        acc.w += w * o4[j].w;
+        den += w * m4[j].y;
+      }
+    }
+    for (; s < nsp; ++s) {
+      const float2 m1 = ml[s * ml_step];
+      const float w = fast_exp2(m1.x - M);
+      const float4 o4 = *reinterpret_cast<const float4*>(po + s * po_step);
       acc.x += w * o4.x;
       acc.y += w * o4.y;
       acc.z += w * o4.z;
       acc.w += w * o4.w;
-      den += w * ml.y;
+      den += w * m1.y;
     }
   }
   const float inv = den > 0.f ? 1.f / den : 0.f;          // a unit without visible keys gives zeros
   *reinterpret_cast<float4*>(dst) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
 }
 
-template <int D, int RTW, bool MASKED>
-hipError_t launch_attn(const DecodeArgs& a, int units, hipStream_t stream) {
-  const size_t lds = 2 * kStages * DShape<D>::kTileBytes + (MASKED ? kStages * 4 * 64 * sizeof(uint32_t) : 0);
-  const hipError_t e = allow_lds(decode_attn_kernel<D, RTW, MASKED>, lds);
+template <int D, int RTW, int W, int KT, bool MASKED>
+hipError_t launch_attn(const DecodeArgs& a, hipStream_t stream) {
+  constexpr int kStages = stages_for(KT);
+  const size_t lds = 2 * kStages * KT * DShape<D>::kTileBytes + (MASKED ? kStages * W * 64 * sizeof(uint32_t) : 0);
+  const hipError_t e = allow_lds(decode_attn_kernel<D, RTW, W, KT, MASKED>, lds);
   if (e != hipSuccess) return e;
-  (void)units;
-  hipLaunchKernelGGL((decode_attn_kernel<D, RTW, MASKED>), dim3(a.max_items), dim3(256), lds, stream, a);
+  hipLaunchKernelGGL((decode_attn_kernel<D, RTW, W, KT, MASKED>), dim3(a.max_items), dim3(W * 64), lds, stream, a);
   return hipGetLastError();
 }
 
 template <int D, bool MASKED>
 hipError_t launch_typed(const DecodeArgs& a, int units, hipStream_t stream) {
-  const dim3 block(256);
   hipLaunchKernelGGL(decode_plan_kernel<MASKED>, dim3(1), dim3(1024), 0, stream, a, units);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  e = a.rows_pad <= 128 ? launch_attn<D, 1, MASKED>(a, units, stream) : launch_attn<D, 2, MASKED>(a, units, stream);
+  // up to 128 rows: 4 wavefronts of 32 rows, two workgroups per CU; up to 256: see RFKV_DECODE_* below
+  constexpr int kWBig = 256 / (32 * RFKV_DECODE_RTW);
+  if (a.rows_pad <= 128) e = launch_attn<D, 1, 4, kt_for(D, 4, RFKV_DECODE_KT_SMALL), MASKED>(a, stream);
+  else e = launch_attn<D, RFKV_DECODE_RTW, kWBig, kt_for(D, kWBig, RFKV_DECODE_KT), MASKED>(a, stream);
   if (e != hipSuccess) return e;
   const int items = a.rows * (D / 4);
-  hipLaunchKernelGGL(decode_merge_kernel<MASKED>, dim3((items + 255) / 256, units), block, 0, stream, a);
+  hipLaunchKernelGGL(decode_merge_kernel<MASKED>, dim3((items + 255) / 256, units), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
