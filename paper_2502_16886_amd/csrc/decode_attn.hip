@@ -41,7 +41,10 @@ namespace {
 
 // Shape of a decode workgroup: W wavefronts of 32 * RTW query rows each; a pipeline stage holds
 // KT 32-key tiles of K and of V; kStagesFor stages of them are in flight / in use.
-constexpr int stages_for(int kt) { return kt == 1 ? 4 : 3; }
+#ifndef RFKV_DECODE_STAGES2
+#define RFKV_DECODE_STAGES2 3
+#endif
+constexpr int stages_for(int kt) { return kt == 1 ? 4 : RFKV_DECODE_STAGES2; }
 // tiles per stage, raised where a stage would otherwise hold fewer load instructions than wavefronts
 constexpr int kt_for(int d, int w, int kt) { return kt * (d / 16) < w ? w / (d / 16) : kt; }
 
@@ -196,6 +199,7 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
   constexpr int kStageLoads = KT * S::kLoads;            // direct-to-LDS instructions per stage and tensor
   constexpr int kPerWave = kStageLoads / W;              // ... per wavefront
   static_assert(kPerWave >= 1 && kPerWave * W == kStageLoads, "the wavefronts share a stage's loads evenly");
+  static_assert(KT <= 2, "one mask byte per lane covers at most 64 keys per stage");
   // dynamic LDS: kStages key stages, kStages value stages, then (MASKED) 64 mask words per stage and wavefront
   extern __shared__ __attribute__((aligned(1024))) unsigned char dsm[];
   unsigned char* ksm = dsm;
