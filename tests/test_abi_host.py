@@ -130,3 +130,37 @@ def test_binding_raises_on_error(lib):
     with pytest.raises(B.RfkvError) as e:
         B.rfkv_score(good(window=0), FAKE, FAKE, CU, FAKE, FAKE, FAKE, 1 << 40, stream=0)
     assert e.value.status == B.RFKV_INVALID_ARG
+
+
+def decode(p, n_new=64, q=FAKE, k=FAKE, v=FAKE, cu_h=CU, offs=FAKE, out=FAKE, ws=FAKE, wsb=1 << 40):
+    return B.rfkv_decode_attention(p, q, n_new, k, v, cu_h, offs, out, ws, wsb, stream=0, check=False)
+
+
+def masked(p, n_new=64, q=FAKE, k=FAKE, v=FAKE, cu_h=CU, cu_d=FAKE, mask=FAKE, out=FAKE, ws=FAKE, wsb=1 << 40):
+    return B.rfkv_masked_attention(p, q, n_new, k, v, cu_h, cu_d, mask, out, ws, wsb, stream=0, check=False)
+
+
+def test_decode_attention_host_checks(lib):
+    """Everything the decode entry points can reject before touching the GPU (nothing is enqueued)."""
+    need = B.rfkv_decode_workspace_bytes(good(), 64, 4096)
+    assert need > 256 * 256 * 128 * 4                        # a partial output slot per workgroup at least
+    assert B.rfkv_decode_workspace_bytes(good(), 65, 4096) == 0
+    assert B.rfkv_decode_workspace_bytes(good(dtype=B.DTYPE_FP32, window=8), 4, 4096) == 0
+    assert lib.rfkv_decode_workspace_bytes(None, 4, 4096) == 0
+    assert decode(good(), n_new=65) == B.RFKV_UNSUPPORTED
+    assert decode(good(dtype=B.DTYPE_FP32, window=8)) == B.RFKV_UNSUPPORTED
+    assert decode(good(), n_new=-1) == B.RFKV_INVALID_ARG
+    assert decode(good(), q=None) == B.RFKV_INVALID_ARG
+    assert decode(good(), k=None) == B.RFKV_INVALID_ARG
+    assert decode(good(), v=FAKE + 4) == B.RFKV_INVALID_ARG
+    assert decode(good(), offs=None) == B.RFKV_INVALID_ARG
+    assert decode(good(), out=None) == B.RFKV_INVALID_ARG
+    assert decode(good(), cu_h=None) == B.RFKV_INVALID_ARG
+    assert decode(good(), cu_h=np.array([0, -5], dtype=np.int32)) == B.RFKV_INVALID_ARG
+    assert decode(good(), wsb=need - 1) == B.RFKV_WORKSPACE_TOO_SMALL
+    assert decode(good(), n_new=0) == B.RFKV_OK              # nothing to do
+    assert decode(good(batch=0), cu_h=np.array([0], dtype=np.int32)) == B.RFKV_OK
+    assert masked(good(), mask=None) == B.RFKV_INVALID_ARG
+    assert masked(good(), cu_d=None) == B.RFKV_INVALID_ARG
+    assert masked(good(k_stride_tok=100)) == B.RFKV_INVALID_ARG
+    assert masked(good(), wsb=16) == B.RFKV_WORKSPACE_TOO_SMALL
