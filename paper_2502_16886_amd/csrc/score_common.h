@@ -237,7 +237,7 @@ __device__ __forceinline__ void lds_read_b128_n(uint4* out, const uint32_t* a) {
   }
 }
 
-// MFMA fragments of a 32-key tile that issue_tile_load has brought in (the caller has waited for
+// MFMA fragments of a 32-key tile that TileLoader::issue has brought in (the caller has waited for
 // its loads): lane (col, hi) gets the `hi` half of key row `col`, chunk by chunk.  Complete on return.
 // One row tile (32 rows) of a unit's window queries into `buf`, in the layout of a key tile
 // (row r = t * G + g of the KV head; rows past the unit's last repeat the last row: their
@@ -307,7 +307,7 @@ __device__ __forceinline__ void read_q_frags(uint4* qf, const unsigned char* row
 
 // defined in score.hip
 hipError_t launch_score_merge(const Geometry& g, const ScoreArgs& a, hipStream_t stream);
-// defined in score_qreg.hip: the register-resident-Q kernels and the shapes they cover
+// defined in score_qreg.hip: the streaming kernels and the shapes they cover
 bool score_qreg_covers(const Geometry& g, bool bf16);
 hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks);
 }  // namespace rfkv

@@ -1,20 +1,25 @@
-// Scoring kernels for up to 128 score rows per KV head (window * G <= 128: the Llama / Mistral
-// shapes with a 32-row window, and the paper's own k = 1), Sec. 3.2 "Reducing Overhead", Eq. 2.
+// Streaming scoring kernels for up to 256 score rows per KV head (window * G <= 256: the Llama /
+// Mistral shapes with a 32-row window, Qwen's G = 7, a 64-row window, and the paper's own k = 1),
+// Sec. 3.2 "Reducing Overhead", Eq. 2.
 //
 // Same two-pass scheme as score.hip (row statistics, merge, column reduction); what differs is
 // where the operands live:
 //
-//   Q   every wavefront keeps the MFMA fragments of ALL window rows in registers for the whole
-//       kernel (4 row tiles x 8 chunks x 16 bytes per lane for bf16, d = 128).  They pass
-//       through LDS once per workgroup (coalesced global loads, padded rows) and are never
-//       touched again.
-//   K   streamed through two wavefront-private LDS buffers of one 32-key tile each by
-//       direct-to-LDS loads (global_load_lds_dwordx4): each instruction moves 1 KB of
-//       consecutive key bytes, so HBM/L2 requests are whole cache lines, and no VGPRs are held
-//       while the data is in flight.  A tile lands XOR-swizzled (16-byte slot s of row r holds
-//       chunk s ^ (r & 15)) so the MFMA-layout read-back (lane = row, 8 x ds_read_b128) is
-//       bank-conflict free.  While tile i is being multiplied, tiles i+1 and i+2 are in flight.
-//       The second buffer set reuses the LDS the Q staging occupied.
+//   Q   up to 4 row tiles: every wavefront keeps the MFMA fragments of ALL window rows in
+//       registers for the whole kernel (4 row tiles x 8 chunks x 16 bytes per lane for bf16,
+//       d = 128).  One wavefront per row tile brings the tile in by direct-to-LDS loads, in the
+//       layout of a key tile, into the LDS that afterwards serves as the second set of key-tile
+//       buffers.  Up to 8 row tiles: the queries stay in LDS (padded rows) and 8 wavefronts with
+//       one tile buffer each read them at every use.
+//   K   streamed through wavefront-private LDS buffers of one 32-key tile each by direct-to-LDS
+//       loads (global_load_lds_dwordx4): each instruction moves 1 KB of consecutive key bytes, so
+//       HBM/L2 requests are whole cache lines, and no VGPRs are held while the data is in flight.
+//       A tile lands XOR-swizzled (16-byte slot s of row r holds chunk s ^ (r & 15)) so the
+//       MFMA-layout read-back (lane = row, 8 x ds_read_b128) is bank-conflict free.  While tile i
+//       is being multiplied, tiles i+1 and i+2 are in flight.
+//
+// The kernels count their own loads and stores (s_waitcnt vmcnt(N)) and read LDS through inline
+// assembly wherever a direct-to-LDS load may be in flight; see score_common.h for why.
 //
 // A wavefront therefore touches LDS only for 16 KB per 8 KB key tile (DMA write + fragment
 // read); its 32 MFMAs per tile reuse the K fragments 4x and the Q fragments for ever.
