@@ -203,6 +203,55 @@ def oracle_select(scores, cu_seqlens, rank_mode, n_sink, T, min_keep=0, form="au
     return kept, offs, idx
 
 
+def select_layer(scores_seq, rank_mode, n_sink, T, min_keep=0, form="auto"):
+    """One cut per (layer, sequence) instead of one per head (Fig. 1 evicts "per layer"; Sec. 3.3
+    finds "the stopping positions of all layers"): the reduced attention matrix of the layer is
+    A' [Hkv, n], every head's row is ranked on its own, the vector masked at rank i keeps ranks
+    1..i of every head, and i* is the leftmost i with 1 - ||A~'_i||_F / ||A'||_F < T, the norms
+    taken over the whole matrix.  Returns (kept, [idx_h ascending for each head])."""
+    A = np.asarray(scores_seq, dtype=np.float64)
+    Hkv, n = A.shape
+    if n == 0:
+        return 0, [np.zeros(0, dtype=np.int64) for _ in range(Hkv)]
+    ranks = [rank_positions(A[h], rank_mode, n_sink) for h in range(Hkv)]
+    ranked = np.stack([A[h][ranks[h]] for h in range(Hkv)])            # [Hkv, n], rank order per head
+    if form == "auto":
+        form = "definition" if n * Hkv <= DEFINITION_FORM_MAX_N else "cumsum"
+    F = np.sqrt(np.sum(A * A))
+    i_star = n
+    if F > 0.0:
+        if form == "definition":
+            for i in range(1, n + 1):
+                masked = ranked.copy()
+                masked[:, i:] = 0.0
+                if 1.0 - np.sqrt(np.sum(masked * masked)) / F < T:
+                    i_star = i
+                    break
+        else:
+            C = np.sqrt(np.cumsum(np.sum(ranked * ranked, axis=0)))
+            hit = np.nonzero(1.0 - C / C[-1] < T)[0]
+            i_star = int(hit[0]) + 1 if len(hit) else n
+    kept = min(n, max(i_star, int(min_keep)))
+    return kept, [np.sort(ranks[h][:kept]) for h in range(Hkv)]
+
+
+def oracle_select_layer(scores, cu_seqlens, rank_mode, n_sink, T, min_keep=0, form="auto"):
+    """oracle_select with one cut per (layer, sequence): same outputs, every head of a sequence
+    keeps the same number of positions."""
+    Hkv = scores.shape[0]
+    B = len(cu_seqlens) - 1
+    kept = np.zeros(B * Hkv, dtype=np.int64)
+    chunks = []
+    for b in range(B):
+        s, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        c, idxs = select_layer(scores[:, s:e], rank_mode, n_sink, T, min_keep, form)
+        kept[b * Hkv:(b + 1) * Hkv] = c
+        chunks.extend(idxs)
+    offs = np.concatenate([[0], np.cumsum(kept)]).astype(np.int64)
+    idx = np.concatenate(chunks) if chunks else np.zeros(0, dtype=np.int64)
+    return kept, offs, idx
+
+
 # ----------------------------------------------------------------------------
 # compaction  (Alg. 1, "Compress K / V by R")
 # ----------------------------------------------------------------------------
