@@ -51,6 +51,7 @@ typedef enum rfkv_status {
 
 enum { RFKV_RANK_POSITION = 0, RFKV_RANK_SCORE = 1 };
 enum { RFKV_DTYPE_FP32 = 0, RFKV_DTYPE_BF16 = 1 };
+enum { RFKV_PER_HEAD = 0, RFKV_PER_LAYER = 1 };
 
 /* Limits of this build. */
 enum {
@@ -77,11 +78,23 @@ typedef struct rfkv_params {
   int32_t dtype;            /* storage type of Q, K, V: RFKV_DTYPE_FP32 or RFKV_DTYPE_BF16        */
   float   softmax_scale;    /* logit scale; 0 selects 1 / sqrt(head_dim)                          */
   int32_t min_keep;         /* floor on the kept count per unit (0 = the paper's rule alone)      */
+  int32_t granularity;      /* RFKV_PER_HEAD: one cut per (sequence, KV head) (Sec. 3.2, "per layer
+                               and per attention head"); RFKV_PER_LAYER: one cut per (layer,
+                               sequence), the norms of Eq. 1 taken over the reduced attention
+                               matrix of all KV heads (Fig. 1 "per layer"; Sec. 3.3 "the stopping
+                               positions of all layers"), every head keeping the same number of
+                               positions.  RFKV_PER_LAYER is built for RFKV_RANK_POSITION only.    */
   /* strides in elements; the head_dim axis is contiguous.  Token index is the packed index
      0..N-1 for K/V and the packed window-row index 0..sum_b w'_b - 1 for Q.                      */
   int64_t k_stride_tok, k_stride_head;
   int64_t v_stride_tok, v_stride_head;
   int64_t q_stride_row, q_stride_head;
+  int64_t out_pad_rows;     /* 0: ragged output, unit u at out_offsets[u] = sum of earlier kept counts.
+                               > 0: padded output (Sec. 3.3 "Running at Scale": shorter cache segments
+                               are padded and masked): unit u owns rows [u * out_pad_rows, (u + 1) *
+                               out_pad_rows) of k_out / v_out (and of idx), the first kept[u] of them
+                               are written, the rest are left untouched; out_offsets[u] = u *
+                               out_pad_rows; the mask is t < kept[u].  Must be >= the longest sequence. */
 } rfkv_params;
 
 /* Library version, major * 10000 + minor * 100 + patch. */

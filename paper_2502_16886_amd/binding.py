@@ -22,6 +22,8 @@ RANK_POSITION = 0
 RANK_SCORE = 1
 DTYPE_FP32 = 0
 DTYPE_BF16 = 1
+PER_HEAD = 0
+PER_LAYER = 1
 
 # RFKV_LIBRARY points the binding at another build of the same library (kernel tuning variants)
 LIB_PATH = os.environ.get("RFKV_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librfkv.so")
@@ -33,10 +35,11 @@ class RfkvParams(ctypes.Structure):
         ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
         ("head_dim", ctypes.c_int32), ("window", ctypes.c_int32), ("n_sink", ctypes.c_int32),
         ("threshold", ctypes.c_float), ("rank_mode", ctypes.c_int32), ("dtype", ctypes.c_int32),
-        ("softmax_scale", ctypes.c_float), ("min_keep", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float), ("min_keep", ctypes.c_int32), ("granularity", ctypes.c_int32),
         ("k_stride_tok", ctypes.c_int64), ("k_stride_head", ctypes.c_int64),
         ("v_stride_tok", ctypes.c_int64), ("v_stride_head", ctypes.c_int64),
         ("q_stride_row", ctypes.c_int64), ("q_stride_head", ctypes.c_int64),
+        ("out_pad_rows", ctypes.c_int64),
     ]
 
 
@@ -206,12 +209,14 @@ def rfkv_masked_attention(params, q_new, n_new, k, v, cu_host, cu_dev, keep_mask
 # convenience: parameter struct for contiguous [N, Hkv, d] / [rows, Hq, d] tensors
 # ----------------------------------------------------------------------------
 def make_params(batch, n_q_heads, n_kv_heads, head_dim, window, dtype, n_sink=4, threshold=0.01,
-                rank_mode=RANK_POSITION, softmax_scale=0.0, min_keep=0) -> RfkvParams:
+                rank_mode=RANK_POSITION, softmax_scale=0.0, min_keep=0, granularity=PER_HEAD,
+                out_pad_rows=0) -> RfkvParams:
     p = RfkvParams()
     p.batch, p.n_q_heads, p.n_kv_heads, p.head_dim = batch, n_q_heads, n_kv_heads, head_dim
     p.window, p.n_sink, p.threshold, p.rank_mode = window, n_sink, threshold, rank_mode
     p.dtype = DTYPE_BF16 if dtype in ("bf16", DTYPE_BF16) else DTYPE_FP32
     p.softmax_scale, p.min_keep = softmax_scale, min_keep
+    p.granularity, p.out_pad_rows = granularity, out_pad_rows
     p.k_stride_tok = p.v_stride_tok = n_kv_heads * head_dim
     p.k_stride_head = p.v_stride_head = head_dim
     p.q_stride_row = n_q_heads * head_dim
@@ -238,6 +243,8 @@ def alloc_layer_buffers(params: RfkvParams, total_tokens: int, max_seqlen: int, 
     import torch
     units = params.batch * params.n_kv_heads
     rows = total_tokens * params.n_kv_heads if capacity_rows is None else capacity_rows
+    if params.out_pad_rows > 0 and capacity_rows is None:       # padded layout: a fixed slot per unit
+        rows = units * params.out_pad_rows
     tdt = torch.bfloat16 if params.dtype == DTYPE_BF16 else torch.float32
     ws_bytes = rfkv_workspace_bytes(params, total_tokens, max_seqlen)
     if ws_bytes == 0 and total_tokens > 0:
@@ -246,7 +253,8 @@ def alloc_layer_buffers(params: RfkvParams, total_tokens: int, max_seqlen: int, 
         scores=torch.empty((params.n_kv_heads, total_tokens), dtype=torch.float32, device=device),
         kept=torch.empty(units, dtype=torch.int32, device=device),
         out_offsets=torch.empty(units + 1, dtype=torch.int64, device=device),
-        idx=torch.empty(max(1, total_tokens * params.n_kv_heads), dtype=torch.int32, device=device),
+        idx=torch.empty(max(1, total_tokens * params.n_kv_heads, rows if params.out_pad_rows > 0 else 0),
+                        dtype=torch.int32, device=device),
         k_out=torch.empty((max(1, rows), params.head_dim), dtype=tdt, device=device),
         v_out=torch.empty((max(1, rows), params.head_dim), dtype=tdt, device=device),
         ws=torch.empty(max(256, ws_bytes), dtype=torch.uint8, device=device),

@@ -62,6 +62,9 @@ rfkv_status check_params(const rfkv_params* p) {
   if (!(p->softmax_scale >= 0.f) || !std::isfinite(p->softmax_scale)) return RFKV_INVALID_ARG;
   if (std::isnan(p->threshold)) return RFKV_INVALID_ARG;
   if (p->rank_mode != RFKV_RANK_POSITION && p->rank_mode != RFKV_RANK_SCORE) return RFKV_INVALID_ARG;
+  if (p->granularity != RFKV_PER_HEAD && p->granularity != RFKV_PER_LAYER) return RFKV_INVALID_ARG;
+  if (p->out_pad_rows < 0) return RFKV_INVALID_ARG;
+  if (p->granularity == RFKV_PER_LAYER && p->rank_mode != RFKV_RANK_POSITION) return RFKV_UNSUPPORTED;
   if (p->dtype != RFKV_DTYPE_FP32 && p->dtype != RFKV_DTYPE_BF16) return RFKV_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return RFKV_UNSUPPORTED;
   const int64_t rows = (int64_t)p->window * (p->n_q_heads / p->n_kv_heads);
@@ -181,6 +184,7 @@ hipError_t run_select(const rfkv_params* p, const Geometry& g, const Workspace& 
   a.min_keep = p->min_keep;
   a.rank_mode = p->rank_mode;
   a.threshold = p->threshold;
+  a.per_layer = p->granularity == RFKV_PER_LAYER ? 1 : 0;
   return launch_select(g, a, stream);
 }
 
@@ -195,6 +199,7 @@ CompactArgs compact_base(const rfkv_params* p, const Geometry& g, const int32_t*
   a.n_kv_heads = g.n_kv_heads;
   a.units = g.units;
   a.row_bytes = g.head_dim * g.elem_bytes;
+  a.pad_rows = p->out_pad_rows;
   return a;
 }
 
@@ -254,6 +259,7 @@ rfkv_status rfkv_select(const rfkv_params* params, const float* scores, const in
   int32_t max_len;
   if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
   if (!kept || !out_offsets) return RFKV_INVALID_ARG;
+  if (params->out_pad_rows > 0 && params->out_pad_rows < max_len) return RFKV_OUTPUT_TOO_SMALL;
   if (params->batch == 0) return RFKV_OK;
   if (!aligned16(ws)) return RFKV_INVALID_ARG;
   if (total > 0 && (!aligned16(scores) || !idx)) return RFKV_INVALID_ARG;
@@ -422,6 +428,10 @@ static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_
   int32_t max_len;
   if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
   if (!kept || !out_offsets || out_capacity_rows < 0) return RFKV_INVALID_ARG;
+  if (params->out_pad_rows > 0 &&
+      (params->out_pad_rows < max_len ||
+       params->out_pad_rows * params->batch * params->n_kv_heads > out_capacity_rows))
+    return RFKV_OUTPUT_TOO_SMALL;
   if (params->batch == 0) return RFKV_OK;
   if (!aligned16(ws)) return RFKV_INVALID_ARG;
   if (total > 0 && (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)))

@@ -11,7 +11,8 @@
 //   kSrcPaddedIdx     the per-unit padded list the select kernel wrote
 //   kSrcPackedIdx     a packed list plus offsets supplied by the caller
 // In the first two cases the unit's output offset is the sum of the kept counts of the units
-// before it; workgroup x == 0 of each unit also publishes it (and the grand total).
+// before it (ragged layout) or unit * pad_rows (padded layout, Sec. 3.3 "Running at Scale");
+// workgroup x == 0 of each unit also publishes it (and the grand total).
 #include "kernels.h"
 
 namespace rfkv {
@@ -48,6 +49,13 @@ __global__ __launch_bounds__(kBlockThreads) void compact_kernel(CompactArgs a) {
   int64_t off;
   if (a.source == kSrcPackedIdx) {
     off = a.offsets_in[unit];
+  } else if (a.pad_rows > 0) {
+    // padded layout: a fixed slot per unit, rows past the kept count are left untouched
+    off = (int64_t)unit * a.pad_rows;
+    if (blockIdx.x == 0 && threadIdx.x == 0 && a.offsets_out) {
+      a.offsets_out[unit] = off;
+      if (unit == a.units - 1) a.offsets_out[a.units] = (int64_t)a.units * a.pad_rows;
+    }
   } else {
     if (unit <= kUniformPrefixUnits) {
       // uniform loop: scalar loads, no LDS, no barrier

@@ -64,6 +64,7 @@ struct SelectArgs {
   int32_t from_scores;    // the tile sums are not there yet: form them from the scores first
   int32_t n_kv_heads, n_sink, min_keep, rank_mode;
   float threshold;
+  int32_t per_layer;      // one cut per (layer, sequence) over all heads instead of one per unit
   int32_t lds_floats;     // set by launch_select: floats of dynamic LDS the select kernel may use
 };
 
@@ -84,6 +85,7 @@ struct CompactArgs {
   int32_t* idx_out;             // other sources: packed indices written here (may be null)
   int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
   int64_t capacity_rows;
+  int64_t pad_rows;             // > 0: padded layout, unit u's rows start at u * pad_rows (not kSrcPackedIdx)
   int32_t n_kv_heads, units, row_bytes, source;
 };
 

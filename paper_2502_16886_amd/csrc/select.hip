@@ -537,6 +537,154 @@ __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
   }
 }
 
+// Position ranking with one cut per (layer, sequence): the norm of Eq. 1 runs over the reduced
+// attention matrix of all KV heads of the layer (Fig. 1: eviction "per layer"; Sec. 3.3: "the
+// stopping positions of all layers"), every head keeps the same positions.  One workgroup per
+// sequence; the same search as the per-head position path of select_kernel with every mass
+// replaced by its sum over the heads (heads added in index order, fp64).
+__global__ __launch_bounds__(kT) void select_layer_kernel(SelectArgs a) {
+  __shared__ double sh_dbl[kWaves];
+  __shared__ double sh_incl[kT];
+  __shared__ int sh_i[8];
+  const int b = blockIdx.x;
+  const int H = a.n_kv_heads;
+  int tile_base = 0;
+  for (int bb = 0; bb < b; ++bb) tile_base += (a.cu[bb + 1] - a.cu[bb] + kTileKeys - 1) / kTileKeys;
+  const int s0 = a.cu[b];
+  const int n = a.cu[b + 1] - s0;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  auto publish = [&](int kept, int sinks) {
+    for (int h = tid; h < H; h += kT) {
+      a.kept[b * H + h] = kept;
+      a.desc[b * H + h] = make_int4(kept, sinks, 0, 0);
+    }
+  };
+  if (n == 0) {
+    publish(0, 0);
+    return;
+  }
+  const float* s = a.scores + s0;                          // head h: s + h * total_tokens
+  const double* tiles = a.tile_sq + tile_base;             // head h: tiles + h * tiles_total
+  const int nt = (n + kTileKeys - 1) / kTileKeys;
+  const int m_eff = min(max(a.n_sink, 0), n);
+  if (!(a.threshold > 0.f)) {                              // T <= 0: no prefix short of everything qualifies
+    publish(n, m_eff);
+    return;
+  }
+  auto pos_mass = [&](int p) -> double {                   // squared scores of position p, all heads
+    double v = 0.0;
+    for (int h = 0; h < H; ++h) {
+      const double x = (double)s[(int64_t)h * a.total_tokens + p];
+      v += x * x;
+    }
+    return v;
+  };
+  double sink = 0.0;
+  if (m_eff <= 32) {
+    for (int p = 0; p < m_eff; ++p) sink += pos_mass(p);
+  } else {
+    for (int p = tid; p < m_eff; p += kT) sink += pos_mass(p);
+    sink = block_sum_double(sink, sh_dbl);
+    __syncthreads();
+  }
+  const int jm = m_eff / kTileKeys;                        // first tile holding a tail position
+  const int ntail = m_eff < n ? nt - jm : 0;
+  const int C = (ntail + kT - 1) / kT;                     // tail tiles per thread, in rank order
+  const int k0 = min(ntail, tid * C), k1 = min(ntail, k0 + C);
+  auto tile_mass = [&](int j) -> double {                  // tail mass of tile j, all heads
+    double v = 0.0;
+    if (j > jm || m_eff % kTileKeys == 0) {
+      for (int h = 0; h < H; ++h) v += tiles[(int64_t)h * a.tiles_total + j];
+    } else {                                               // the tile shared with the sinks
+      for (int p = min(n, (j + 1) * kTileKeys) - 1; p >= m_eff; --p) v += pos_mass(p);
+    }
+    return v;
+  };
+  double mine = 0.0;
+  for (int k = k0; k < k1; ++k) mine += tile_mass(nt - 1 - k);
+  double inc = mine;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const double o = __shfl_up(inc, d);
+    if (lane >= d) inc += o;
+  }
+  __syncthreads();
+  if (lane == 63) sh_dbl[wave] = inc;
+  __syncthreads();
+  double wave_off = 0.0, tail_total = 0.0;
+  for (int w = 0; w < kWaves; ++w) {
+    if (w < wave) wave_off += sh_dbl[w];
+    tail_total += sh_dbl[w];
+  }
+  inc += wave_off;
+  sh_incl[tid] = inc;
+  const double f2 = sink + tail_total;
+  const bool degenerate = !(f2 > 0.0) || !(f2 < 1e300);
+  if (tid == 0) {
+    sh_i[0] = n;
+    sh_i[3] = kT;
+  }
+  __syncthreads();
+  if (!degenerate) {
+    const PredF pred(f2, (double)a.threshold, a.min_keep);
+    auto count_through = [&](int k) -> int { return m_eff + n - max((nt - 1 - k) * kTileKeys, m_eff); };
+    auto wave_search = [&](int first, int step, int len, int ranks_before, double mass_before, int fallback) {
+      const int p = first + lane * step;
+      double v = lane < len ? pos_mass(p) : 0.0;
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const double o = __shfl_up(v, d);
+        if (lane >= d) v += o;
+      }
+      const bool ok = lane < len && pred(ranks_before + lane + 1, mass_before + v);
+      const unsigned long long mask = __ballot(ok);
+      if (lane == 0) sh_i[0] = mask ? ranks_before + __ffsll((long long)mask) : fallback;
+    };
+    if (pred(m_eff, sink)) {
+      if (m_eff <= 64) {
+        if (wave == 0) wave_search(0, 1, m_eff, 0, 0.0, m_eff);
+      } else if (tid == 0) {
+        double run = 0.0;
+        int res = m_eff;
+        for (int p = 0; p < m_eff; ++p) {
+          run += pos_mass(p);
+          if (pred(p + 1, run)) {
+            res = p + 1;
+            break;
+          }
+        }
+        sh_i[0] = res;
+      }
+    } else {
+      if (k1 > k0 && pred(count_through(k1 - 1), sink + inc)) atomicMin(&sh_i[3], tid);
+      __syncthreads();
+      if (sh_i[3] == tid) {
+        double run = sink + (tid > 0 ? sh_incl[tid - 1] : 0.0);
+        int jstar = nt - k1;
+        for (int k = k0; k + 1 < k1; ++k) {
+          const double tm = tile_mass(nt - 1 - k);
+          if (pred(count_through(k), run + tm)) {
+            jstar = nt - 1 - k;
+            break;
+          }
+          run += tm;
+        }
+        sh_i[4] = jstar;
+        sh_dbl[0] = run;
+      }
+      __syncthreads();
+      if (sh_i[3] < kT && wave == 0) {
+        const int jt = sh_i[4];
+        const int hi_p = min(n, (jt + 1) * kTileKeys) - 1, lo_p = max(jt * kTileKeys, m_eff);
+        wave_search(hi_p, -1, hi_p - lo_p + 1, m_eff + (n - 1 - hi_p), sh_dbl[0], m_eff + (n - lo_p));
+      }
+    }
+  }
+  __syncthreads();
+  const int kept = degenerate ? n : sh_i[0];
+  publish(kept, min(kept, m_eff));
+}
+
 }  // namespace
 
 hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t stream) {
@@ -548,6 +696,10 @@ hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t str
                        stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+  }
+  if (a.per_layer) {                               // one cut per sequence over all heads (position ranking)
+    hipLaunchKernelGGL(select_layer_kernel, dim3(g.batch), dim3(kT), 0, stream, a);
+    return hipGetLastError();
   }
   // Score ranking keeps a unit's scores in LDS when the longest sequence fits (with up to three
   // floats of alignment slack); otherwise units that fit what is there use it and the rest stream.

@@ -37,7 +37,7 @@ class DeviceLayer:
     """Inputs of one layer resident on the GPU plus the parameter struct."""
 
     def __init__(self, layer: W.Layer, rank_mode=B.RANK_POSITION, threshold=None, min_keep=0, n_sink=None,
-                 kv_layout="token_major"):
+                 kv_layout="token_major", granularity=B.PER_HEAD, out_pad_rows=0):
         import torch
         c = layer.cfg
         self.layer = layer
@@ -53,7 +53,8 @@ class DeviceLayer:
         self.params = B.make_params(self.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.window, c.dtype,
                                     n_sink=c.n_sink if n_sink is None else n_sink,
                                     threshold=c.threshold if threshold is None else threshold,
-                                    rank_mode=rank_mode, min_keep=min_keep)
+                                    rank_mode=rank_mode, min_keep=min_keep, granularity=granularity,
+                                    out_pad_rows=out_pad_rows)
         self.kv_layout = kv_layout
         if kv_layout == "head_major":
             # [Hkv, N, d]: each head's rows contiguous (for one sequence, the [B, H, n, d] cache layout)

@@ -36,8 +36,10 @@ def test_exports_every_declared_symbol(lib):
 
 
 def test_params_struct_matches_header_layout():
-    # 11 four-byte fields, 4 bytes of padding, 6 eight-byte strides
-    assert ctypes.sizeof(B.RfkvParams) == 96
+    # 12 four-byte fields, 6 eight-byte strides, the padded-layout row count
+    assert ctypes.sizeof(B.RfkvParams) == 104
+    assert B.RfkvParams.granularity.offset == 44
+    assert B.RfkvParams.out_pad_rows.offset == 96
     assert B.RfkvParams.k_stride_tok.offset == 48
 
 
