@@ -27,6 +27,7 @@ Workspace carve_workspace(const Geometry& g, void* base) {
   w.idx_pad = static_cast<int32_t*>(take((size_t)g.total_tokens * g.n_kv_heads * sizeof(int32_t)));
   w.scores = static_cast<float*>(take((size_t)g.total_tokens * g.n_kv_heads * sizeof(float)));
   w.tile_sq = static_cast<double*>(take((size_t)g.tiles_total * g.n_kv_heads * sizeof(double)));
+  if (g.spill) w.logits = static_cast<float*>(take((size_t)g.tiles_total * 32 * kSpillRows * g.n_kv_heads * sizeof(float)));
   w.bytes = off;
   return w;
 }
@@ -116,6 +117,8 @@ Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len, con
   g.window = p->window;
   g.units = p->batch * p->n_kv_heads;
   g.rows_pad = (int32_t)padded_rows((int64_t)p->window * g.group);
+  // few score rows (the paper's k = 1): the first scoring pass keeps its logits, no second pass over K
+  g.spill = (int64_t)p->window * g.group <= kSpillRows ? 1 : 0;
   g.span = choose_span(total, p->n_kv_heads);
   g.nspans = (max_len + g.span - 1) / g.span;
   g.max_seqlen = max_len;
@@ -151,6 +154,7 @@ hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w
   a.partials = w.partials;
   a.bvec = w.bvec;
   a.tile_sq = w.tile_sq;
+  a.logits = g.spill ? w.logits : nullptr;
   a.tiles_total = g.tiles_total;
   a.k_stride_tok = p->k_stride_tok;
   a.k_stride_head = p->k_stride_head;

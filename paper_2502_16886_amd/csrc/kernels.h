@@ -11,6 +11,7 @@ constexpr int kBlockThreads = 256;     // 4 wavefronts per workgroup in the scor
 constexpr int kKeyTilesPerWave = 2;    // 32-key MFMA tiles a wavefront processes per iteration
 constexpr int kKeysPerIter = 4 * kKeyTilesPerWave * 32;   // keys a workgroup consumes per iteration
 constexpr int kSelectThreads = 1024;
+constexpr int kSpillRows = 8;          // up to this many score rows the first scoring pass keeps its logits
 
 // Geometry shared by the host (workspace sizing, grids) and the kernels.
 struct Geometry {
@@ -23,6 +24,7 @@ struct Geometry {
   int64_t total_tokens;   // N
   int32_t elem_bytes;     // 2 (bf16) or 4 (fp32)
   int64_t tiles_total;    // sum over sequences of ceil(n_b / 32) (an upper bound when sizing)
+  int32_t spill;          // window * group <= kSpillRows: scoring keeps its logits instead of re-reading K
 };
 
 struct Workspace {
@@ -32,6 +34,7 @@ struct Workspace {
   int32_t* idx_pad;       // [N * Hkv]                  per-unit padded index lists (score ranking)
   float*   scores;        // [Hkv][N]                   used when the caller does not want scores
   double*  tile_sq;       // [Hkv][tiles_total]         sum of squared scores per 32-position tile
+  float*   logits;        // [Hkv][kSpillRows][tiles_total * 32]  scaled logits, only when window * G <= kSpillRows
   size_t   bytes;
 };
 
@@ -45,6 +48,7 @@ struct ScoreArgs {
   float2* partials;
   float* bvec;
   double* tile_sq;
+  float* logits;          // null unless the first pass keeps its logits (window * G <= kSpillRows)
   int64_t tiles_total;
   int64_t k_stride_tok, k_stride_head, q_stride_row, q_stride_head;
   int64_t total_tokens;

@@ -32,12 +32,18 @@ namespace {
 
 // PASS 1: per-row (reference exponent, sum) partials of this workgroup's span.
 // PASS 2: scores (and per-tile squared sums) of this workgroup's span.
+// PASS 3: pass 1 that also writes the logits of up to kSpillRows rows (the paper's k = 1: the
+//         G rows of the last query position), so that the scores follow from 4 * rows bytes per key
+//         instead of a second pass over the keys (score_spill_reduce_kernel).
 // QREG:   window-query fragments in registers (4 wavefronts, two tile buffers each, the second
 //         set reusing the query staging area) or, for more than 4 row tiles, read from LDS at every
 //         use (8 wavefronts, one tile buffer each).
 template <typename T, int D, int RT_T, int PASS, bool QREG>
 __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_kernel(ScoreArgs a) {
   using S = Shape<T, D>;
+  constexpr bool kStats = PASS != 2;                   // pass 1 (and 3: pass 1 that also keeps its logits)
+  constexpr bool kSpill = PASS == 3;
+  static_assert(!kSpill || (RT_T == 1 && QREG), "logits are kept for a single row tile only");
   constexpr int kWaves = QREG ? 4 : 8;
   constexpr int kThreads = kWaves * 64;
   constexpr int kTileBytes = 32 * S::kRowBytes;
@@ -74,7 +80,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   uint4 qf[kQRegTiles][S::kChunks];                    // QREG: fragments of all row tiles, for the whole kernel
   float mc[RT_T], l[RT_T];
   int rowlast[RT_T];
-  if (PASS == 1) {
+  if (kStats) {
 #pragma unroll
     for (int rt = 0; rt < RT_T; ++rt) {
       mc[rt] = -1e30f;
@@ -169,7 +175,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
 
   // From here on the loop counts the loads and stores in flight itself.  Per iteration a wavefront
   // issues the kLoads loads of one tile and, in pass 2, kStores stores (scores, tile sum).
-  constexpr int kStores = PASS == 2 ? 2 : 0;
+  constexpr int kStores = PASS == 2 ? 2 : (kSpill ? 4 : 0);
   for (int it = 0; tile0 < span_end; tile0 += kStep, ++it) {
     uint4 kf[S::kChunks];
     unsigned char* kbuf = (QREG && (it & 1)) ? kbuf1 : kbuf0;
@@ -197,7 +203,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
         const uint4 q = QREG ? qf[QREG ? rt : 0][ch]
                              : *reinterpret_cast<const uint4*>(qsm + (rt * 32 + col) * S::kLdsRowBytes +
                                                                hi * S::kHalfBytes + ch * 16);
-        acc = PASS == 1 ? mma_chunk<T>(kf[ch], q, acc)      // keys x rows: a lane owns one row
+        acc = kStats ? mma_chunk<T>(kf[ch], q, acc)      // keys x rows: a lane owns one row
                         : mma_chunk<T>(q, kf[ch], acc);     // rows x keys: a lane owns one key
       }
       return acc;
@@ -210,12 +216,23 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
     for (int rt = 0; rt < RT_T; ++rt) {
       f32x16 nxt = acc;
       if (rt + 1 < RT_T) nxt = logits(rt + 1);
-      if (PASS == 1) {
+      if (kStats) {
         if (masked) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int key = tile0 + (i >> 2) * 8 + hi * 4 + (i & 3);
             if (key > rowlast[rt]) acc[i] = kNegInf;
+          }
+        }
+        if (kSpill) {
+          // raw logits (q . k, unscaled), row `col`, keys tile0 + 8 q + 4 hi + 0..3 per 16-byte store; the
+          // buffer holds whole tiles, so the last tile's surplus keys are written and never read
+          float* lrow = a.logits + ((int64_t)(u.h * kSpillRows + (col & (kSpillRows - 1))) * a.tiles_total + u.tile_base) * 32 +
+                        tile0 + hi * 4;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const float4 v = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+            if (col < kSpillRows) *reinterpret_cast<float4*>(lrow + q * 8) = v;
           }
         }
         float tmax = kNegInf;
@@ -266,7 +283,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no load may still be writing LDS from here on
-  if (PASS == 1) {
+  if (kStats) {
     // the two half-waves hold disjoint keys of the same rows; then the four wavefronts
 #pragma unroll
     for (int rt = 0; rt < RT_T; ++rt) {
@@ -297,6 +314,48 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   }
 }
 
+// Scores from kept logits (PASS 3): one thread per key.  x_r = q_r . k (unscaled), c = scale * log2 e,
+// b_r = reference + log2(sum * G) from the merge: score = sum_r 2^(x_r c - b_r) / (rows that see the key).
+__global__ __launch_bounds__(256) void score_spill_reduce_kernel(ScoreArgs a) {
+  const Unit u = load_unit(a, blockIdx.y);
+  const int key0 = blockIdx.x * 256;
+  if (key0 >= u.n) return;                             // uniform for the whole workgroup
+  const int key = key0 + threadIdx.x;
+  float sum = 0.f;
+  if (key < u.n) {
+    const float* lbase = a.logits + ((int64_t)(u.h * kSpillRows) * a.tiles_total + u.tile_base) * 32 + key;
+    for (int r = 0; r < u.rows; ++r) {
+      const float x = lbase[(int64_t)r * a.tiles_total * 32];
+      const float b = a.bvec[(int64_t)blockIdx.y * a.rows_pad + r];
+      const int rowlast = u.n - u.wp + r / a.group;
+      if (key <= rowlast) sum += fast_exp2(__builtin_fmaf(x, a.c, -b));     // one rounding, as in pass 2
+    }
+  }
+  const float score = key < u.n ? sum / (float)min(u.wp, u.n - key) : 0.f;
+  if (key < u.n) a.scores[(int64_t)u.h * a.total_tokens + u.s0 + key] = score;
+  // per-tile squared sums: the butterfly of tile_sum_sq, in both halves of the wavefront at once
+  double v = (double)score * (double)score;
+#pragma unroll
+  for (int d = 16; d >= 1; d >>= 1) v += __shfl_xor(v, d);
+  if ((threadIdx.x & 31) == 0 && key < u.n) a.tile_sq[(int64_t)u.h * a.tiles_total + u.tile_base + (key >> 5)] = v;
+}
+
+template <typename T, int D>
+hipError_t launch_stream_spill(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
+  const dim3 grid(g.nspans, g.units);
+  hipLaunchKernelGGL((score_stream_kernel<T, D, 1, 3, true>), grid, dim3(256), 0, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (marks) marks->after(kKernelStats);
+  e = launch_score_merge(g, a, stream);
+  if (e != hipSuccess) return e;
+  if (marks) marks->after(kKernelMerge);
+  hipLaunchKernelGGL(score_spill_reduce_kernel, dim3((g.max_seqlen + 255) / 256, g.units), dim3(256), 0, stream, a);
+  e = hipGetLastError();
+  if (marks && e == hipSuccess) marks->after(kKernelReduce);
+  return e;
+}
+
 template <typename T, int D, int RT_T, bool QREG>
 hipError_t launch_stream_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const dim3 grid(g.nspans, g.units);
@@ -323,6 +382,7 @@ constexpr bool qlds8_fits() {
 template <typename T, int D>
 hipError_t launch_stream_rt(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const int rt = g.rows_pad / 32;
+  if (a.logits) return launch_stream_spill<T, D>(g, a, stream, marks);     // window * G <= kSpillRows
   if (rt <= 1) return launch_stream_typed<T, D, 1, true>(g, a, stream, marks);
   if (rt <= 2) return launch_stream_typed<T, D, 2, true>(g, a, stream, marks);
   if constexpr (Shape<T, D>::kChunks * 4 <= 32) {

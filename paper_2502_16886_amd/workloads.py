@@ -91,6 +91,8 @@ CONFIGS = {
               spike_frac=0.05, x_spike=3.0, peaked_first_half=True),
     4: Config("llama3-8b-128k", 32, 32, 8, 128, 64, "bf16", context=131072, spike_frac=0.005),
     "H": Config("llama3-8b-32k", 32, 32, 8, 128, 32, "bf16", context=32768),
+    # the headline shape with the paper's own window, k = 1 (Sec. 4.1 "we set k = 1 in practice")
+    "K1": Config("llama3-8b-32k-k1", 32, 32, 8, 128, 1, "bf16", context=32768),
 }
 
 

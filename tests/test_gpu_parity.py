@@ -53,6 +53,10 @@ def test_config0_tiny_fp32(mode):
     ("bf16", 8, 2, 64, 72, [700, 300]),             # 288 rows: beyond the streaming kernels
     ("fp32", 8, 2, 64, 32, [640, 33]),              # fp32 d = 64, 128 rows
     ("bf16", 16, 4, 64, 32, [2050]),                # bf16 d = 64, 128 rows
+    ("bf16", 32, 8, 128, 1, [1500, 333, 1, 40]),    # the paper's k = 1 with GQA 4: logits kept, one K pass
+    ("bf16", 8, 2, 128, 2, [777, 2, 1]),            # 8 rows, two window positions: causal masking in the kept logits
+    ("bf16", 28, 4, 128, 1, [900]),                 # k = 1, G = 7
+    ("fp32", 8, 1, 128, 1, [513, 64]),              # k = 1, G = 8, fp32 d = 128
 ])
 def test_small_shapes(mode, dtype, Hq, Hkv, d, w, lens):
     cfg = small_cfg(dtype, Hq, Hkv, d, w, batch=len(lens))
@@ -184,7 +188,7 @@ def test_repeat_runs_are_bit_identical_and_capacity_is_respected():
 # ------------------------------------------------------------------ the workload configurations at full size
 # (config, layers, K/V storage): the headline shape runs in the storage the benchmark times
 FULL_CASES = [(1, [0, 13, 31], "token_major"), (2, [5], "head_major"), (3, [2], "token_major"),
-              ("H", [0], "head_major"), (4, [1], "head_major")]
+              ("H", [0], "head_major"), (4, [1], "head_major"), ("K1", [0, 7], "head_major")]
 
 
 @pytest.mark.parametrize("cfg_id,layers,kv_layout", FULL_CASES)
