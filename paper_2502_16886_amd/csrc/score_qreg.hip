@@ -76,8 +76,14 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
 
   int tile0 = span_begin + wave * 32;
   const TileLoader<T, D> tiles(kunit, tok_bytes, u.n, lane);
-  constexpr int kQRegTiles = QREG ? RT_T : 1;
-  uint4 qf[kQRegTiles][S::kChunks];                    // QREG: fragments of all row tiles, for the whole kernel
+#ifndef RFKV_QLDS_HELD
+#define RFKV_QLDS_HELD 4
+#endif
+  // row tiles whose query fragments live in registers for the whole kernel: all of them (QREG), or,
+  // with the queries resident in LDS, as many as pass 2's register budget allows (pass 1 has none to spare)
+  constexpr int kHeld = QREG ? RT_T : ((PASS == 2 && RFKV_QLDS_HELD <= RT_T) ? RFKV_QLDS_HELD : 0);
+  constexpr int kQRegTiles = kHeld > 0 ? kHeld : 1;
+  uint4 qf[kQRegTiles][S::kChunks];
   float mc[RT_T], l[RT_T];
   int rowlast[RT_T];
   if (kStats) {
@@ -169,6 +175,8 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
     }
     lds_writes_done();
     __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < kHeld; ++rt) read_q_frags<T, D>(qf[rt], qsm + rt * 32 * S::kLdsRowBytes, col, hi);
     if (tile0 < span_end) tiles.issue(tile0, kbuf0);
   }
   float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
@@ -200,7 +208,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
       for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
       for (int ch = 0; ch < S::kChunks; ++ch) {
-        const uint4 q = QREG ? qf[QREG ? rt : 0][ch]
+        const uint4 q = rt < kHeld ? qf[rt < kHeld ? rt : 0][ch]
                              : *reinterpret_cast<const uint4*>(qsm + (rt * 32 + col) * S::kLdsRowBytes +
                                                                hi * S::kHalfBytes + ch * 16);
         acc = kStats ? mma_chunk<T>(kf[ch], q, acc)      // keys x rows: a lane owns one row
