@@ -16,7 +16,7 @@ SCORE_ATOL = 1e-30
 # Bound used to decide whether a cut may legitimately move: the fp32 pipeline (MFMA accumulate,
 # one fused multiply-add, one hardware exp2 per term) keeps every score within this relative
 # error of the exact value; measured errors are reported next to it by the tests (up to 1.3e-6 with
-# a 32-row window; up to 2.0e-6 with the paper's k = 1, where a score is the mean of only G terms and
+# a 32-row window; up to 2.3e-6 with the paper's k = 1, where a score is the mean of only G terms and
 # the fp32 accumulation error of a large sink logit, ~3 ulp of a raw q.k near 100, does not average out).
 SCORE_EPS_FOR_CUT = 4e-6
 
