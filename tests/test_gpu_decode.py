@@ -163,3 +163,27 @@ def test_decode_full_size_config4():
     w2 = _check(got_m, ref, bound, "masked")
     print(f"config 4 decode: retained {res['kept'].sum() / (8 * 131072):.3f}, worst error / bound: "
           f"compacted {w1:.2f}, masked {w2:.2f}")
+
+
+def test_many_units_compress_and_decode():
+    """1500 units (375 short sequences x 4 KV heads): the planner's batched prefix over more units than it
+    has threads, compaction's block-wide offset sums, and the per-unit kernels' grids."""
+    rng = np.random.default_rng(11)
+    lens = [int(x) for x in rng.integers(1, 200, size=375)]
+    lens[7] = 0
+    cfg = W.Config("t", 1, 8, 4, 64, 8, "bf16", batch=len(lens), context=max(lens), threshold=0.05)
+    layer = W.make_layer(7, 3, cfg=cfg, lengths=lens)
+    for mode in (B.RANK_POSITION, B.RANK_SCORE):
+        dl = H.DeviceLayer(layer, rank_mode=mode)
+        dl.compress()
+        res = dl.results()
+        H.compare_layer(layer, res, mode)
+        if mode == B.RANK_POSITION:
+            qn = W.make_new_queries(7, 3, n_new=3, cfg=cfg, lengths=lens)
+            got = _run_decode(dl, qn, 3)
+            qf = W.to_f64(qn, "bf16")
+            k_c, v_c = W.to_f64(res["k_out"], "bf16"), W.to_f64(res["v_out"], "bf16")
+            ref = O.oracle_decode_attention(qf, k_c, v_c, res["out_offsets"], 8, 4)
+            bound = _bound(qf, k_c, v_c, res["out_offsets"], 8, 4, masked=False)
+            _check(got, ref, bound, "compacted, 1500 units")
+            assert np.all(got[7] == 0)
