@@ -152,6 +152,8 @@ def make_layer(cfg_id, layer: int = 0, cfg: Config | None = None, lengths=None) 
         aux = _rng(seed, 10 * b + 4)
         peaked = (not cfg.peaked_first_half) or (b < B // 2)
         for h in range(Hkv):
+            if n == 0:
+                break                                   # an empty sequence has no window and no keys
             qbar = qb[:, h * G:(h + 1) * G, :].astype(np.float64).mean(axis=(0, 1))
             norm = float(np.linalg.norm(qbar))
             u = qbar / norm if norm > 0 else np.zeros(d)
