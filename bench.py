@@ -21,7 +21,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
 
@@ -146,7 +145,7 @@ def main():
 
     import numpy as np
     import torch
-    import rfkv_harness as H
+    from paper_2502_16886_amd import device as H
     from paper_2502_16886_amd import binding as B
     from paper_2502_16886_amd import workloads as W
 
