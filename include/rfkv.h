@@ -55,7 +55,10 @@ enum { RFKV_PER_HEAD = 0, RFKV_PER_LAYER = 1 };
 
 /* Limits of this build. */
 enum {
-  RFKV_MAX_SCORE_ROWS = 512,     /* window * G, after rounding up to a multiple of 32             */
+  RFKV_MAX_SCORE_ROWS = 512,     /* window * G (rounded up to a multiple of 32) of the streaming  */
+                                 /* kernels; more rows take the wide-window path below            */
+  RFKV_MAX_WIDE_ROWS = 65536,    /* window * G of the wide-window path (the paper's ablation of k */
+                                 /* up to 10 % of n): bf16 with head_dim 64 or 128, fp32 with 64  */
   RFKV_MAX_UNITS = 65535         /* B * n_kv_heads                                                */
 };
 

@@ -46,12 +46,17 @@ int64_t padded_rows(int64_t rows) {
 
 // keys one score workgroup covers: enough workgroups to fill 256 CUs a few times over, but long
 // enough that staging the window queries (once per workgroup) stays a small part of its traffic
-int32_t choose_span(int64_t total_tokens, int32_t n_kv_heads) {
+int32_t choose_span(int64_t total_tokens, int32_t n_kv_heads, int max_iters) {
   const int64_t work = total_tokens * n_kv_heads;      // keys to score in the layer
   int64_t span = (work / 1024 + kKeysPerIter - 1) / kKeysPerIter * kKeysPerIter;
   if (span < 2 * kKeysPerIter) span = 2 * kKeysPerIter;
-  if (span > 16 * kKeysPerIter) span = 16 * kKeysPerIter;
+  if (span > (int64_t)max_iters * kKeysPerIter) span = (int64_t)max_iters * kKeysPerIter;
   return (int32_t)span;
+}
+
+bool wide_window(const rfkv_params* p) {
+  const int64_t rows = (int64_t)p->window * (p->n_q_heads / p->n_kv_heads);
+  return (rows + 31) / 32 * 32 > RFKV_MAX_SCORE_ROWS;
 }
 
 rfkv_status check_params(const rfkv_params* p) {
@@ -69,9 +74,13 @@ rfkv_status check_params(const rfkv_params* p) {
   if (p->dtype != RFKV_DTYPE_FP32 && p->dtype != RFKV_DTYPE_BF16) return RFKV_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return RFKV_UNSUPPORTED;
   const int64_t rows = (int64_t)p->window * (p->n_q_heads / p->n_kv_heads);
-  if ((rows + 31) / 32 * 32 > RFKV_MAX_SCORE_ROWS) return RFKV_UNSUPPORTED;
   if ((int64_t)p->batch * p->n_kv_heads > RFKV_MAX_UNITS) return RFKV_UNSUPPORTED;
   const int eb = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
+  if (wide_window(p)) {
+    // row-blocked statistics keep 128 rows of queries in registers: 256-byte rows at most
+    if (rows > RFKV_MAX_WIDE_ROWS || p->head_dim * eb > 256) return RFKV_UNSUPPORTED;
+    return RFKV_OK;
+  }
   // the window queries of one unit must fit in LDS next to the per-row tables
   const int64_t rows_pad = padded_rows(rows);
   if (rows_pad * (p->head_dim * eb + 16 + 8) > 156 * 1024) return RFKV_UNSUPPORTED;
@@ -117,9 +126,12 @@ Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len, con
   g.window = p->window;
   g.units = p->batch * p->n_kv_heads;
   g.rows_pad = (int32_t)padded_rows((int64_t)p->window * g.group);
+  g.wide = wide_window(p) ? 1 : 0;
+  if (g.wide) g.rows_pad = (g.rows_pad + 127) / 128 * 128;      // whole blocks of 128 rows (4 row tiles)
   // few score rows (the paper's k = 1): the first scoring pass keeps its logits, no second pass over K
   g.spill = (int64_t)p->window * g.group <= kSpillRows ? 1 : 0;
-  g.span = choose_span(total, p->n_kv_heads);
+  // a wide window multiplies the statistics pass's workgroups by its row blocks: longer spans
+  g.span = choose_span(g.wide ? total * (g.rows_pad / 128) / 2 : total, p->n_kv_heads, g.wide ? 64 : 16);
   g.nspans = (max_len + g.span - 1) / g.span;
   g.max_seqlen = max_len;
   g.total_tokens = total;

@@ -25,6 +25,7 @@ struct Geometry {
   int32_t elem_bytes;     // 2 (bf16) or 4 (fp32)
   int64_t tiles_total;    // sum over sequences of ceil(n_b / 32) (an upper bound when sizing)
   int32_t spill;          // window * group <= kSpillRows: scoring keeps its logits instead of re-reading K
+  int32_t wide;           // window * group > RFKV_MAX_SCORE_ROWS: row-blocked statistics, key-resident column sums
 };
 
 struct Workspace {

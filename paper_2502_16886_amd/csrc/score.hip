@@ -319,6 +319,7 @@ hipError_t launch_score_merge(const Geometry& g, const ScoreArgs& a, hipStream_t
 
 hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks) {
   if (g.units == 0 || g.nspans == 0) return hipSuccess;
+  if (g.wide) return launch_score_wide(g, a, bf16, stream, marks);
   if (score_qreg_covers(g, bf16)) return launch_score_qreg(g, a, bf16, stream, marks);
   if (bf16) {
     if (g.head_dim == 64) return launch_typed<Bf16, 64>(g, a, stream, marks);

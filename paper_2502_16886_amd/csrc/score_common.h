@@ -310,4 +310,7 @@ hipError_t launch_score_merge(const Geometry& g, const ScoreArgs& a, hipStream_t
 // defined in score_qreg.hip: the streaming kernels and the shapes they cover
 bool score_qreg_covers(const Geometry& g, bool bf16);
 hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks);
+// wide windows (more than RFKV_MAX_SCORE_ROWS score rows): statistics in score_qreg.hip, the whole path in score_wide.hip
+hipError_t launch_score_wide_stats(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream);
+hipError_t launch_score_wide(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks);
 }  // namespace rfkv

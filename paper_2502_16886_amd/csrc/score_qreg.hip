@@ -38,12 +38,16 @@ namespace {
 // QREG:   window-query fragments in registers (4 wavefronts, two tile buffers each, the second
 //         set reusing the query staging area) or, for more than 4 row tiles, read from LDS at every
 //         use (8 wavefronts, one tile buffer each).
-template <typename T, int D, int RT_T, int PASS, bool QREG>
+// WIDE:   pass 1 over one block of RT_T row tiles out of many (blockIdx.z picks the block): the
+//         statistics of windows with more rows than a workgroup can hold (the large windows of the
+//         paper's ablation of k, "Attention Matrix Reduction": k = 1 %, 5 %, 10 % of n).
+template <typename T, int D, int RT_T, int PASS, bool QREG, bool WIDE = false>
 __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_kernel(ScoreArgs a) {
   using S = Shape<T, D>;
   constexpr bool kStats = PASS != 2;                   // pass 1 (and 3: pass 1 that also keeps its logits)
   constexpr bool kSpill = PASS == 3;
   static_assert(!kSpill || (RT_T == 1 && QREG), "logits are kept for a single row tile only");
+  static_assert(!WIDE || (PASS == 1 && QREG), "row blocks exist for the statistics pass only");
   constexpr int kWaves = QREG ? 4 : 8;
   constexpr int kThreads = kWaves * 64;
   constexpr int kTileBytes = 32 * S::kRowBytes;
@@ -61,6 +65,8 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   const int span_begin = bx * a.span;
   if (span_begin >= u.n) return;                       // uniform for the whole workgroup
   const int span_end = min(u.n, span_begin + a.span);
+  const int row0 = WIDE ? (int)blockIdx.z * (RT_T * 32) : 0;    // first score row of this workgroup
+  if (WIDE && row0 >= u.row_tiles * 32) return;        // a short sequence has fewer window rows
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int col = lane & 31, hi = lane >> 5;
@@ -91,7 +97,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
     for (int rt = 0; rt < RT_T; ++rt) {
       mc[rt] = -1e30f;
       l[rt] = 0.f;
-      const int r = rt * 32 + col;
+      const int r = row0 + rt * 32 + col;
       rowlast[rt] = r < u.rows ? u.n - u.wp + r / a.group : -1;
     }
   }
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
                                          (__attribute__((address_space(3))) void*)(bsm + wave * 64), 4, 0, 0);
       }
     }
-    if (wave < RT_T) issue_q_tile_load<T, D>(a, u, wave, smem_b + wave * kTileBytes, lane);
+    if (wave < RT_T) issue_q_tile_load<T, D>(a, u, (row0 >> 5) + wave, smem_b + wave * kTileBytes, lane);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_writes_done();
     __syncthreads();
@@ -308,7 +314,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
       for (int rt = 0; rt < RT_T; ++rt) red[wave * kRows32 + rt * 32 + col] = make_float2(mc[rt], l[rt]);
     }
     __syncthreads();
-    for (int r = threadIdx.x; r < u.row_tiles * 32; r += kThreads) {
+    for (int r = threadIdx.x; r < (WIDE ? RT_T * 32 : u.row_tiles * 32); r += kThreads) {
       float m = red[r].x, s = red[r].y;
 #pragma unroll
       for (int w = 1; w < kWaves; ++w) {
@@ -317,7 +323,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
         s = s * fast_exp2(m - nm) + o.y * fast_exp2(o.x - nm);
         m = nm;
       }
-      a.partials[((int64_t)by * a.nspans + bx) * a.rows_pad + r] = make_float2(m, s);
+      a.partials[((int64_t)by * a.nspans + bx) * a.rows_pad + row0 + r] = make_float2(m, s);
     }
   }
 }
@@ -421,6 +427,27 @@ hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, h
   }
   if (g.head_dim == 64) return launch_stream_rt<Fp32, 64>(g, a, stream, marks);
   return launch_stream_rt<Fp32, 128>(g, a, stream, marks);
+}
+
+// Row statistics of a wide window: the pass-1 kernel over blocks of 128 score rows.
+template <typename T, int D>
+hipError_t launch_wide_stats_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream) {
+  if constexpr (Shape<T, D>::kChunks * 4 <= 32) {
+    const dim3 grid(g.nspans, g.units, g.rows_pad / 128);
+    hipLaunchKernelGGL((score_stream_kernel<T, D, 4, 1, true, true>), grid, dim3(256), 0, stream, a);
+    return hipGetLastError();
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_score_wide_stats(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream) {
+  if (g.rows_pad % 128 != 0) return hipErrorInvalidValue;
+  if (bf16) {
+    if (g.head_dim == 64) return launch_wide_stats_typed<Bf16, 64>(g, a, stream);
+    return launch_wide_stats_typed<Bf16, 128>(g, a, stream);
+  }
+  if (g.head_dim == 64) return launch_wide_stats_typed<Fp32, 64>(g, a, stream);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace rfkv

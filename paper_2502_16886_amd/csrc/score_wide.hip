@@ -1,0 +1,203 @@
+// Scoring with a wide observation window: more score rows (window * G) than one workgroup can keep
+// in registers or LDS.  The paper's ablation of the window size ("Attention Matrix Reduction":
+// k = 1 %, 5 %, 10 % of n) runs Eq. 2 with thousands of rows, where the contraction Q_win K^T is a
+// real GEMM and the matrix cores, not HBM, set the pace.
+//
+// Same two passes as the narrow kernels (row statistics, merge, column sums of the normalised
+// probabilities), with the operands the other way round in the second pass:
+//
+//   pass 1  score_stream_kernel<.., WIDE> (score_qreg.hip): a workgroup keeps one block of 128 score
+//           rows in registers and streams its span of keys; grid.z walks the row blocks.
+//   merge   score_merge_kernel: b_r = reference + log2(sum * G) per row.
+//   pass 2  score_colsum_wide_kernel (here): a workgroup keeps 256 KEYS in registers (each
+//           wavefront the MFMA fragments of two 32-key tiles) and streams the window queries, four
+//           row tiles per stage, through a double-buffered LDS ring filled by direct-to-LDS
+//           loads, together with the rows' exponent offsets b_r.  A lane owns one key column, so
+//           the sum over rows is a chain of register adds and the scores leave the kernel once.
+//           Rows that cannot see a key block (the causal part of the window) are skipped by
+//           whole stages; partly visible stages mask per element with one comparison.
+//
+// Per 32 x 32 tile of logits a wavefront spends 8 MFMAs (d = 128: 256 cycles) and, per lane, 16 x
+// (fma, exp2, add): the quarter-rate exponential makes the vector ALU the longer pole (about
+// 1.5 x the matrix time), so two workgroups share a CU and overlap one's MFMAs with the other's
+// arithmetic.
+#include "kernels.h"
+#include "score_common.h"
+#include "tile_sum.h"
+
+namespace rfkv {
+namespace {
+
+constexpr int kWideKT = 2;             // key tiles a wavefront keeps
+constexpr int kWideStage = 4;          // row tiles per stage, one brought in by each wavefront
+constexpr int kWideKeys = 4 * kWideKT * 32;    // keys per workgroup
+
+template <typename T, int D>
+constexpr size_t wide_lds_bytes() {
+  return 2 * kWideStage * 32 * Shape<T, D>::kRowBytes + 2 * kWideStage * 64 * sizeof(float);
+}
+
+// 4 x 16 bytes at consecutive 32-byte steps: the exponent offsets of the 16 rows a lane's accumulators hold
+__device__ __forceinline__ void read_row_offsets(float4* bv, const float* tile, int hi) {
+  uint32_t addr[4];
+  const uint32_t base = lds_offset(tile) + hi * 16;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) addr[j] = base + j * 32;
+  uint4 raw[4];
+  lds_read_b128_x4(raw, addr);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) bv[j] = __builtin_bit_cast(float4, raw[j]);
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) {
+  using S = Shape<T, D>;
+  constexpr int kTileBytes = 32 * S::kRowBytes;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char wsm[];
+  unsigned char* qs = wsm;                                               // [2][kWideStage] query row tiles
+  float* bs = reinterpret_cast<float*>(wsm + 2 * kWideStage * kTileBytes);   // [2][kWideStage][64] offsets
+  const int by = blockIdx.y;
+  const Unit u = load_unit(a, by);
+  const int kb0 = blockIdx.x * kWideKeys;
+  if (kb0 >= u.n) return;                              // uniform for the whole workgroup
+
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int col = lane & 31, hi = lane >> 5;
+  const float c = a.c;
+  const unsigned char* kunit = static_cast<const unsigned char*>(a.k) +
+                               ((int64_t)u.s0 * a.k_stride_tok + (int64_t)u.h * a.k_stride_head) * T::kBytes;
+  const TileLoader<T, D> tiles(kunit, a.k_stride_tok * T::kBytes, u.n, lane);
+
+  // this wavefront's keys: two tiles, staged once through the (still unused) query ring
+  uint4 kf[kWideKT][S::kChunks];
+  int t0[kWideKT];
+#pragma unroll
+  for (int kt = 0; kt < kWideKT; ++kt) {
+    t0[kt] = kb0 + (wave * kWideKT + kt) * 32;         // tiles past the end re-read the last key; never stored
+    tiles.issue(t0[kt], qs + (wave * kWideKT + kt) * kTileBytes);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+  for (int kt = 0; kt < kWideKT; ++kt) read_tile_frags<T, D>(kf[kt], qs + (wave * kWideKT + kt) * kTileBytes, col, hi);
+  __syncthreads();                                     // the ring is free for the queries
+
+  // Row r = t * G + g sees key i iff i <= n - wp + t, i.e. iff r >= G * (i - (n - wp)).
+  const int base_pos = u.n - u.wp;
+  int rmin[kWideKT];
+#pragma unroll
+  for (int kt = 0; kt < kWideKT; ++kt) rmin[kt] = a.group * (t0[kt] + col - base_pos);
+  const int rows_blind = max(0, a.group * (kb0 - base_pos));                  // rows below see none of the block's keys
+  const int wave_rmax = a.group * (t0[kWideKT - 1] + 31 - base_pos);          // rows from here on see all of the wavefront's keys
+  const int stage_begin = rows_blind / (kWideStage * 32);
+  const int stage_end = (u.row_tiles + kWideStage - 1) / kWideStage;          // <= rows_pad / 128
+
+  auto issue_stage = [&](int s) {
+    const int buf = s & 1;
+    const int rt = s * kWideStage + wave;
+    issue_q_tile_load<T, D>(a, u, rt, qs + (buf * kWideStage + wave) * kTileBytes, lane);
+    const float* src = a.bvec + (int64_t)by * a.rows_pad + min(rt * 32 + lane, a.rows_pad - 1);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(bs + (buf * kWideStage + wave) * 64), 4, 0, 0);
+  };
+
+  auto logits = [&](const uint4* q, const uint4* k) {
+    f32x16 acc;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int ch = 0; ch < S::kChunks; ++ch) acc = mma_chunk<T>(q[ch], k[ch], acc);     // rows x keys: a lane owns one key
+    return acc;
+  };
+
+  float colsum[kWideKT];
+#pragma unroll
+  for (int kt = 0; kt < kWideKT; ++kt) colsum[kt] = 0.f;
+
+  if (stage_begin < stage_end) issue_stage(stage_begin);
+  for (int s = stage_begin; s < stage_end; ++s) {
+    // stage s has landed (every wavefront waits for its own loads, then all meet); the other half
+    // of the ring was last read in stage s - 1, which every wavefront has left
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    if (s + 1 < stage_end) issue_stage(s + 1);
+    const int buf = s & 1;
+    const bool masked = s * (kWideStage * 32) < wave_rmax;
+    constexpr int kItems = kWideStage * kWideKT;       // (row tile j, key tile kt), j-major
+    uint4 qf[2][S::kChunks];
+    float4 bv[4];
+    read_tile_frags<T, D>(qf[0], qs + (buf * kWideStage) * kTileBytes, col, hi);
+    f32x16 acc = logits(qf[0], kf[0]);
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+      const int j = it / kWideKT, kt = it % kWideKT;
+      // the MFMA chain of the next item is issued before this item's softmax arithmetic
+      f32x16 nxt = acc;
+      if (it + 1 < kItems) {
+        const int j2 = (it + 1) / kWideKT, kt2 = (it + 1) % kWideKT;
+        if (kt2 == 0) read_tile_frags<T, D>(qf[j2 & 1], qs + (buf * kWideStage + j2) * kTileBytes, col, hi);
+        nxt = logits(qf[j2 & 1], kf[kt2]);
+      }
+      if (kt == 0) read_row_offsets(bv, bs + (buf * kWideStage + j) * 64, hi);
+      // accumulator i of this lane: row (s * kWideStage + j) * 32 + (i / 4) * 8 + hi * 4 + i % 4, key t0[kt] + col
+      if (!masked) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          colsum[kt] += fast_exp2(__builtin_fmaf(acc[q * 4 + 0], c, -bv[q].x));
+          colsum[kt] += fast_exp2(__builtin_fmaf(acc[q * 4 + 1], c, -bv[q].y));
+          colsum[kt] += fast_exp2(__builtin_fmaf(acc[q * 4 + 2], c, -bv[q].z));
+          colsum[kt] += fast_exp2(__builtin_fmaf(acc[q * 4 + 3], c, -bv[q].w));
+        }
+      } else {
+        const int rel = rmin[kt] - (s * kWideStage + j) * 32 - hi * 4;     // visible iff (i / 4) * 8 + i % 4 >= rel
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const float p0 = fast_exp2(__builtin_fmaf(acc[q * 4 + 0], c, -bv[q].x));
+          const float p1 = fast_exp2(__builtin_fmaf(acc[q * 4 + 1], c, -bv[q].y));
+          const float p2 = fast_exp2(__builtin_fmaf(acc[q * 4 + 2], c, -bv[q].z));
+          const float p3 = fast_exp2(__builtin_fmaf(acc[q * 4 + 3], c, -bv[q].w));
+          colsum[kt] += (q * 8 + 0 >= rel ? p0 : 0.f) + (q * 8 + 1 >= rel ? p1 : 0.f) +
+                        (q * 8 + 2 >= rel ? p2 : 0.f) + (q * 8 + 3 >= rel ? p3 : 0.f);
+        }
+      }
+      acc = nxt;
+    }
+  }
+
+  float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
+#pragma unroll
+  for (int kt = 0; kt < kWideKT; ++kt) {
+    const float tot = colsum[kt] + __shfl_xor(colsum[kt], 32);
+    const int key = t0[kt] + col;
+    const float score = key < u.n ? tot / (float)min(u.wp, u.n - key) : 0.f;
+    if (hi == 0 && key < u.n) out[key] = score;
+    const double tsq = tile_sum_sq(score, lane);
+    if (lane == 0 && t0[kt] < u.n) a.tile_sq[(int64_t)u.h * a.tiles_total + u.tile_base + (t0[kt] >> 5)] = tsq;
+  }
+}
+
+template <typename T, int D>
+hipError_t launch_colsum_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream) {
+  constexpr size_t lds = wide_lds_bytes<T, D>();
+  hipError_t e = allow_lds(score_colsum_wide_kernel<T, D>, lds);
+  if (e != hipSuccess) return e;
+  const dim3 grid((g.max_seqlen + kWideKeys - 1) / kWideKeys, g.units);
+  hipLaunchKernelGGL((score_colsum_wide_kernel<T, D>), grid, dim3(256), lds, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_score_wide(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks) {
+  hipError_t e = launch_score_wide_stats(g, a, bf16, stream);
+  if (e != hipSuccess) return e;
+  if (marks) marks->after(kKernelStats);
+  e = launch_score_merge(g, a, stream);
+  if (e != hipSuccess) return e;
+  if (marks) marks->after(kKernelMerge);
+  if (bf16) e = g.head_dim == 64 ? launch_colsum_typed<Bf16, 64>(g, a, stream) : launch_colsum_typed<Bf16, 128>(g, a, stream);
+  else e = g.head_dim == 64 ? launch_colsum_typed<Fp32, 64>(g, a, stream) : hipErrorInvalidValue;
+  if (marks && e == hipSuccess) marks->after(kKernelReduce);
+  return e;
+}
+
+}  // namespace rfkv

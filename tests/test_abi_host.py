@@ -107,7 +107,8 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
 def test_unsupported_problems(lib):
     assert score(good(dtype=3)) == B.RFKV_UNSUPPORTED
     assert score(good(head_dim=96)) == B.RFKV_UNSUPPORTED
-    assert score(good(window=256)) == B.RFKV_UNSUPPORTED                     # 256 * 4 rows > 512
+    assert score(good(window=20000)) == B.RFKV_UNSUPPORTED                   # 20000 * 4 rows > RFKV_MAX_WIDE_ROWS
+    assert score(good(dtype=B.DTYPE_FP32, window=256)) == B.RFKV_UNSUPPORTED  # wide window: 256-byte rows at most
     assert score(good(dtype=B.DTYPE_FP32, window=128)) == B.RFKV_UNSUPPORTED  # fp32 queries do not fit in LDS
     assert score(good(batch=10000), cu_h=np.zeros(10001, dtype=np.int32)) == B.RFKV_UNSUPPORTED
 

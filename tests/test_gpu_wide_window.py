@@ -1,0 +1,47 @@
+"""GPU parity of the wide-window scoring path (window * G beyond the streaming kernels' 512 rows: the
+window sizes of the paper's ablation of k, 1 % .. 10 % of n) against the float64 oracle: scores,
+selection in both rankings, compacted rows."""
+import numpy as np
+import pytest
+
+import rfkv_harness as H
+from oracle import refreekv_oracle as O
+from paper_2502_16886_amd import binding as B
+from paper_2502_16886_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+WIDE = [
+    # (Hq, Hkv, d, dtype, window, lens)
+    (8, 2, 128, "bf16", 300, [3000]),                 # 10 % of n, 1200 rows
+    (28, 4, 128, "bf16", 200, [2000, 150, 700]),      # G = 7: 1400 rows; one sequence shorter than the window
+    (4, 4, 64, "bf16", 600, [1300, 5, 601]),          # G = 1, d = 64
+    (8, 2, 64, "fp32", 150, [900, 149]),              # fp32: 600 rows
+    (4, 1, 128, "bf16", 1024, [700]),                 # window >= n: the whole causal attention matrix
+    (32, 8, 128, "bf16", 129, [1111, 300]),           # 516 rows: just past the streaming kernels' limit
+]
+
+
+@pytest.mark.parametrize("case", WIDE, ids=lambda c: f"Hq{c[0]}_Hkv{c[1]}_d{c[2]}_{c[3]}_w{c[4]}")
+@pytest.mark.parametrize("rank_mode", [B.RANK_POSITION, B.RANK_SCORE], ids=["position", "score"])
+def test_wide_window_small_shapes(case, rank_mode):
+    Hq, Hkv, d, dtype, w, lens = case
+    cfg = W.Config("t", 1, Hq, Hkv, d, w, dtype, batch=len(lens), context=max(lens), threshold=0.02)
+    layer = W.make_layer(3, 1, cfg=cfg, lengths=lens)
+    dl = H.DeviceLayer(layer, rank_mode=rank_mode)
+    dl.compress()
+    rep = H.compare_layer(layer, dl.results(), rank_mode)
+    print(rep)
+
+
+def test_wide_window_rejections():
+    import torch
+    t = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    cu = np.array([0, 100], np.int32)
+    p = B.make_params(1, 8, 2, 128, 300, "fp32")              # fp32 rows of 512 bytes
+    st = B.rfkv_compress_layer(p, t, t, t, cu, t, None, t, t, None, t, t, 200, t, 1 << 16, check=False)
+    assert st == B.RFKV_UNSUPPORTED
+    p = B.make_params(1, 8, 2, 128, 20000, "bf16")            # 80000 rows
+    st = B.rfkv_compress_layer(p, t, t, t, cu, t, None, t, t, None, t, t, 200, t, 1 << 16, check=False)
+    assert st == B.RFKV_UNSUPPORTED
