@@ -116,6 +116,75 @@ def time_decode_attention(torch, np, H, B, W, cfg_id=4, n_new=64, reps=20):
             "masked_mfma_TFLOPs": round(flop_per_key * N * Hkv / (t_m * 1e-3) / 1e12, 1)}
 
 
+def time_wide_window(np, H, B, W, window=328, reps=12):
+    """The ablation's large window (k = 1 % of n) on the headline shape: the window contraction is a
+    real GEMM, so the kernels are priced against the dense bf16 MFMA peak (2 passes over Q_win K^T)."""
+    base = W.CONFIGS["H"]
+    cfg = W.Config(f"{base.name}-w{window}", base.layers, base.n_q_heads, base.n_kv_heads, base.head_dim, window,
+                   base.dtype, batch=1, context=base.context)
+    layer = W.make_layer("H", 0, cfg=cfg)
+    dl = H.DeviceLayer(layer, kv_layout="head_major")
+    b = dl.buf
+    kms = np.zeros(len(B.KERNEL_NAMES))
+    for i in range(reps + 2):
+        _, ms = B.rfkv_compress_layer_timed(dl.params, dl.q, dl.k, dl.v, dl.cu_host, dl.cu_dev, b.scores, b.kept,
+                                            b.out_offsets, b.idx, b.k_out, b.v_out, b.capacity_rows, b.ws, b.ws_bytes,
+                                            None)
+        if i >= 2:
+            kms += np.array(ms)
+    kms /= reps
+    n, G, d, Hkv = cfg.context, cfg.n_q_heads // cfg.n_kv_heads, cfg.head_dim, cfg.n_kv_heads
+    # logits a pass has to form: row t of the window sees n - w + t + 1 keys
+    visible = sum(n - window + t + 1 for t in range(window)) * G * Hkv
+    flop = 2.0 * visible * d
+    k = dict(zip(B.KERNEL_NAMES, kms.tolist()))
+    peak = 2500.0
+    return {"workload": f"{cfg.name}: {n} tokens, window {window} ({window * G} score rows per KV head), position ranking",
+            "ms_per_step": round(float(kms.sum()), 5), "kernel_ms": {a: round(v, 5) for a, v in k.items()},
+            "flop_per_pass": flop,
+            "roofline": {"bound": "mfma", "kernel": "score_reduce", "achieved": round(flop / (k["score_reduce"] * 1e-3) / 1e12, 1),
+                         "peak": peak, "unit": "TFLOP/s",
+                         "frac": round(flop / (k["score_reduce"] * 1e-3) / 1e12 / peak, 4), "traffic": None},
+            "stats_TFLOPs": round(flop / (k["score_stats"] * 1e-3) / 1e12, 1)}
+
+
+def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, reps=6):
+    """The post-prefill pass over the whole model in ONE call: the caches of `n_layers` layers (the
+    paper keeps the first two layers whole, Sec. 3.3 "Retaining Bottom Layers", so 30 of 32) laid out
+    [layer, token, head, d] are a batch of `n_layers` sequences to the library, one launch of every
+    kernel instead of one per layer.  The generated layer buffers repeat to fill the 30."""
+    if len({len(l.cu_seqlens) for l in host_layers}) != 1 or len(host_layers[0].cu_seqlens) != 2:
+        return None
+    pick = [host_layers[i % len(host_layers)] for i in range(n_layers)]
+    n = int(pick[0].cu_seqlens[-1])
+    merged = W.Layer(W.Config(f"{cfg.name}-x{n_layers}", cfg.layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                              cfg.window, cfg.dtype, batch=n_layers, context=n, threshold=cfg.threshold,
+                              n_sink=cfg.n_sink),
+                     np.concatenate([l.q_win for l in pick]), np.concatenate([l.k for l in pick]),
+                     np.concatenate([l.v for l in pick]), (np.arange(n_layers + 1) * n).astype(np.int32))
+    dl = H.DeviceLayer(merged, kv_layout="token_major")
+    for _ in range(2):
+        dl.compress(None)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dl.compress(None)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    kept = int(dl.buf.out_offsets[-1])
+    e = 2 if cfg.dtype == "bf16" else 4
+    wrows = n_layers * min(cfg.window, n)
+    alg = algorithmic_bytes(n_layers * n, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows, kept,
+                            n_layers * cfg.n_kv_heads, False)
+    del dl
+    torch.cuda.empty_cache()
+    return {"layers_per_call": n_layers, "ms_per_call": round(ms, 4), "ms_per_layer": round(ms / n_layers, 5),
+            "tokens_per_s_per_layer_pass": round(n / (ms / n_layers * 1e-3), 1),
+            "pipeline_frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -134,6 +203,10 @@ def main():
     ap.add_argument("--decode", type=int, default=1,
                     help="also time the decode attention of 64 new queries over the compacted cache of the "
                          "long-context workload (config 4) against masked attention over the full cache (0 = skip)")
+    ap.add_argument("--all-layers", type=int, default=30,
+                    help="also time this many layers compressed by one call, as a batch (0 = skip)")
+    ap.add_argument("--wide", type=int, default=1,
+                    help="also time the ablation's wide window (k = 1 %% of n) on the headline shape (0 = skip)")
     ap.add_argument("--streams", type=int, default=4,
                     help="HIP streams the steps are spread over (layers are independent; step i runs on stream i %% S)")
     ap.add_argument("--graph", type=int, default=1, help="replay the timed steps from a HIP graph (1) or launch eagerly (0)")
@@ -310,6 +383,14 @@ def main():
     if args.decode:
         decode = time_decode_attention(torch, np, H, B, W)
 
+    all_layers = None
+    if args.all_layers:
+        all_layers = time_all_layers(torch, np, H, B, W, host_layers, cfg, args.all_layers)
+
+    wide = None
+    if args.wide:
+        wide = time_wide_window(np, H, B, W)
+
     if args.calibrate_copy:
         src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -331,7 +412,7 @@ def main():
                    "input_generation_s": round(gen_s, 1)},
         "percent_peak_hbm": round(100 * roofline["pipeline_frac"], 2),
         "roofline": roofline, "cpu_baseline": cpu, "score_ranking": score_mode, "single_stream": single,
-        "decode_attention": decode,
+        "all_layers_one_call": all_layers, "decode_attention": decode, "wide_window": wide,
     }
     print(json.dumps(line))
 

@@ -179,6 +179,9 @@ hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w
   a.rows_pad = g.rows_pad;
   a.span = g.span;
   a.nspans = g.nspans;
+  a.units = g.units;
+  a.wide_items = g.wide ? (g.rows_pad / 128) * g.nspans * g.units : 0;
+  a.span_colsum = g.max_seqlen;
   a.c = scale_times_log2e(p);
   return launch_score(g, a, p->dtype == RFKV_DTYPE_BF16, stream, marks);
 }

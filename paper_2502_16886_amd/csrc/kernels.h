@@ -54,6 +54,9 @@ struct ScoreArgs {
   int64_t k_stride_tok, k_stride_head, q_stride_row, q_stride_head;
   int64_t total_tokens;
   int32_t n_kv_heads, group, window, rows_pad, span, nspans;
+  int32_t wide_items;     // wide window: work items of the statistics pass (row blocks * spans * units)
+  int32_t units;
+  int32_t span_colsum;    // wide window: the longest sequence (keys the column-sum grid covers per unit)
   float c;                // softmax scale * log2(e)
 };
 

@@ -60,12 +60,26 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   __shared__ __attribute__((aligned(16))) unsigned char qsm[QREG ? 16 : RT_T * 32 * S::kLdsRowBytes];
   __shared__ __attribute__((aligned(256))) float bsm[RT_T * 32 < 64 ? 64 : RT_T * 32];   // pass 2: exponent offset per row
   __shared__ __attribute__((aligned(16))) int rlast_s[RT_T * 32];    // pass 2: last visible key per row
-  const int bx = blockIdx.x, by = blockIdx.y;
+  int bx = blockIdx.x, by = blockIdx.y, rblock = 0;
+  if (WIDE) {
+    // One-dimensional grid, work item w = row block + blocks * (span + spans * unit).  Workgroups go
+    // to the 8 XCDs in turn, so workgroup g takes item (g % 8) * chunk + g / 8: the workgroups
+    // resident on one XCD are consecutive items, i.e. the row blocks of one span of keys, and
+    // share that span in their L2 instead of each streaming it from memory.
+    const int chunk = (a.wide_items + 7) >> 3;
+    const int w = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= chunk || w >= a.wide_items) return;
+    const int blocks = a.rows_pad / (RT_T * 32);
+    rblock = w % blocks;
+    const int rest = w / blocks;
+    bx = rest % a.nspans;
+    by = rest / a.nspans;
+  }
   const Unit u = load_unit(a, by);
   const int span_begin = bx * a.span;
   if (span_begin >= u.n) return;                       // uniform for the whole workgroup
   const int span_end = min(u.n, span_begin + a.span);
-  const int row0 = WIDE ? (int)blockIdx.z * (RT_T * 32) : 0;    // first score row of this workgroup
+  const int row0 = WIDE ? rblock * (RT_T * 32) : 0;    // first score row of this workgroup
   if (WIDE && row0 >= u.row_tiles * 32) return;        // a short sequence has fewer window rows
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -91,14 +105,17 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   constexpr int kQRegTiles = kHeld > 0 ? kHeld : 1;
   uint4 qf[kQRegTiles][S::kChunks];
   float mc[RT_T], l[RT_T];
-  int rowlast[RT_T];
+  int rowlast[WIDE ? 1 : RT_T];                         // last key a lane's row sees (WIDE: worked out where it is needed)
+  auto last_visible = [&](int rt) {
+    const int r = row0 + rt * 32 + col;
+    return r < u.rows ? u.n - u.wp + r / a.group : -1;
+  };
   if (kStats) {
 #pragma unroll
     for (int rt = 0; rt < RT_T; ++rt) {
       mc[rt] = -1e30f;
       l[rt] = 0.f;
-      const int r = row0 + rt * 32 + col;
-      rowlast[rt] = r < u.rows ? u.n - u.wp + r / a.group : -1;
+      if (!WIDE) rowlast[rt] = last_visible(rt);
     }
   }
   if constexpr (QREG) {
@@ -206,6 +223,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
     if (tile0 + kAhead < span_end) tiles.issue(tile0 + kAhead, kbuf);
     const bool masked = tile0 + 32 > first_masked_key;
 
+    float colsum = 0.f;
     // Logits of one row tile against this key tile.  Row tiles past the unit's rows hold zero
     // queries: they are computed like the others and their results are never used.
     auto logits = [&](int rt) {
@@ -222,9 +240,10 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
       }
       return acc;
     };
-    // The MFMA chain of row tile rt + 1 is issued before the softmax arithmetic of row tile rt, so the
-    // matrix pipe and the vector ALU of this wavefront work at the same time.
-    float colsum = 0.f;
+    // The MFMA chain of row tile rt + 1 is issued before the softmax arithmetic of row tile rt: its
+    // last MFMAs run under that arithmetic, and the other wavefront of the SIMD fills the rest of
+    // the chain (a wavefront issues in order, so a dependent chain holds up what follows it).
+    // Issuing the chain one MFMA at a time between slices of the arithmetic measured no faster here.
     f32x16 acc = logits(0);
 #pragma unroll
     for (int rt = 0; rt < RT_T; ++rt) {
@@ -232,10 +251,11 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
       if (rt + 1 < RT_T) nxt = logits(rt + 1);
       if (kStats) {
         if (masked) {
+          const int rlast = WIDE ? last_visible(rt) : rowlast[WIDE ? 0 : rt];
 #pragma unroll
           for (int i = 0; i < 16; ++i) {
             const int key = tile0 + (i >> 2) * 8 + hi * 4 + (i & 3);
-            if (key > rowlast[rt]) acc[i] = kNegInf;
+            if (key > rlast) acc[i] = kNegInf;
           }
         }
         if (kSpill) {
@@ -433,7 +453,7 @@ hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, h
 template <typename T, int D>
 hipError_t launch_wide_stats_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream) {
   if constexpr (Shape<T, D>::kChunks * 4 <= 32) {
-    const dim3 grid(g.nspans, g.units, g.rows_pad / 128);
+    const dim3 grid((a.wide_items + 7) / 8 * 8);
     hipLaunchKernelGGL((score_stream_kernel<T, D, 4, 1, true, true>), grid, dim3(256), 0, stream, a);
     return hipGetLastError();
   }

@@ -9,8 +9,8 @@
 //   pass 1  score_stream_kernel<.., WIDE> (score_qreg.hip): a workgroup keeps one block of 128 score
 //           rows in registers and streams its span of keys; grid.z walks the row blocks.
 //   merge   score_merge_kernel: b_r = reference + log2(sum * G) per row.
-//   pass 2  score_colsum_wide_kernel (here): a workgroup keeps 256 KEYS in registers (each
-//           wavefront the MFMA fragments of two 32-key tiles) and streams the window queries, four
+//   pass 2  score_colsum_wide_kernel (here): a workgroup keeps 512 KEYS in registers (each
+//           wavefront the MFMA fragments of four 32-key tiles) and streams the window queries, four
 //           row tiles per stage, through a double-buffered LDS ring filled by direct-to-LDS
 //           loads, together with the rows' exponent offsets b_r.  A lane owns one key column, so
 //           the sum over rows is a chain of register adds and the scores leave the kernel once.
@@ -25,10 +25,12 @@
 #include "score_common.h"
 #include "tile_sum.h"
 
+#include <type_traits>
+
 namespace rfkv {
 namespace {
 
-constexpr int kWideKT = 2;             // key tiles a wavefront keeps
+constexpr int kWideKT = 4;             // key tiles a wavefront keeps
 constexpr int kWideStage = 4;          // row tiles per stage, one brought in by each wavefront
 constexpr int kWideKeys = 4 * kWideKT * 32;    // keys per workgroup
 
@@ -38,7 +40,7 @@ constexpr size_t wide_lds_bytes() {
 }
 
 // 4 x 16 bytes at consecutive 32-byte steps: the exponent offsets of the 16 rows a lane's accumulators hold
-__device__ __forceinline__ void read_row_offsets(float4* bv, const float* tile, int hi) {
+__device__ __forceinline__ void read_row_offsets(float* bv, const float* tile, int hi) {
   uint32_t addr[4];
   const uint32_t base = lds_offset(tile) + hi * 16;
 #pragma unroll
@@ -46,7 +48,12 @@ __device__ __forceinline__ void read_row_offsets(float4* bv, const float* tile, 
   uint4 raw[4];
   lds_read_b128_x4(raw, addr);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) bv[j] = __builtin_bit_cast(float4, raw[j]);
+  for (int j = 0; j < 4; ++j) {
+    bv[4 * j + 0] = __uint_as_float(raw[j].x);
+    bv[4 * j + 1] = __uint_as_float(raw[j].y);
+    bv[4 * j + 2] = __uint_as_float(raw[j].z);
+    bv[4 * j + 3] = __uint_as_float(raw[j].w);
+  }
 }
 
 template <typename T, int D>
@@ -56,9 +63,18 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
   extern __shared__ __attribute__((aligned(1024))) unsigned char wsm[];
   unsigned char* qs = wsm;                                               // [2][kWideStage] query row tiles
   float* bs = reinterpret_cast<float*>(wsm + 2 * kWideStage * kTileBytes);   // [2][kWideStage][64] offsets
-  const int by = blockIdx.y;
+  // One-dimensional grid, work item w = key block + blocks * unit.  Workgroups go to the 8 XCDs in
+  // turn, so workgroup g takes item (g % 8) * chunk + g / 8: the workgroups resident on one XCD are
+  // neighbouring key blocks of one unit and stream the same window queries, which then come from
+  // that XCD's L2 rather than from memory once per workgroup.
+  const int kblocks = (a.span_colsum + kWideKeys - 1) / kWideKeys;
+  const int items = kblocks * a.units;
+  const int chunk = (items + 7) >> 3;
+  const int w = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= chunk || w >= items) return;
+  const int by = w / kblocks;
   const Unit u = load_unit(a, by);
-  const int kb0 = blockIdx.x * kWideKeys;
+  const int kb0 = (w - by * kblocks) * kWideKeys;
   if (kb0 >= u.n) return;                              // uniform for the whole workgroup
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -68,17 +84,20 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
                                ((int64_t)u.s0 * a.k_stride_tok + (int64_t)u.h * a.k_stride_head) * T::kBytes;
   const TileLoader<T, D> tiles(kunit, a.k_stride_tok * T::kBytes, u.n, lane);
 
-  // this wavefront's keys: two tiles, staged once through the (still unused) query ring
+  // this wavefront's keys, staged two tiles at a time through its two slots of the (still unused) query ring
   uint4 kf[kWideKT][S::kChunks];
   int t0[kWideKT];
+  static_assert(kWideKT % 2 == 0 && 2 * kWideStage == 2 * 4, "two private ring slots per wavefront");
 #pragma unroll
-  for (int kt = 0; kt < kWideKT; ++kt) {
-    t0[kt] = kb0 + (wave * kWideKT + kt) * 32;         // tiles past the end re-read the last key; never stored
-    tiles.issue(t0[kt], qs + (wave * kWideKT + kt) * kTileBytes);
+  for (int kt = 0; kt < kWideKT; ++kt) t0[kt] = kb0 + (wave * kWideKT + kt) * 32;   // tiles past the end re-read the last key; never stored
+#pragma unroll
+  for (int half = 0; half < kWideKT / 2; ++half) {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) tiles.issue(t0[half * 2 + e], qs + (wave * 2 + e) * kTileBytes);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int e = 0; e < 2; ++e) read_tile_frags<T, D>(kf[half * 2 + e], qs + (wave * 2 + e) * kTileBytes, col, hi);
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#pragma unroll
-  for (int kt = 0; kt < kWideKT; ++kt) read_tile_frags<T, D>(kf[kt], qs + (wave * kWideKT + kt) * kTileBytes, col, hi);
   __syncthreads();                                     // the ring is free for the queries
 
   // Row r = t * G + g sees key i iff i <= n - wp + t, i.e. iff r >= G * (i - (n - wp)).
@@ -113,6 +132,54 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
 #pragma unroll
   for (int kt = 0; kt < kWideKT; ++kt) colsum[kt] = 0.f;
 
+  // One stage: kWideStage row tiles against the wavefront's kWideKT key tiles, item by item
+  // (row tile j, key tile kt), j-major.  A wavefront issues in order, and a dependent MFMA waits
+  // at the issue stage for the one before it, so a chain issued back to back holds up every
+  // instruction behind it.  The chain of item it + 1 is therefore issued one MFMA at a time
+  // between slices of item it's softmax arithmetic (fma, exp2, add per element), with scheduling
+  // barriers so that the compiler keeps that order: the matrix pipe works in the shadow of the
+  // vector ALU.
+  auto stage_compute = [&](int s, auto masked_tag) {
+    constexpr bool kMasked = decltype(masked_tag)::value;
+    constexpr int kItems = kWideStage * kWideKT;
+    constexpr int kSlice = 16 / S::kChunks;            // elements of this item per chunk of the next chain
+    static_assert(kSlice * S::kChunks == 16, "the chain divides the 16 accumulators evenly");
+    const int buf = s & 1;
+    uint4 qf[2][S::kChunks];
+    float bv[16];
+    read_tile_frags<T, D>(qf[0], qs + (buf * kWideStage) * kTileBytes, col, hi);
+    f32x16 acc = logits(qf[0], kf[0]);
+#pragma unroll
+    for (int it = 0; it < kItems; ++it) {
+      const int j = it / kWideKT, kt = it % kWideKT;
+      const bool more = it + 1 < kItems;
+      const int j2 = (it + 1) / kWideKT, kt2 = (it + 1) % kWideKT;
+      if (more && kt2 == 0) read_tile_frags<T, D>(qf[j2 & 1], qs + (buf * kWideStage + j2) * kTileBytes, col, hi);
+      if (kt == 0) read_row_offsets(bv, bs + (buf * kWideStage + j) * 64, hi);
+      // accumulator i of this lane: row (s * kWideStage + j) * 32 + (i / 4) * 8 + hi * 4 + i % 4, key t0[kt] + col;
+      // visible iff (i / 4) * 8 + i % 4 >= rel
+      const int rel = rmin[kt] - (s * kWideStage + j) * 32 - hi * 4;
+      f32x16 nxt;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) nxt[i] = 0.f;
+      float sum = colsum[kt];
+#pragma unroll
+      for (int ch = 0; ch < S::kChunks; ++ch) {
+        if (more) nxt = mma_chunk<T>(qf[j2 & 1][ch], kf[kt2][ch], nxt);     // rows x keys: a lane owns one key
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int e = 0; e < kSlice; ++e) {
+          const int i = ch * kSlice + e;
+          const float p = fast_exp2(__builtin_fmaf(acc[i], c, -bv[i]));
+          sum += (!kMasked || (i / 4) * 8 + i % 4 >= rel) ? p : 0.f;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      colsum[kt] = sum;
+      acc = nxt;
+    }
+  };
+
   if (stage_begin < stage_end) issue_stage(stage_begin);
   for (int s = stage_begin; s < stage_end; ++s) {
     // stage s has landed (every wavefront waits for its own loads, then all meet); the other half
@@ -120,47 +187,8 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     if (s + 1 < stage_end) issue_stage(s + 1);
-    const int buf = s & 1;
-    const bool masked = s * (kWideStage * 32) < wave_rmax;
-    constexpr int kItems = kWideStage * kWideKT;       // (row tile j, key tile kt), j-major
-    uint4 qf[2][S::kChunks];
-    float4 bv[4];
-    read_tile_frags<T, D>(qf[0], qs + (buf * kWideStage) * kTileBytes, col, hi);
-    f32x16 acc = logits(qf[0], kf[0]);
-#pragma unroll
-    for (int it = 0; it < kItems; ++it) {
-      const int j = it / kWideKT, kt = it % kWideKT;
-      // the MFMA chain of the next item is issued before this item's softmax arithmetic
-      f32x16 nxt = acc;
-      if (it + 1 < kItems) {
-        const int j2 = (it + 1) / kWideKT, kt2 = (it + 1) % kWideKT;
-        if (kt2 == 0) read_tile_frags<T, D>(qf[j2 & 1], qs + (buf * kWideStage + j2) * kTileBytes, col, hi);
-        nxt = logits(qf[j2 & 1], kf[kt2]);
-      }
-      if (kt == 0) read_row_offsets(bv, bs + (buf * kWideStage + j) * 64, hi);
-      // accumulator i of this lane: row (s * kWideStage + j) * 32 + (i / 4) * 8 + hi * 4 + i % 4, key t0[kt] + col
-      if (!masked) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          colsum[kt] += fast_exp2(__builtin_fmaf(acc[q * 4 + 0], c, -bv[q].x));
-          colsum[kt] += fast_exp2(__builtin_fmaf(acc[q * 4 + 1], c, -bv[q].y));
-          colsum[kt] += fast_exp2(__builtin_fmaf(acc[q * 4 + 2], c, -bv[q].z));
-          colsum[kt] += fast_exp2(__builtin_fmaf(acc[q * 4 + 3], c, -bv[q].w));
-        }
-      } else {
-        const int rel = rmin[kt] - (s * kWideStage + j) * 32 - hi * 4;     // visible iff (i / 4) * 8 + i % 4 >= rel
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const float p0 = fast_exp2(__builtin_fmaf(acc[q * 4 + 0], c, -bv[q].x));
-          const float p1 = fast_exp2(__builtin_fmaf(acc[q * 4 + 1], c, -bv[q].y));
-          const float p2 = fast_exp2(__builtin_fmaf(acc[q * 4 + 2], c, -bv[q].z));
-          const float p3 = fast_exp2(__builtin_fmaf(acc[q * 4 + 3], c, -bv[q].w));
-          colsum[kt] += (q * 8 + 0 >= rel ? p0 : 0.f) + (q * 8 + 1 >= rel ? p1 : 0.f) +
-                        (q * 8 + 2 >= rel ? p2 : 0.f) + (q * 8 + 3 >= rel ? p3 : 0.f);
-        }
-      }
-      acc = nxt;
-    }
+    if (s * (kWideStage * 32) < wave_rmax) stage_compute(s, std::true_type{});
+    else stage_compute(s, std::false_type{});
   }
 
   float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
@@ -180,8 +208,8 @@ hipError_t launch_colsum_typed(const Geometry& g, const ScoreArgs& a, hipStream_
   constexpr size_t lds = wide_lds_bytes<T, D>();
   hipError_t e = allow_lds(score_colsum_wide_kernel<T, D>, lds);
   if (e != hipSuccess) return e;
-  const dim3 grid((g.max_seqlen + kWideKeys - 1) / kWideKeys, g.units);
-  hipLaunchKernelGGL((score_colsum_wide_kernel<T, D>), grid, dim3(256), lds, stream, a);
+  const int items = (g.max_seqlen + kWideKeys - 1) / kWideKeys * g.units;
+  hipLaunchKernelGGL((score_colsum_wide_kernel<T, D>), dim3((items + 7) / 8 * 8), dim3(256), lds, stream, a);
   return hipGetLastError();
 }
 

@@ -45,3 +45,37 @@ def test_wide_window_rejections():
     p = B.make_params(1, 8, 2, 128, 20000, "bf16")            # 80000 rows
     st = B.rfkv_compress_layer(p, t, t, t, cu, t, None, t, t, None, t, t, 200, t, 1 << 16, check=False)
     assert st == B.RFKV_UNSUPPORTED
+
+
+def test_wide_window_full_size_one_percent():
+    """The headline shape (32 q / 8 kv heads, d = 128, n = 32768) with the ablation's k = 1 % of n
+    (328 window positions, 1312 score rows per KV head): every score, the selection and the
+    compacted rows against the oracle, in the launch configuration the benchmark times."""
+    cfg = W.Config("llama3-8b-32k-w328", 32, 32, 8, 128, 328, "bf16", batch=1, context=32768)
+    layer = W.make_layer("H", 1, cfg=cfg)
+    dl = H.DeviceLayer(layer, kv_layout="head_major")
+    dl.compress()
+    gpu = dl.results()
+    rep = H.compare_layer(layer, gpu, B.RANK_POSITION)
+    print(rep)
+    # mass conservation, a property of Eq. 2 that holds at any size: sum_i cnt_i A'[i] = w per head
+    n, w = 32768, 328
+    cnt = np.minimum(w, n - np.arange(n))
+    mass = (gpu["scores"].astype(np.float64) * cnt).sum(axis=1)
+    assert np.abs(mass - w).max() < 1e-3 * w
+
+
+def test_wide_window_ten_percent():
+    """k = 10 % of n at n = 16384 (1638 window positions, 6552 score rows per KV head, 52 blocks of 128
+    rows): full parity and mass conservation per head."""
+    n, w, Hq, Hkv, d = 16384, 1638, 32, 8, 128
+    cfg = W.Config("t", 1, Hq, Hkv, d, w, "bf16", batch=1, context=n)
+    layer = W.make_layer("H", 2, cfg=cfg)
+    dl = H.DeviceLayer(layer, kv_layout="head_major")
+    dl.compress()
+    gpu = dl.results()
+    rep = H.compare_layer(layer, gpu, B.RANK_POSITION)
+    print(rep)
+    cnt = np.minimum(w, n - np.arange(n))
+    mass = (gpu["scores"].astype(np.float64) * cnt).sum(axis=1)
+    assert np.abs(mass - w).max() < 1e-3 * w
