@@ -180,7 +180,8 @@ def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, reps=6):
                             n_layers * cfg.n_kv_heads, False)
     del dl
     torch.cuda.empty_cache()
-    return {"layers_per_call": n_layers, "ms_per_call": round(ms, 4), "ms_per_layer": round(ms / n_layers, 5),
+    return {"layers_per_call": n_layers, "retained_fraction": round(kept / (n_layers * n * cfg.n_kv_heads), 4),
+            "ms_per_call": round(ms, 4), "ms_per_layer": round(ms / n_layers, 5),
             "tokens_per_s_per_layer_pass": round(n / (ms / n_layers * 1e-3), 1),
             "pipeline_frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 

@@ -54,9 +54,19 @@ int32_t choose_span(int64_t total_tokens, int32_t n_kv_heads, int max_iters) {
   return (int32_t)span;
 }
 
+// The wide-window kernels (row-blocked statistics, key-resident column sums) take every window the
+// streaming kernels cannot hold, and, where their 256-byte row limit allows, every window of more
+// than 128 score rows: from 5 to 8 row tiles they already beat the streaming kernels, which would
+// have to re-read part of the queries from LDS for every key tile.
+#ifndef RFKV_WIDE_ABOVE
+#define RFKV_WIDE_ABOVE 128
+#endif
 bool wide_window(const rfkv_params* p) {
   const int64_t rows = (int64_t)p->window * (p->n_q_heads / p->n_kv_heads);
-  return (rows + 31) / 32 * 32 > RFKV_MAX_SCORE_ROWS;
+  const int64_t rows32 = (rows + 31) / 32 * 32;
+  const int eb = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
+  if (rows32 > RFKV_MAX_SCORE_ROWS) return true;
+  return rows32 > RFKV_WIDE_ABOVE && p->head_dim * eb <= 256;
 }
 
 rfkv_status check_params(const rfkv_params* p) {

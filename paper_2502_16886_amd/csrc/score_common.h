@@ -292,17 +292,6 @@ __device__ __forceinline__ void read_tile_frags(uint4* kf, const unsigned char* 
   lds_read_b128_n<S::kChunks>(kf, addr);
 }
 
-// Fragments of one row tile of queries staged in padded rows (row stride kLdsRowBytes).
-template <typename T, int D>
-__device__ __forceinline__ void read_q_frags(uint4* qf, const unsigned char* rows, int col, int hi) {
-  using S = Shape<T, D>;
-  const uint32_t base = lds_offset(rows) + col * S::kLdsRowBytes + hi * S::kHalfBytes;
-  uint32_t addr[S::kChunks];
-#pragma unroll
-  for (int ch = 0; ch < S::kChunks; ++ch) addr[ch] = base + ch * 16;
-  lds_read_b128_n<S::kChunks>(qf, addr);
-}
-
 }  // namespace
 
 // defined in score.hip

@@ -1,16 +1,14 @@
-// Streaming scoring kernels for up to 256 score rows per KV head (window * G <= 256: the Llama /
-// Mistral shapes with a 32-row window, Qwen's G = 7, a 64-row window, and the paper's own k = 1),
-// Sec. 3.2 "Reducing Overhead", Eq. 2.
+// Streaming scoring kernels for up to 128 score rows per KV head (window * G <= 128: the Llama /
+// Mistral shapes with a 32-row window and the paper's own k = 1), Sec. 3.2 "Reducing Overhead",
+// Eq. 2; the statistics kernel also serves the wide-window path (score_wide.hip) block by block.
 //
 // Same two-pass scheme as score.hip (row statistics, merge, column reduction); what differs is
 // where the operands live:
 //
-//   Q   up to 4 row tiles: every wavefront keeps the MFMA fragments of ALL window rows in
-//       registers for the whole kernel (4 row tiles x 8 chunks x 16 bytes per lane for bf16,
-//       d = 128).  One wavefront per row tile brings the tile in by direct-to-LDS loads, in the
-//       layout of a key tile, into the LDS that afterwards serves as the second set of key-tile
-//       buffers.  Up to 8 row tiles: the queries stay in LDS (padded rows) and 8 wavefronts with
-//       one tile buffer each read them at every use.
+//   Q   every wavefront keeps the MFMA fragments of ALL its (up to 4) row tiles in registers for
+//       the whole kernel (4 row tiles x 8 chunks x 16 bytes per lane for bf16, d = 128).  One
+//       wavefront per row tile brings the tile in by direct-to-LDS loads, in the layout of a key
+//       tile, into the LDS that afterwards serves as the second set of key-tile buffers.
 //   K   streamed through wavefront-private LDS buffers of one 32-key tile each by direct-to-LDS
 //       loads (global_load_lds_dwordx4): each instruction moves 1 KB of consecutive key bytes, so
 //       HBM/L2 requests are whole cache lines, and no VGPRs are held while the data is in flight.
@@ -35,29 +33,24 @@ namespace {
 // PASS 3: pass 1 that also writes the logits of up to kSpillRows rows (the paper's k = 1: the
 //         G rows of the last query position), so that the scores follow from 4 * rows bytes per key
 //         instead of a second pass over the keys (score_spill_reduce_kernel).
-// QREG:   window-query fragments in registers (4 wavefronts, two tile buffers each, the second
-//         set reusing the query staging area) or, for more than 4 row tiles, read from LDS at every
-//         use (8 wavefronts, one tile buffer each).
 // WIDE:   pass 1 over one block of RT_T row tiles out of many (blockIdx.z picks the block): the
 //         statistics of windows with more rows than a workgroup can hold (the large windows of the
 //         paper's ablation of k, "Attention Matrix Reduction": k = 1 %, 5 %, 10 % of n).
-template <typename T, int D, int RT_T, int PASS, bool QREG, bool WIDE = false>
-__global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_kernel(ScoreArgs a) {
+template <typename T, int D, int RT_T, int PASS, bool WIDE = false>
+__global__ __launch_bounds__(256, 2) void score_stream_kernel(ScoreArgs a) {
   using S = Shape<T, D>;
   constexpr bool kStats = PASS != 2;                   // pass 1 (and 3: pass 1 that also keeps its logits)
   constexpr bool kSpill = PASS == 3;
-  static_assert(!kSpill || (RT_T == 1 && QREG), "logits are kept for a single row tile only");
-  static_assert(!WIDE || (PASS == 1 && QREG), "row blocks exist for the statistics pass only");
-  constexpr int kWaves = QREG ? 4 : 8;
+  static_assert(!kSpill || RT_T == 1, "logits are kept for a single row tile only");
+  static_assert(!WIDE || PASS == 1, "row blocks exist for the statistics pass only");
+  constexpr int kWaves = 4;
   constexpr int kThreads = kWaves * 64;
   constexpr int kTileBytes = 32 * S::kRowBytes;
   constexpr int kLoads = kTileBytes / 1024;            // direct-to-LDS instructions per tile
   // distinct LDS objects, so that reads of one are known not to touch a buffer with loads in flight
   __shared__ __attribute__((aligned(1024))) unsigned char smem[kWaves * kTileBytes];   // tile buffers
-  // QREG: the window queries on their way to registers, then the odd tiles; otherwise nothing
-  __shared__ __attribute__((aligned(1024))) unsigned char smem_b[QREG ? kWaves * kTileBytes : 1024];
-  // !QREG: the window queries, padded rows, for the whole kernel
-  __shared__ __attribute__((aligned(16))) unsigned char qsm[QREG ? 16 : RT_T * 32 * S::kLdsRowBytes];
+  // the window queries on their way to registers, then the odd tiles
+  __shared__ __attribute__((aligned(1024))) unsigned char smem_b[kWaves * kTileBytes];
   __shared__ __attribute__((aligned(256))) float bsm[RT_T * 32 < 64 ? 64 : RT_T * 32];   // pass 2: exponent offset per row
   __shared__ __attribute__((aligned(16))) int rlast_s[RT_T * 32];    // pass 2: last visible key per row
   int bx = blockIdx.x, by = blockIdx.y, rblock = 0;
@@ -87,7 +80,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   const float c = a.c;
   const float kNegInf = -__builtin_inff();
   unsigned char* kbuf0 = smem + wave * kTileBytes;     // this wavefront's tile buffer(s)
-  unsigned char* kbuf1 = QREG ? smem_b + wave * kTileBytes : kbuf0;
+  unsigned char* kbuf1 = smem_b + wave * kTileBytes;
   const unsigned char* kunit = static_cast<const unsigned char*>(a.k) +
                                ((int64_t)u.s0 * a.k_stride_tok + (int64_t)u.h * a.k_stride_head) * T::kBytes;
   const int64_t tok_bytes = a.k_stride_tok * T::kBytes;
@@ -96,14 +89,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
 
   int tile0 = span_begin + wave * 32;
   const TileLoader<T, D> tiles(kunit, tok_bytes, u.n, lane);
-#ifndef RFKV_QLDS_HELD
-#define RFKV_QLDS_HELD 4
-#endif
-  // row tiles whose query fragments live in registers for the whole kernel: all of them (QREG), or,
-  // with the queries resident in LDS, as many as pass 2's register budget allows (pass 1 has none to spare)
-  constexpr int kHeld = QREG ? RT_T : ((PASS == 2 && RFKV_QLDS_HELD <= RT_T) ? RFKV_QLDS_HELD : 0);
-  constexpr int kQRegTiles = kHeld > 0 ? kHeld : 1;
-  uint4 qf[kQRegTiles][S::kChunks];
+  uint4 qf[RT_T][S::kChunks];                          // query fragments of every row tile, for the whole kernel
   float mc[RT_T], l[RT_T];
   int rowlast[WIDE ? 1 : RT_T];                         // last key a lane's row sees (WIDE: worked out where it is needed)
   auto last_visible = [&](int rt) {
@@ -118,7 +104,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
       if (!WIDE) rowlast[rt] = last_visible(rt);
     }
   }
-  if constexpr (QREG) {
+  {
     // Everything the loop needs arrives by direct-to-LDS loads, issued at once: the first key tile
     // (the bulk: memory is busy from the start), pass 2's per-row exponent offsets (64 per
     // wavefront) and one row tile of window queries per wavefront into the second buffer set.
@@ -143,64 +129,6 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
     for (int rt = 0; rt < RT_T; ++rt) read_tile_frags<T, D>(qf[rt], smem_b + rt * kTileBytes, col, hi);
     __syncthreads();                                   // the query tiles become the second buffer set
     if (tile0 + kStep < span_end) tiles.issue(tile0 + kStep, kbuf1);
-  } else {
-    // The window queries (row r = t * G + g of this KV head) and pass 2's per-row exponent offsets
-    // are staged before the first key tile is requested: with a direct-to-LDS load in flight the
-    // compiler makes every use of an ordinarily loaded register wait for all loads.
-    float bmine = __builtin_inff();
-    if (PASS == 2 && threadIdx.x < RT_T * 32 && (int)threadIdx.x < a.rows_pad)
-      bmine = a.bvec[(int64_t)by * a.rows_pad + threadIdx.x];
-    constexpr int kCpr = S::kRowBytes / 16;
-    constexpr int kQPerThread = RT_T * 32 * kCpr / kThreads;
-    static_assert(kQPerThread * kThreads == RT_T * 32 * kCpr, "query staging must divide evenly");
-    static_assert(kThreads % kCpr == 0, "a thread keeps its chunk column from one piece to the next");
-    uint4 qv[kQPerThread];
-    {
-      // thread's piece j: row r0 + j * kRowStep, chunk ch.  (t, g) = (r / G, r % G) advance without
-      // a division per piece; rows past the unit's last are loaded from the last row (so that no
-      // load hangs on a branch) and zeroed when they are staged.
-      const unsigned char* qbase = static_cast<const unsigned char*>(a.q);
-      constexpr int kRowStep = kThreads / kCpr;
-      const int ch = threadIdx.x % kCpr;
-      const int dt = kRowStep / a.group, dg = kRowStep - dt * a.group;
-      int r = threadIdx.x / kCpr;
-      int t = r / a.group, g = r - t * a.group;
-      const int t_last = (u.rows - 1) / a.group, g_last = (u.rows - 1) - t_last * a.group;
-#pragma unroll
-      for (int j = 0; j < kQPerThread; ++j) {
-        const bool in = r < u.rows;
-        const int tt = in ? t : t_last, gg = in ? g : g_last;
-        const int64_t off = (int64_t)(u.q0 + tt) * a.q_stride_row + (int64_t)(u.h * a.group + gg) * a.q_stride_head;
-        qv[j] = *reinterpret_cast<const uint4*>(qbase + off * T::kBytes + ch * 16);
-        r += kRowStep;
-        t += dt;
-        g += dg;
-        if (g >= a.group) {
-          g -= a.group;
-          ++t;
-        }
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < kQPerThread; ++j) {
-      const int i = threadIdx.x + j * kThreads;
-      const int r = i / kCpr;
-      const uint4 v = r < u.rows ? qv[j] : make_uint4(0, 0, 0, 0);
-      lds_write_b128(qsm + r * S::kLdsRowBytes + (i - r * kCpr) * 16, v);
-    }
-    if (PASS == 2) {
-      static_assert(RT_T * 32 <= kThreads, "one table entry per thread");
-      if (threadIdx.x < RT_T * 32) {
-        const int r = threadIdx.x;
-        lds_write_b32(bsm + r, __float_as_uint(bmine));
-        lds_write_b32(rlast_s + r, (uint32_t)(r < u.rows ? u.n - u.wp + r / a.group : -1));
-      }
-    }
-    lds_writes_done();
-    __syncthreads();
-#pragma unroll
-    for (int rt = 0; rt < kHeld; ++rt) read_q_frags<T, D>(qf[rt], qsm + rt * 32 * S::kLdsRowBytes, col, hi);
-    if (tile0 < span_end) tiles.issue(tile0, kbuf0);
   }
   float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
 
@@ -209,17 +137,17 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
   constexpr int kStores = PASS == 2 ? 2 : (kSpill ? 4 : 0);
   for (int it = 0; tile0 < span_end; tile0 += kStep, ++it) {
     uint4 kf[S::kChunks];
-    unsigned char* kbuf = (QREG && (it & 1)) ? kbuf1 : kbuf0;
+    unsigned char* kbuf = (it & 1) ? kbuf1 : kbuf0;
     // Loads and stores complete in issue order.  Behind this tile's loads there are at most the next
     // tile's loads and (from the second iteration on) the stores of the iteration before.
-    if (QREG && tile0 + kStep < span_end) {
+    if (tile0 + kStep < span_end) {
       if (it == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads) : "memory");
       else asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kLoads + kStores) : "memory");
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     read_tile_frags<T, D>(kf, kbuf, col, hi);          // complete on return: the buffer is free
-    constexpr int kAhead = QREG ? 2 * kStep : kStep;
+    constexpr int kAhead = 2 * kStep;
     if (tile0 + kAhead < span_end) tiles.issue(tile0 + kAhead, kbuf);
     const bool masked = tile0 + 32 > first_masked_key;
 
@@ -232,9 +160,7 @@ __global__ __launch_bounds__(QREG ? 256 : 512, QREG ? 2 : 1) void score_stream_k
       for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
       for (int ch = 0; ch < S::kChunks; ++ch) {
-        const uint4 q = rt < kHeld ? qf[rt < kHeld ? rt : 0][ch]
-                             : *reinterpret_cast<const uint4*>(qsm + (rt * 32 + col) * S::kLdsRowBytes +
-                                                               hi * S::kHalfBytes + ch * 16);
+        const uint4 q = qf[rt][ch];
         acc = kStats ? mma_chunk<T>(kf[ch], q, acc)      // keys x rows: a lane owns one row
                         : mma_chunk<T>(q, kf[ch], acc);     // rows x keys: a lane owns one key
       }
@@ -377,7 +303,7 @@ __global__ __launch_bounds__(256) void score_spill_reduce_kernel(ScoreArgs a) {
 template <typename T, int D>
 hipError_t launch_stream_spill(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const dim3 grid(g.nspans, g.units);
-  hipLaunchKernelGGL((score_stream_kernel<T, D, 1, 3, true>), grid, dim3(256), 0, stream, a);
+  hipLaunchKernelGGL((score_stream_kernel<T, D, 1, 3>), grid, dim3(256), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (marks) marks->after(kKernelStats);
@@ -390,40 +316,31 @@ hipError_t launch_stream_spill(const Geometry& g, const ScoreArgs& a, hipStream_
   return e;
 }
 
-template <typename T, int D, int RT_T, bool QREG>
+template <typename T, int D, int RT_T>
 hipError_t launch_stream_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const dim3 grid(g.nspans, g.units);
-  const dim3 block(QREG ? 256 : 512);
-  hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 1, QREG>), grid, block, 0, stream, a);
+  const dim3 block(256);
+  hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 1>), grid, block, 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (marks) marks->after(kKernelStats);
   e = launch_score_merge(g, a, stream);
   if (e != hipSuccess) return e;
   if (marks) marks->after(kKernelMerge);
-  hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 2, QREG>), grid, block, 0, stream, a);
+  hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 2>), grid, block, 0, stream, a);
   e = hipGetLastError();
   if (marks && e == hipSuccess) marks->after(kKernelReduce);
   return e;
-}
-
-// Static LDS of the LDS-resident-query variant with 8 row tiles: queries + 8 tile buffers.
-template <typename T, int D>
-constexpr bool qlds8_fits() {
-  return 8 * 32 * Shape<T, D>::kLdsRowBytes + 8 * 32 * Shape<T, D>::kRowBytes + 4096 <= 64 * 1024 * 2 + 28 * 1024;
 }
 
 template <typename T, int D>
 hipError_t launch_stream_rt(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const int rt = g.rows_pad / 32;
   if (a.logits) return launch_stream_spill<T, D>(g, a, stream, marks);     // window * G <= kSpillRows
-  if (rt <= 1) return launch_stream_typed<T, D, 1, true>(g, a, stream, marks);
-  if (rt <= 2) return launch_stream_typed<T, D, 2, true>(g, a, stream, marks);
+  if (rt <= 1) return launch_stream_typed<T, D, 1>(g, a, stream, marks);
+  if (rt <= 2) return launch_stream_typed<T, D, 2>(g, a, stream, marks);
   if constexpr (Shape<T, D>::kChunks * 4 <= 32) {
-    if (rt <= 4) return launch_stream_typed<T, D, 4, true>(g, a, stream, marks);
-  }
-  if constexpr (qlds8_fits<T, D>()) {
-    if (rt <= 8) return launch_stream_typed<T, D, 8, false>(g, a, stream, marks);
+    if (rt <= 4) return launch_stream_typed<T, D, 4>(g, a, stream, marks);
   }
   return hipErrorInvalidValue;
 }
@@ -435,8 +352,7 @@ bool score_qreg_covers(const Geometry& g, bool bf16) {
   const int chunks = g.head_dim * g.elem_bytes / 32;    // 16-byte chunks of half a row
   (void)bf16;
   if (rt <= 2) return true;
-  if (rt <= 4 && chunks * 4 <= 32) return true;
-  return rt <= 8 && chunks <= 8;                        // LDS-resident queries: 256-byte rows only
+  return rt <= 4 && chunks * 4 <= 32;                   // 4 row tiles of fragments: 256-byte rows only
 }
 
 hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream,
@@ -454,7 +370,7 @@ template <typename T, int D>
 hipError_t launch_wide_stats_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream) {
   if constexpr (Shape<T, D>::kChunks * 4 <= 32) {
     const dim3 grid((a.wide_items + 7) / 8 * 8);
-    hipLaunchKernelGGL((score_stream_kernel<T, D, 4, 1, true, true>), grid, dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((score_stream_kernel<T, D, 4, 1, true>), grid, dim3(256), 0, stream, a);
     return hipGetLastError();
   }
   return hipErrorInvalidValue;
