@@ -194,6 +194,28 @@ RFKV_API rfkv_status rfkv_compress_layer_timed(const rfkv_params* params, const 
                                 float* kernel_ms_host);
 
 /*
+ * Scoring and the fused pass when the prefill already has the window rows' softmax normalisers.
+ * A causal attention forward pass returns, next to its output, the log-sum-exp of every query
+ * row: lse[t, hq] = ln sum_{i <= pos(t)} exp(scale * q[t, hq] . k[i]).  For the window rows this is
+ * exactly what the first of the two passes over K computes (the denominators of the softmax rows
+ * that Eq. 2 averages, Sec. 3.2 "Reducing Overhead"); given it, K is read once.
+ *   lse_win  device, float32 [sum_b min(window, n_b)][n_q_heads], contiguous, rows in the order of
+ *            q_win (natural logarithm, of the logits scaled by the same softmax_scale; causal).
+ * Everything else as in rfkv_score / rfkv_compress_layer, including workspace size and errors;
+ * RFKV_INVALID_ARG also when lse_win is null or not 4-byte aligned.  The scores are
+ * sum over rows of exp(logit - lse): they are only as good as the lse handed in.
+ */
+RFKV_API rfkv_status rfkv_score_lse(const rfkv_params* params, const void* q_win, const float* lse_win,
+                                    const void* k, const int32_t* cu_seqlens_host,
+                                    const int32_t* cu_seqlens_dev, float* scores, void* ws, size_t ws_bytes,
+                                    void* stream);
+RFKV_API rfkv_status rfkv_compress_layer_lse(const rfkv_params* params, const void* q_win, const float* lse_win,
+                                    const void* k, const void* v, const int32_t* cu_seqlens_host,
+                                    const int32_t* cu_seqlens_dev, float* scores_opt, int32_t* kept,
+                                    int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
+                                    int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Decode attention over the compacted cache -- the consumer of Alg. 1's compressed K / V (the
  * paper's efficiency comparison, Sec. 4.3, is between attention over the pruned and over the full
  * cache).  n_new new queries per sequence attend to every retained position of their sequence

@@ -21,7 +21,9 @@ Everything here is written from the paper's definitions, slowly and plainly:
 * compaction             -- gather of the retained K/V rows (Alg. 1, last steps),
   emitted in ascending original position;
 * decode attention       -- softmax(q K_c^T / sqrt(d)) V_c of new queries over the compacted
-  ragged cache, and the same over the full cache with evicted positions masked.
+  ragged cache, and the same over the full cache with evicted positions masked;
+* scores from given row normalisers -- the window rows' log-sum-exp as an input (what the
+  prefill's attention forward keeps), exp(logit - lse) in place of the softmax rows.
 
 All floating point is float64.  Inputs arrive already upcast (bf16/fp32 -> fp64
 is exact), so the oracle sees the same values the GPU sees.
@@ -33,7 +35,8 @@ definition-form == cumsum-form, exhaustive subset search for the score ranking,
 literal prefix enumeration for the position ranking, T = 0 / T >= 1 limits,
 attention over the compacted cache == masked full attention, and the decode
 attention against a library scaled-dot-product attention, a single-key cache and an
-all-equal-keys cache.  The paper
+all-equal-keys cache; the log-sum-exp against scipy's, scores from it against the
+softmax-row scores, and its shift law (lse + ln 2 halves a row's share).  The paper
 prints no worked numeric example of the rule, so there is no paper-value pin;
 results on the paper's real datasets/models are parity-unpinned.
 """
@@ -116,6 +119,86 @@ def oracle_score(q_win, k, cu_seqlens, n_q_heads, n_kv_heads, window, scale=None
         for h in range(Hkv):
             if n > 0:
                 out[h, s:e] = score_unit(q_win[q0:q0 + wp, h * G:(h + 1) * G, :], k[s:e, h, :], scale)
+        q0 += wp
+    return out
+
+
+# ----------------------------------------------------------------------------
+# scoring from given row normalisers  (Sec. 3.2 "Reducing Overhead", Eq. 2)
+#
+# The rows Eq. 2 averages are softmax rows of the causal attention the prefill has just computed;
+# an attention forward pass keeps each row's normaliser as a log-sum-exp.  These functions state
+# what the scores are when that normaliser is an INPUT: p[t, i] = exp(logit[t, i] - lse[t]).
+# ----------------------------------------------------------------------------
+def window_lse(q_rows: np.ndarray, k_rows: np.ndarray, scale: float) -> np.ndarray:
+    """ln sum_{i <= pos(t)} exp(scale q_t . k_i) for the last w' query positions, [w']."""
+    q_rows = np.asarray(q_rows, dtype=np.float64)
+    k_rows = np.asarray(k_rows, dtype=np.float64)
+    wp, n = q_rows.shape[0], k_rows.shape[0]
+    logits = (q_rows @ k_rows.T) * scale
+    out = np.empty(wp, dtype=np.float64)
+    for t in range(wp):
+        row = logits[t, : n - wp + t + 1]
+        m = row.max()
+        out[t] = m + np.log(np.exp(row - m).sum())
+    return out
+
+
+def oracle_window_lse(q_win, k, cu_seqlens, n_q_heads, n_kv_heads, window, scale=None):
+    """The log-sum-exp of every window row, [sum_b min(window, n_b), Hq] (rows as in q_win)."""
+    q_win = np.asarray(q_win, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    d = k.shape[2]
+    G = n_q_heads // n_kv_heads
+    if scale is None or scale == 0:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((q_win.shape[0], n_q_heads), dtype=np.float64)
+    q0 = 0
+    for b in range(len(cu_seqlens) - 1):
+        s, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        wp = min(window, e - s)
+        for hq in range(n_q_heads):
+            if wp > 0:
+                out[q0:q0 + wp, hq] = window_lse(q_win[q0:q0 + wp, hq, :], k[s:e, hq // G, :], scale)
+        q0 += wp
+    return out
+
+
+def score_unit_from_lse(q_unit: np.ndarray, k_unit: np.ndarray, lse_unit: np.ndarray, scale: float) -> np.ndarray:
+    """A' for one (sequence, KV head) with the rows' normalisers given.  q_unit [w', G, d],
+    k_unit [n, d], lse_unit [w', G]."""
+    wp, G, _ = q_unit.shape
+    n = k_unit.shape[0]
+    acc = np.zeros(n, dtype=np.float64)
+    for g in range(G):
+        logits = (q_unit[:, g, :] @ k_unit.T) * scale
+        P = np.zeros((wp, n), dtype=np.float64)
+        for t in range(wp):
+            last = n - wp + t
+            P[t, : last + 1] = np.exp(logits[t, : last + 1] - lse_unit[t, g])
+        acc += reduced_attention_vector(P)
+    return acc / G
+
+
+def oracle_score_lse(q_win, lse_win, k, cu_seqlens, n_q_heads, n_kv_heads, window, scale=None):
+    """Scores [Hkv, N] as oracle_score, with lse_win [sum_b min(window, n_b), Hq] given."""
+    q_win = np.asarray(q_win, dtype=np.float64)
+    lse_win = np.asarray(lse_win, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    N, Hkv, d = k.shape
+    G = n_q_heads // n_kv_heads
+    if scale is None or scale == 0:
+        scale = 1.0 / np.sqrt(d)
+    out = np.zeros((Hkv, N), dtype=np.float64)
+    q0 = 0
+    for b in range(len(cu_seqlens) - 1):
+        s, e = int(cu_seqlens[b]), int(cu_seqlens[b + 1])
+        n = e - s
+        wp = min(window, n)
+        for h in range(Hkv):
+            if n > 0:
+                out[h, s:e] = score_unit_from_lse(q_win[q0:q0 + wp, h * G:(h + 1) * G, :], k[s:e, h, :],
+                                                  lse_win[q0:q0 + wp, h * G:(h + 1) * G], scale)
         q0 += wp
     return out
 

@@ -85,6 +85,10 @@ def load_library() -> ctypes.CDLL:
     lib.rfkv_compress_layer.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     lib.rfkv_compress_layer_timed.restype = ctypes.c_int
     lib.rfkv_compress_layer_timed.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp, vp]
+    lib.rfkv_score_lse.restype = ctypes.c_int
+    lib.rfkv_score_lse.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.rfkv_compress_layer_lse.restype = ctypes.c_int
+    lib.rfkv_compress_layer_lse.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     lib.rfkv_decode_workspace_bytes.restype = sz
     lib.rfkv_decode_workspace_bytes.argtypes = [P, i32, i32]
     lib.rfkv_decode_attention.restype = ctypes.c_int
@@ -97,8 +101,8 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = ("rfkv_version", "rfkv_status_string", "rfkv_last_device_error", "rfkv_workspace_bytes",
                     "rfkv_score", "rfkv_select", "rfkv_compact", "rfkv_compress_layer",
-                    "rfkv_compress_layer_timed", "rfkv_decode_workspace_bytes", "rfkv_decode_attention",
-                    "rfkv_masked_attention")
+                    "rfkv_compress_layer_timed", "rfkv_score_lse", "rfkv_compress_layer_lse",
+                    "rfkv_decode_workspace_bytes", "rfkv_decode_attention", "rfkv_masked_attention")
 KERNEL_NAMES = ("score_stats", "score_merge", "score_reduce", "select", "compact")
 
 
@@ -150,6 +154,12 @@ def rfkv_score(params, q_win, k, cu_host, cu_dev, scores, ws, ws_bytes, stream=N
     return _check(st, "rfkv_score", check)
 
 
+def rfkv_score_lse(params, q_win, lse_win, k, cu_host, cu_dev, scores, ws, ws_bytes, stream=None, check=True) -> int:
+    st = load_library().rfkv_score_lse(ctypes.byref(params), _ptr(q_win), _ptr(lse_win), _ptr(k), _ptr(cu_host),
+                                       _ptr(cu_dev), _ptr(scores), _ptr(ws), int(ws_bytes), _stream(stream))
+    return _check(st, "rfkv_score_lse", check)
+
+
 def rfkv_select(params, scores, cu_host, cu_dev, kept, out_offsets, idx, ws, ws_bytes, stream=None,
                 check=True) -> int:
     st = load_library().rfkv_select(ctypes.byref(params), _ptr(scores), _ptr(cu_host), _ptr(cu_dev), _ptr(kept),
@@ -172,6 +182,15 @@ def rfkv_compress_layer(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, 
                                             _ptr(idx_opt), _ptr(k_out), _ptr(v_out), int(out_capacity_rows),
                                             _ptr(ws), int(ws_bytes), _stream(stream))
     return _check(st, "rfkv_compress_layer", check)
+
+
+def rfkv_compress_layer_lse(params, q_win, lse_win, k, v, cu_host, cu_dev, scores_opt, kept, out_offsets, idx_opt,
+                            k_out, v_out, out_capacity_rows, ws, ws_bytes, stream=None, check=True) -> int:
+    st = load_library().rfkv_compress_layer_lse(ctypes.byref(params), _ptr(q_win), _ptr(lse_win), _ptr(k), _ptr(v),
+                                                _ptr(cu_host), _ptr(cu_dev), _ptr(scores_opt), _ptr(kept),
+                                                _ptr(out_offsets), _ptr(idx_opt), _ptr(k_out), _ptr(v_out),
+                                                int(out_capacity_rows), _ptr(ws), int(ws_bytes), _stream(stream))
+    return _check(st, "rfkv_compress_layer_lse", check)
 
 
 def rfkv_compress_layer_timed(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, out_offsets, idx_opt,

@@ -166,10 +166,13 @@ float scale_times_log2e(const rfkv_params* p) {
   return (float)(s * 1.4426950408889634);
 }
 
-hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w, const void* q, const void* k,
-                     const int32_t* cu_dev, float* scores, hipStream_t stream, const Marks* marks = nullptr) {
+hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w, const void* q, const float* lse,
+                     const void* k, const int32_t* cu_dev, float* scores, hipStream_t stream,
+                     const Marks* marks = nullptr) {
   ScoreArgs a{};
   a.q = q;
+  a.lse = lse;
+  a.n_q_heads = g.n_q_heads;
   a.k = k;
   a.scores = scores;
   a.cu = cu_dev;
@@ -262,9 +265,9 @@ size_t rfkv_workspace_bytes(const rfkv_params* params, int64_t total_tokens, int
   return carve_workspace(g, nullptr).bytes + 256;
 }
 
-rfkv_status rfkv_score(const rfkv_params* params, const void* q_win, const void* k,
-                       const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores, void* ws,
-                       size_t ws_bytes, void* stream) {
+static rfkv_status score_impl(const rfkv_params* params, const void* q_win, const float* lse_win, bool with_lse,
+                              const void* k, const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
+                              float* scores, void* ws, size_t ws_bytes, void* stream) {
   rfkv_status st = check_params(params);
   if (st != RFKV_OK) return st;
   if ((st = check_strides(params, true, true, false)) != RFKV_OK) return st;
@@ -273,10 +276,24 @@ rfkv_status rfkv_score(const rfkv_params* params, const void* q_win, const void*
   if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
   if (total == 0) return RFKV_OK;
   if (!aligned16(q_win) || !aligned16(k) || !aligned16(scores) || !aligned16(ws)) return RFKV_INVALID_ARG;
+  if (with_lse && (!lse_win || (reinterpret_cast<uintptr_t>(lse_win) & 3u))) return RFKV_INVALID_ARG;
   const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
   const Workspace w = carve_workspace(g, ws);
   if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
-  return device_status(run_score(params, g, w, q_win, k, cu_seqlens_dev, scores, static_cast<hipStream_t>(stream)));
+  return device_status(run_score(params, g, w, q_win, with_lse ? lse_win : nullptr, k, cu_seqlens_dev, scores,
+                                 static_cast<hipStream_t>(stream)));
+}
+
+rfkv_status rfkv_score(const rfkv_params* params, const void* q_win, const void* k,
+                       const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores, void* ws,
+                       size_t ws_bytes, void* stream) {
+  return score_impl(params, q_win, nullptr, false, k, cu_seqlens_host, cu_seqlens_dev, scores, ws, ws_bytes, stream);
+}
+
+rfkv_status rfkv_score_lse(const rfkv_params* params, const void* q_win, const float* lse_win, const void* k,
+                           const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores, void* ws,
+                           size_t ws_bytes, void* stream) {
+  return score_impl(params, q_win, lse_win, true, k, cu_seqlens_host, cu_seqlens_dev, scores, ws, ws_bytes, stream);
 }
 
 rfkv_status rfkv_select(const rfkv_params* params, const float* scores, const int32_t* cu_seqlens_host,
@@ -446,8 +463,8 @@ rfkv_status rfkv_masked_attention(const rfkv_params* params, const void* q_new, 
                      ws_bytes, stream);
 }
 
-static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_win, const void* k, const void* v,
-                                const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores_opt,
+static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_win, const float* lse_win,
+                                bool with_lse, const void* k, const void* v, const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores_opt,
                                 int32_t* kept, int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
                                 int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream, const Marks* marks) {
   rfkv_status st = check_params(params);
@@ -466,13 +483,14 @@ static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_
   if (total > 0 && (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)))
     return RFKV_INVALID_ARG;
   if (scores_opt && !aligned16(scores_opt)) return RFKV_INVALID_ARG;
+  if (with_lse && total > 0 && (!lse_win || (reinterpret_cast<uintptr_t>(lse_win) & 3u))) return RFKV_INVALID_ARG;
   const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
   const Workspace w = carve_workspace(g, ws);
   if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* scores = scores_opt ? scores_opt : w.scores;
   hipError_t e = hipSuccess;
-  if (total > 0) e = run_score(params, g, w, q_win, k, cu_seqlens_dev, scores, s, marks);
+  if (total > 0) e = run_score(params, g, w, q_win, with_lse ? lse_win : nullptr, k, cu_seqlens_dev, scores, s, marks);
   if (e != hipSuccess) return device_status(e);
   e = run_select(params, g, w, scores, cu_seqlens_dev, kept, false, s);
   if (e != hipSuccess) return device_status(e);
@@ -497,8 +515,17 @@ rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, co
                                 const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev, float* scores_opt,
                                 int32_t* kept, int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
                                 int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream) {
-  return compress_layer_impl(params, q_win, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept, out_offsets,
-                             idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, nullptr);
+  return compress_layer_impl(params, q_win, nullptr, false, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept,
+                             out_offsets, idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, nullptr);
+}
+
+rfkv_status rfkv_compress_layer_lse(const rfkv_params* params, const void* q_win, const float* lse_win, const void* k,
+                                    const void* v, const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
+                                    float* scores_opt, int32_t* kept, int64_t* out_offsets, int32_t* idx_opt,
+                                    void* k_out, void* v_out, int64_t out_capacity_rows, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  return compress_layer_impl(params, q_win, lse_win, true, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept,
+                             out_offsets, idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, nullptr);
 }
 
 rfkv_status rfkv_compress_layer_timed(const rfkv_params* params, const void* q_win, const void* k, const void* v,
@@ -520,8 +547,8 @@ rfkv_status rfkv_compress_layer_timed(const rfkv_params* params, const void* q_w
   } else {
     // every slot gets a record first so that kernels this problem skips read as zero time
     for (int i = kNumKernels; i >= 0; --i) (void)hipEventRecord(m.ev[i], m.stream);      // start event last
-    st = compress_layer_impl(params, q_win, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept, out_offsets,
-                             idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, &m);
+    st = compress_layer_impl(params, q_win, nullptr, false, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept,
+                             out_offsets, idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, &m);
     e = hipStreamSynchronize(m.stream);
     if (st == RFKV_OK && e != hipSuccess) st = device_status(e);
     if (st == RFKV_OK) {

@@ -50,10 +50,11 @@ struct ScoreArgs {
   float* bvec;
   double* tile_sq;
   float* logits;          // null unless the first pass keeps its logits (window * G <= kSpillRows)
+  const float* lse;       // optional [window rows][Hq]: the rows' log-sum-exp from the prefill; no statistics pass then
   int64_t tiles_total;
   int64_t k_stride_tok, k_stride_head, q_stride_row, q_stride_head;
   int64_t total_tokens;
-  int32_t n_kv_heads, group, window, rows_pad, span, nspans;
+  int32_t n_q_heads, n_kv_heads, group, window, rows_pad, span, nspans;
   int32_t wide_items;     // wide window: work items of the statistics pass (row blocks * spans * units)
   int32_t units;
   int32_t span_colsum;    // wide window: the longest sequence (keys the column-sum grid covers per unit)

@@ -180,6 +180,22 @@ __global__ __launch_bounds__(kBlockThreads) void score_merge_kernel(ScoreArgs a)
         r < u.rows ? m + __log2f(sum * (float)a.group) : __builtin_inff();
 }
 
+// Row offsets from a log-sum-exp the caller already has (the causal attention forward of the prefill
+// returns ln sum_i exp(scale q.k_i) per query row): b_r = lse_r * log2(e) + log2(G), the value the
+// statistics pass and the merge would have produced.  Rows that do not exist get +inf.
+__global__ __launch_bounds__(kBlockThreads) void score_lse_offsets_kernel(ScoreArgs a) {
+  const Unit u = load_unit(a, blockIdx.y);
+  const int r = blockIdx.x * kBlockThreads + threadIdx.x;
+  if (r >= a.rows_pad) return;
+  float b = __builtin_inff();
+  if (r < u.rows) {
+    const int t = r / a.group, g = r - t * a.group;
+    const double lse = (double)a.lse[(int64_t)(u.q0 + t) * a.n_q_heads + u.h * a.group + g];
+    b = (float)(lse * 1.4426950408889634 + log2((double)a.group));
+  }
+  a.bvec[(int64_t)blockIdx.y * a.rows_pad + r] = b;
+}
+
 // ---------------------------------------------------------------------------------------------
 // pass 2: column sums of the normalised probabilities
 // ---------------------------------------------------------------------------------------------
@@ -287,18 +303,21 @@ template <typename T, int D>
 hipError_t launch_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const dim3 grid(g.nspans, g.units);
   const int rt = g.rows_pad / 32;
-  hipError_t e;
-  if (rt <= 1) e = launch_stats<T, D, 1>(g, a, grid, stream);
-  else if (rt <= 2) e = launch_stats<T, D, 2>(g, a, grid, stream);
-  else if (rt <= 4) e = launch_stats<T, D, 4>(g, a, grid, stream);
-  else if (rt <= 8) e = launch_stats<T, D, 8>(g, a, grid, stream);
-  else e = launch_stats<T, D, 16>(g, a, grid, stream);
+  hipError_t e = launch_score_offsets(g, a, stream, marks);    // from the caller's log-sum-exp, if given
   if (e != hipSuccess) return e;
-  if (marks) marks->after(kKernelStats);
+  if (!a.lse) {
+    if (rt <= 1) e = launch_stats<T, D, 1>(g, a, grid, stream);
+    else if (rt <= 2) e = launch_stats<T, D, 2>(g, a, grid, stream);
+    else if (rt <= 4) e = launch_stats<T, D, 4>(g, a, grid, stream);
+    else if (rt <= 8) e = launch_stats<T, D, 8>(g, a, grid, stream);
+    else e = launch_stats<T, D, 16>(g, a, grid, stream);
+    if (e != hipSuccess) return e;
+    if (marks) marks->after(kKernelStats);
 
-  e = launch_score_merge(g, a, stream);
-  if (e != hipSuccess) return e;
-  if (marks) marks->after(kKernelMerge);
+    e = launch_score_merge(g, a, stream);
+    if (e != hipSuccess) return e;
+    if (marks) marks->after(kKernelMerge);
+  }
 
   const size_t lds = (size_t)g.rows_pad * (Shape<T, D>::kLdsRowBytes + 8);
   e = allow_lds(score_reduce_kernel<T, D>, lds);
@@ -315,6 +334,18 @@ hipError_t launch_score_merge(const Geometry& g, const ScoreArgs& a, hipStream_t
   hipLaunchKernelGGL(score_merge_kernel, dim3((g.rows_pad + kMergeRows - 1) / kMergeRows, g.units),
                      dim3(kBlockThreads), 0, stream, a);
   return hipGetLastError();
+}
+
+hipError_t launch_score_offsets(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
+  if (!a.lse) return hipSuccess;
+  hipLaunchKernelGGL(score_lse_offsets_kernel, dim3((g.rows_pad + kBlockThreads - 1) / kBlockThreads, g.units),
+                     dim3(kBlockThreads), 0, stream, a);
+  const hipError_t e = hipGetLastError();
+  if (marks && e == hipSuccess) {
+    marks->after(kKernelStats);       // no statistics pass: zero time
+    marks->after(kKernelMerge);       // the offsets kernel stands in for the merge
+  }
+  return e;
 }
 
 hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks) {

@@ -296,6 +296,8 @@ __device__ __forceinline__ void read_tile_frags(uint4* kf, const unsigned char* 
 
 // defined in score.hip
 hipError_t launch_score_merge(const Geometry& g, const ScoreArgs& a, hipStream_t stream);
+// row offsets from the caller's log-sum-exp (a.lse) instead of statistics pass + merge; no-op without one
+hipError_t launch_score_offsets(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks);
 // defined in score_qreg.hip: the streaming kernels and the shapes they cover
 bool score_qreg_covers(const Geometry& g, bool bf16);
 hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks);

@@ -320,13 +320,17 @@ template <typename T, int D, int RT_T>
 hipError_t launch_stream_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const dim3 grid(g.nspans, g.units);
   const dim3 block(256);
-  hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 1>), grid, block, 0, stream, a);
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch_score_offsets(g, a, stream, marks);    // from the caller's log-sum-exp, if given
   if (e != hipSuccess) return e;
-  if (marks) marks->after(kKernelStats);
-  e = launch_score_merge(g, a, stream);
-  if (e != hipSuccess) return e;
-  if (marks) marks->after(kKernelMerge);
+  if (!a.lse) {
+    hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 1>), grid, block, 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (marks) marks->after(kKernelStats);
+    e = launch_score_merge(g, a, stream);
+    if (e != hipSuccess) return e;
+    if (marks) marks->after(kKernelMerge);
+  }
   hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 2>), grid, block, 0, stream, a);
   e = hipGetLastError();
   if (marks && e == hipSuccess) marks->after(kKernelReduce);
@@ -336,7 +340,8 @@ hipError_t launch_stream_typed(const Geometry& g, const ScoreArgs& a, hipStream_
 template <typename T, int D>
 hipError_t launch_stream_rt(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const int rt = g.rows_pad / 32;
-  if (a.logits) return launch_stream_spill<T, D>(g, a, stream, marks);     // window * G <= kSpillRows
+  // window * G <= kSpillRows: one pass that keeps its logits, unless the row offsets are given anyway
+  if (a.logits && !a.lse) return launch_stream_spill<T, D>(g, a, stream, marks);
   if (rt <= 1) return launch_stream_typed<T, D, 1>(g, a, stream, marks);
   if (rt <= 2) return launch_stream_typed<T, D, 2>(g, a, stream, marks);
   if constexpr (Shape<T, D>::kChunks * 4 <= 32) {

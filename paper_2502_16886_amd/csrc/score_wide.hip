@@ -216,12 +216,16 @@ hipError_t launch_colsum_typed(const Geometry& g, const ScoreArgs& a, hipStream_
 }  // namespace
 
 hipError_t launch_score_wide(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks) {
-  hipError_t e = launch_score_wide_stats(g, a, bf16, stream);
+  hipError_t e = launch_score_offsets(g, a, stream, marks);    // from the caller's log-sum-exp, if given
   if (e != hipSuccess) return e;
-  if (marks) marks->after(kKernelStats);
-  e = launch_score_merge(g, a, stream);
-  if (e != hipSuccess) return e;
-  if (marks) marks->after(kKernelMerge);
+  if (!a.lse) {
+    e = launch_score_wide_stats(g, a, bf16, stream);
+    if (e != hipSuccess) return e;
+    if (marks) marks->after(kKernelStats);
+    e = launch_score_merge(g, a, stream);
+    if (e != hipSuccess) return e;
+    if (marks) marks->after(kKernelMerge);
+  }
   if (bf16) e = g.head_dim == 64 ? launch_colsum_typed<Bf16, 64>(g, a, stream) : launch_colsum_typed<Bf16, 128>(g, a, stream);
   else e = g.head_dim == 64 ? launch_colsum_typed<Fp32, 64>(g, a, stream) : hipErrorInvalidValue;
   if (marks && e == hipSuccess) marks->after(kKernelReduce);

@@ -56,8 +56,13 @@ class DeviceLayer:
             assert kv_layout == "token_major"          # [N, Hkv, d]
         self.buf = B.alloc_layer_buffers(self.params, self.N, self.max_len)
 
-    def compress(self, stream=None):
+    def compress(self, stream=None, lse_win=None):
+        """One fused pass; with `lse_win` (device float32 [window rows, Hq]) through rfkv_compress_layer_lse."""
         b = self.buf
+        if lse_win is not None:
+            return B.rfkv_compress_layer_lse(self.params, self.q, lse_win, self.k, self.v, self.cu_host, self.cu_dev,
+                                             b.scores, b.kept, b.out_offsets, b.idx, b.k_out, b.v_out,
+                                             b.capacity_rows, b.ws, b.ws_bytes, stream)
         return B.rfkv_compress_layer(self.params, self.q, self.k, self.v, self.cu_host, self.cu_dev, b.scores,
                                      b.kept, b.out_offsets, b.idx, b.k_out, b.v_out, b.capacity_rows, b.ws,
                                      b.ws_bytes, stream)
