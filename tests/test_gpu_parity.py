@@ -42,15 +42,17 @@ def test_config0_tiny_fp32(mode):
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("dtype,Hq,Hkv,d,w,lens", [
     ("bf16", 8, 2, 128, 32, [777]),                 # several tiles + ragged tail
-    ("bf16", 28, 4, 128, 32, [1500, 333]),          # G = 7: 224 rows -> 7 row tiles
+    ("bf16", 28, 4, 128, 32, [1500, 333]),          # G = 7: 224 rows -> two 128-row blocks of the wide-window kernels
     ("bf16", 8, 8, 64, 16, [300, 1, 45, 1029]),     # G = 1, d = 64, a length-1 sequence
     ("fp32", 8, 2, 128, 8, [513, 64]),              # fp32 d = 128
     ("fp32", 4, 4, 64, 1, [260]),                   # the paper's k = 1
     ("bf16", 32, 8, 128, 64, [40, 2100]),           # n < window for the first sequence; 256 rows
     ("bf16", 4, 1, 128, 5, [3, 2, 4, 70]),          # n <= m (sinks) and odd window
     ("bf16", 8, 2, 128, 24, [900, 20]),             # 96 rows: padded to the 4-row-tile kernels
-    ("bf16", 8, 2, 128, 40, [1100]),                # 160 rows: padded to the 8-row-tile kernels
-    ("bf16", 8, 2, 64, 72, [700, 300]),             # 288 rows: beyond the streaming kernels
+    ("bf16", 8, 2, 128, 40, [1100]),                # 160 rows: wide-window kernels, second block mostly padding
+    ("bf16", 8, 2, 64, 72, [700, 300]),             # 288 rows, d = 64: three blocks
+    ("fp32", 8, 2, 128, 32, [600, 50]),             # fp32 d = 128, 128 rows: the register-operand kernels of score.hip
+    ("fp32", 8, 2, 128, 64, [450]),                 # fp32 d = 128, 256 rows (the most its 512-byte rows allow in LDS is 288)
     ("fp32", 8, 2, 64, 32, [640, 33]),              # fp32 d = 64, 128 rows
     ("bf16", 16, 4, 64, 32, [2050]),                # bf16 d = 64, 128 rows
     ("bf16", 32, 8, 128, 1, [1500, 333, 1, 40]),    # the paper's k = 1 with GQA 4: logits kept, one K pass
