@@ -108,23 +108,35 @@ __global__ __launch_bounds__(256, 2) void score_stream_kernel(ScoreArgs a) {
     // Everything the loop needs arrives by direct-to-LDS loads, issued at once: the first key tile
     // (the bulk: memory is busy from the start), pass 2's per-row exponent offsets (64 per
     // wavefront) and one row tile of window queries per wavefront into the second buffer set.
-    // No register depends on a load, so the compiler adds no wait of its own.
+    // No register depends on a load (the caller's log-sum-exp, if given, aside), so the compiler
+    // adds no wait of its own.  (Folding pass 1's per-span statistics here instead of in the merge
+    // kernel measured slower: every one of the 512 workgroups then starts 3-4 us later.)
     static_assert(RT_T <= kWaves && RT_T * 32 <= kWaves * 64, "one query tile and 64 offsets per wavefront");
     if (tile0 < span_end) tiles.issue(tile0, kbuf0);
     if (PASS == 2) {
       if (threadIdx.x < RT_T * 32)
         lds_write_b32(rlast_s + threadIdx.x,
                       (uint32_t)((int)threadIdx.x < u.rows ? u.n - u.wp + (int)threadIdx.x / a.group : -1));
-      if (wave * 64 < RT_T * 32) {
-        const float* src = a.bvec + (int64_t)by * a.rows_pad + min(wave * 64 + lane, a.rows_pad - 1);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(bsm + wave * 64), 4, 0, 0);
-      }
     }
     if (wave < RT_T) issue_q_tile_load<T, D>(a, u, (row0 >> 5) + wave, smem_b + wave * kTileBytes, lane);
+    if (PASS == 2 && !a.lse && wave * 64 < RT_T * 32) {
+      // the rows' exponent offsets from the merge kernel, 64 per wavefront
+      const float* src = a.bvec + (int64_t)by * a.rows_pad + min(wave * 64 + lane, a.rows_pad - 1);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                       (__attribute__((address_space(3))) void*)(bsm + wave * 64), 4, 0, 0);
+    }
+    float b_lse = __builtin_inff();
+    if (PASS == 2 && a.lse && (int)threadIdx.x < u.rows) {
+      // ... or from the caller's log-sum-exp (natural logarithm, scaled logits) of row (t, g):
+      // b_r = lse_r * log2(e) + log2(G), formed here rather than by a kernel of its own
+      const int r = threadIdx.x, t = r / a.group, g = r - t * a.group;
+      const double lse = (double)a.lse[(int64_t)(u.q0 + t) * a.n_q_heads + u.h * a.group + g];
+      b_lse = (float)(lse * 1.4426950408889634 + log2((double)a.group));
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     lds_writes_done();
     __syncthreads();
+    if (PASS == 2 && a.lse && threadIdx.x < RT_T * 32) bsm[threadIdx.x] = b_lse;      // +inf for rows that do not exist
 #pragma unroll
     for (int rt = 0; rt < RT_T; ++rt) read_tile_frags<T, D>(qf[rt], smem_b + rt * kTileBytes, col, hi);
     __syncthreads();                                   // the query tiles become the second buffer set
@@ -320,8 +332,8 @@ template <typename T, int D, int RT_T>
 hipError_t launch_stream_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream, const Marks* marks) {
   const dim3 grid(g.nspans, g.units);
   const dim3 block(256);
-  hipError_t e = launch_score_offsets(g, a, stream, marks);    // from the caller's log-sum-exp, if given
-  if (e != hipSuccess) return e;
+  // with the caller's log-sum-exp there is no statistics pass, and pass 2 converts it in its prologue
+  hipError_t e = hipSuccess;
   if (!a.lse) {
     hipLaunchKernelGGL((score_stream_kernel<T, D, RT_T, 1>), grid, block, 0, stream, a);
     e = hipGetLastError();
