@@ -252,15 +252,19 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
 
   // This wavefront's share of stage-load `t` (32 * KT keys from span_begin + t * 32 * KT) into stage
   // t % kStages.  Per-lane parts of the addresses: instruction jj of this wavefront fetches row r_jj
-  // of the stage, K chunk cl ^ (r & kSw), V chunk cl ^ (bit 2 of r) << 2 (the layouts the fragment
+  // of the stage, K chunk cl ^ (r & kSw), V chunk cl ^ (vswz(r) << 2) (the layouts the fragment
   // reads expect; a 32-key tile is kLoads consecutive instructions, so tiles stay contiguous in LDS)
   const int rl = lane / S::kCpr, cl = lane % S::kCpr;
+  // 64-byte block b of value row r sits at block b ^ vswz(r): the four key rows a half-wave's
+  // transpose read touches then fall into four different quarters of the 64 banks (without it the
+  // rows of a read, 256 or 128 bytes apart, met in the same banks: 4-way conflicts on every read)
+  auto vswz = [](int r) { return D == 128 ? (r & 3) : ((r >> 1) & 1); };
   uint32_t koff[kPerWave], voff[kPerWave];
 #pragma unroll
   for (int jj = 0; jj < kPerWave; ++jj) {
     const int r = (wave * kPerWave + jj) * S::kRowStep + rl;
     koff[jj] = (uint32_t)(r * k_tok) + (uint32_t)((cl ^ (r & ((S::kCpr < 16 ? S::kCpr : 16) - 1))) << 4);
-    voff[jj] = (uint32_t)(r * v_tok) + (uint32_t)((cl ^ (((r >> 2) & 1) << 2)) << 4);
+    voff[jj] = (uint32_t)(r * v_tok) + (uint32_t)((cl ^ (vswz(r) << 2)) << 4);
   }
   auto issue_tile = [&](int t) {
     const int tile0 = __builtin_amdgcn_readfirstlane(span_begin + t * 32 * KT);
@@ -287,7 +291,7 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
         const int r = j * S::kRowStep + rl;
         const int64_t key = min(tile0 + r, u.len - 1);
         const int kchunk = cl ^ (r & ((S::kCpr < 16 ? S::kCpr : 16) - 1));
-        const int vchunk = cl ^ (((r >> 2) & 1) << 2);
+        const int vchunk = cl ^ (vswz(r) << 2);
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kunit + key * k_tok + kchunk * 16),
                                          (__attribute__((address_space(3))) void*)(ksm + st * kStageBytes + j * 1024),
                                          16, 0, 0);
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
       float tmax = x[0];
 #pragma unroll
       for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, x[i]);
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32)) * c;                 // c > 0: scaling commutes with the maximum
+      tmax = fmaxf(tmax, other_half(tmax)) * c;                 // c > 0: scaling commutes with the maximum
       const float m_new = fmaxf(m_run[rt], tmax);
       const float m_use = m_new == kNegInf ? 0.f : m_new;          // nothing visible yet: every term is 0
       alpha[rt] = fast_exp2(m_run[rt] - m_use);
@@ -415,8 +419,9 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
       const int j = ln & 15, half = (ln >> 4) & 1;
       const uint32_t vb = lds_offset(vbuf) + (4 * hi + (j >> 2)) * S::kRowBytes + (half * 2 + ((j & 3) >> 1)) * 16 +
                           (j & 1) * 8;
+      const int swz = D == 128 ? (j >> 2) : ((j >> 3) & 1);          // vswz of the lane's key row (4 hi + j / 4 + a multiple of 8)
 #pragma unroll
-      for (int dt = 0; dt < S::kDT; ++dt) vaddr[dt] = vb + ((dt ^ hi) << 6);
+      for (int dt = 0; dt < S::kDT; ++dt) vaddr[dt] = vb + ((dt ^ swz) << 6);
     }
     uint4 vf[S::kDT];
     if constexpr (S::kDT == 4) lds_read_vt_x4<S::kRowBytes, 0>(vf, vaddr);
@@ -440,7 +445,7 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
 #pragma unroll
   for (int rt = 0; rt < RTW; ++rt) {
     const int row = (wave * RTW + rt) * 32 + col;
-    const float l_tot = l_run[rt] + __shfl_xor(l_run[rt], 32);
+    const float l_tot = l_run[rt] + other_half(l_run[rt]);
     if (hi == 0) a.part_ml[pbase + row] = make_float2(m_run[rt], l_tot);
     float* orow = a.part_o + (pbase + row) * D;
 #pragma unroll

@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kBlockThreads) void score_stats_kernel(ScoreArgs a)
   // the two half-waves hold disjoint keys of the same rows
 #pragma unroll
   for (int rt = 0; rt < RT_T; ++rt) {
-    const float om = __shfl_xor(mc[rt], 32), ol = __shfl_xor(l[rt], 32);
+    const float om = other_half(mc[rt]), ol = other_half(l[rt]);
     const float nm = fmaxf(mc[rt], om);
     l[rt] = l[rt] * fast_exp2(mc[rt] - nm) + ol * fast_exp2(om - nm);
     mc[rt] = nm;
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kBlockThreads) void score_reduce_kernel(ScoreArgs a
     }
 #pragma unroll
     for (int kt = 0; kt < KT; ++kt) {
-      const float tot = colsum[kt] + __shfl_xor(colsum[kt], 32);
+      const float tot = colsum[kt] + other_half(colsum[kt]);
       const int key = tile0 + kt * 32 + col;
       const float score = key < u.n ? tot / (float)min(u.wp, u.n - key) : 0.f;
       if (hi == 0 && key < u.n) out[key] = score;

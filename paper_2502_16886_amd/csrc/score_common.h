@@ -43,6 +43,16 @@ __device__ __forceinline__ f32x16 mma_chunk<Fp32>(const uint4& a, const uint4& b
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// The value held by lane (l ^ 32), by the gfx950 half-wave swap (v_permlane32_swap: one vector
+// instruction, where a shuffle goes through the LDS crossbar and has to be waited for).  The swap
+// exchanges the upper half of its first operand with the lower half of its second; with the same
+// value in both, every lane ends up with its own value in one result and its partner's in the other.
+__device__ __forceinline__ float other_half(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
+
 struct Unit {
   int b, h;
   int s0, n;        // first packed token and length of the sequence

@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void score_stream_kernel(ScoreArgs a) {
       acc = nxt;
     }
     if (PASS == 2) {
-      const float tot = colsum + __shfl_xor(colsum, 32);
+      const float tot = colsum + other_half(colsum);
       const int key = tile0 + col;
       const float score = key < u.n ? tot / (float)min(u.wp, u.n - key) : 0.f;
       if (hi == 0 && key < u.n) out[key] = score;
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256, 2) void score_stream_kernel(ScoreArgs a) {
     // the two half-waves hold disjoint keys of the same rows; then the four wavefronts
 #pragma unroll
     for (int rt = 0; rt < RT_T; ++rt) {
-      const float om = __shfl_xor(mc[rt], 32), ol = __shfl_xor(l[rt], 32);
+      const float om = other_half(mc[rt]), ol = other_half(l[rt]);
       const float nm = fmaxf(mc[rt], om);
       l[rt] = l[rt] * fast_exp2(mc[rt] - nm) + ol * fast_exp2(om - nm);
       mc[rt] = nm;

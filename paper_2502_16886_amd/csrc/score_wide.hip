@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
   float* out = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
 #pragma unroll
   for (int kt = 0; kt < kWideKT; ++kt) {
-    const float tot = colsum[kt] + __shfl_xor(colsum[kt], 32);
+    const float tot = colsum[kt] + other_half(colsum[kt]);
     const int key = t0[kt] + col;
     const float score = key < u.n ? tot / (float)min(u.wp, u.n - key) : 0.f;
     if (hi == 0 && key < u.n) out[key] = score;
