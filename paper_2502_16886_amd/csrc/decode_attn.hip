@@ -309,6 +309,23 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
   };
   constexpr int kPerTile = 2 * kPerWave + (MASKED ? 1 : 0);        // loads one wavefront issues per stage
 
+  // Per-lane byte offsets of the fragment reads within a 32-key tile.  K: 16-byte chunk
+  // (hi * kChunks + ch) of key row `col`, at slot chunk ^ (col & kSw) (the layout TileLoader-style
+  // loads leave).  V: lane 16 g + j points at key row 4 hi + j / 4, columns (g % 2) * 16 + 4 (j % 4) ..
+  // of column tile dt, whose 64-byte block sits at block dt ^ vswz(row).
+  uint32_t klane[S::kChunks], vlane[S::kDT];
+  {
+    constexpr int kSw = (S::kCpr < 16 ? S::kCpr : 16) - 1;
+#pragma unroll
+    for (int ch = 0; ch < S::kChunks; ++ch)
+      klane[ch] = (uint32_t)(col * S::kCpr + ((hi * S::kChunks + ch) ^ (col & kSw))) * 16u;
+    const int j = lane & 15, half = (lane >> 4) & 1;
+    const uint32_t vb = (4 * hi + (j >> 2)) * S::kRowBytes + (half * 2 + ((j & 3) >> 1)) * 16 + (j & 1) * 8;
+    const int swz = D == 128 ? (j >> 2) : ((j >> 3) & 1);          // vswz of the lane's key row (4 hi + j / 4 + a multiple of 8)
+#pragma unroll
+    for (int dt = 0; dt < S::kDT; ++dt) vlane[dt] = vb + ((dt ^ swz) << 6);
+  }
+
   float m_run[RTW], l_run[RTW];
   f32x16 o[RTW][S::kDT];
 #pragma unroll
@@ -349,7 +366,15 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
     const unsigned char* kbuf = ksm + st * kStageBytes + kt * S::kTileBytes;
     const unsigned char* vbuf = vsm + st * kStageBytes + kt * S::kTileBytes;
     uint4 kf[S::kChunks];
-    read_tile_frags<Bf16, D>(kf, kbuf, col, hi);
+    {
+      // the lane's fragment offsets within a tile are kept in registers; per tile one add of the
+      // tile's (uniform) LDS base each
+      const uint32_t kb = __builtin_amdgcn_readfirstlane(lds_offset(kbuf));
+      uint32_t kaddr[S::kChunks];
+#pragma unroll
+      for (int ch = 0; ch < S::kChunks; ++ch) kaddr[ch] = kb + klane[ch];
+      lds_read_b128_n<S::kChunks>(kf, kaddr);
+    }
 
     uint32_t keep_bits = (uint32_t)(stage_keep >> (32 * kt));              // bit i: key tile0 + i takes part
     if (tile0 + 32 > u.len) keep_bits &= (1u << (u.len - tile0)) - 1u;      // 1 <= len - tile0 <= 31 here
@@ -413,15 +438,9 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
     // O^T += V^T P^T.  Lane (col, hi) of the A operand: value column dt * 32 + col, keys as above.
     uint32_t vaddr[S::kDT];
     {
-      // lane 16 g + j points at key row 4 hi + j / 4, columns (g % 2) * 16 + 4 (j % 4) .. of tile dt
-      int ln = lane;
-      asm volatile("" : "+v"(ln));
-      const int j = ln & 15, half = (ln >> 4) & 1;
-      const uint32_t vb = lds_offset(vbuf) + (4 * hi + (j >> 2)) * S::kRowBytes + (half * 2 + ((j & 3) >> 1)) * 16 +
-                          (j & 1) * 8;
-      const int swz = D == 128 ? (j >> 2) : ((j >> 3) & 1);          // vswz of the lane's key row (4 hi + j / 4 + a multiple of 8)
+      const uint32_t vb = __builtin_amdgcn_readfirstlane(lds_offset(vbuf));
 #pragma unroll
-      for (int dt = 0; dt < S::kDT; ++dt) vaddr[dt] = vb + ((dt ^ swz) << 6);
+      for (int dt = 0; dt < S::kDT; ++dt) vaddr[dt] = vb + vlane[dt];
     }
     uint4 vf[S::kDT];
     if constexpr (S::kDT == 4) lds_read_vt_x4<S::kRowBytes, 0>(vf, vaddr);
