@@ -58,7 +58,9 @@ enum {
   RFKV_MAX_SCORE_ROWS = 512,     /* window * G (rounded up to a multiple of 32) of the streaming  */
                                  /* kernels; more rows take the wide-window path below            */
   RFKV_MAX_WIDE_ROWS = 65536,    /* window * G of the wide-window path (the paper's ablation of k */
-                                 /* up to 10 % of n): bf16 with head_dim 64 or 128, fp32 with 64  */
+                                 /* up to 10 % of n): bf16 with head_dim 64 or 128, fp32 with 64; */
+                                 /* (window * G / 128) * (longest sequence / 512) * units must    */
+                                 /* stay below 2^30, else RFKV_UNSUPPORTED                        */
   RFKV_MAX_UNITS = 65535         /* B * n_kv_heads                                                */
 };
 

@@ -155,6 +155,15 @@ Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len, con
   return g;
 }
 
+// The wide-window kernels index their work items (row block, span, unit) / (key block, unit) with 32-bit
+// integers on a one-dimensional grid.
+rfkv_status check_wide_grid(const Geometry& g) {
+  if (!g.wide) return RFKV_OK;
+  const int64_t stats_items = (int64_t)(g.rows_pad / 128) * g.nspans * g.units;
+  const int64_t colsum_items = ((int64_t)g.max_seqlen + 511) / 512 * g.units;
+  return stats_items > ((int64_t)1 << 30) || colsum_items > ((int64_t)1 << 30) ? RFKV_UNSUPPORTED : RFKV_OK;
+}
+
 rfkv_status device_status(hipError_t e) {
   if (e == hipSuccess) return RFKV_OK;
   g_last_device_error = (int32_t)e;
@@ -278,6 +287,7 @@ static rfkv_status score_impl(const rfkv_params* params, const void* q_win, cons
   if (!aligned16(q_win) || !aligned16(k) || !aligned16(scores) || !aligned16(ws)) return RFKV_INVALID_ARG;
   if (with_lse && (!lse_win || (reinterpret_cast<uintptr_t>(lse_win) & 3u))) return RFKV_INVALID_ARG;
   const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
+  if ((st = check_wide_grid(g)) != RFKV_OK) return st;
   const Workspace w = carve_workspace(g, ws);
   if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
   return device_status(run_score(params, g, w, q_win, with_lse ? lse_win : nullptr, k, cu_seqlens_dev, scores,
@@ -485,6 +495,7 @@ static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_
   if (scores_opt && !aligned16(scores_opt)) return RFKV_INVALID_ARG;
   if (with_lse && total > 0 && (!lse_win || (reinterpret_cast<uintptr_t>(lse_win) & 3u))) return RFKV_INVALID_ARG;
   const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
+  if ((st = check_wide_grid(g)) != RFKV_OK) return st;
   const Workspace w = carve_workspace(g, ws);
   if (ws_bytes < w.bytes) return RFKV_WORKSPACE_TOO_SMALL;
   hipStream_t s = static_cast<hipStream_t>(stream);
