@@ -34,6 +34,19 @@ namespace {
 #ifndef RFKV_COMPACT_UNROLL_MANY
 #define RFKV_COMPACT_UNROLL_MANY 2
 #endif
+// The rows are read once and written once: non-temporal accesses keep them from displacing what the
+// other kernels of the pass (and of the layers running beside it) re-use from the L2 and the
+// Infinity Cache.  The copy itself runs at the same rate; the scoring pass next to it gets faster
+// (headline step 71.5 -> 68.5 us).
+typedef unsigned int cu32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 nt_load(const uint4* p) {
+  const cu32x4 v = __builtin_nontemporal_load(reinterpret_cast<const cu32x4*>(p));
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ void nt_store(uint4* p, const uint4& v) {
+  cu32x4 t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<cu32x4*>(p));
+}
 constexpr int kUniformPrefixUnits = 16;    // up to here every thread sums the earlier kept counts itself
 
 __device__ __forceinline__ int64_t block_sum_i64(int64_t v, int64_t* sh /*[4]*/) {
@@ -121,16 +134,16 @@ __global__ __launch_bounds__(kBlockThreads) void compact_kernel(CompactArgs a) {
         int pos = idx ? idx[t] : (t < sinks ? t : n - kept + t);
         pos = min(max(pos, 0), n - 1);                   // a bad caller-supplied index cannot leave the sequence
         const int64_t tok = (int64_t)s0 + pos;
-        kv[j] = *reinterpret_cast<const uint4*>(kb + a.k_stride_tok * tok + a.k_stride_head * h + piece * 16);
-        vv[j] = *reinterpret_cast<const uint4*>(vb + a.v_stride_tok * tok + a.v_stride_head * h + piece * 16);
+        kv[j] = nt_load(reinterpret_cast<const uint4*>(kb + a.k_stride_tok * tok + a.k_stride_head * h + piece * 16));
+        vv[j] = nt_load(reinterpret_cast<const uint4*>(vb + a.v_stride_tok * tok + a.v_stride_head * h + piece * 16));
         if (off + t < a.capacity_rows) dst[j] = (off + t) * a.row_bytes + piece * 16;
       }
     }
 #pragma unroll
     for (int j = 0; j < kUnroll; ++j) {
       if (dst[j] >= 0) {
-        *reinterpret_cast<uint4*>(ko + dst[j]) = kv[j];
-        *reinterpret_cast<uint4*>(vo + dst[j]) = vv[j];
+        nt_store(reinterpret_cast<uint4*>(ko + dst[j]), kv[j]);
+        nt_store(reinterpret_cast<uint4*>(vo + dst[j]), vv[j]);
       }
     }
   }
