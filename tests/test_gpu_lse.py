@@ -41,6 +41,7 @@ CASES = [
     (8, 2, 128, "bf16", 300, [2000]),                 # 1200 rows
     (8, 2, 128, "fp32", 32, [600]),                   # fp32 d = 128, 128 rows: the register-operand kernels
     (8, 2, 64, "fp32", 16, [512]),                    # config 0's shape
+    (8, 2, 128, "bf16", 32, [0, 400, 0]),             # empty sequences
 ]
 
 

@@ -20,6 +20,8 @@ WIDE = [
     (8, 2, 64, "fp32", 150, [900, 149]),              # fp32: 600 rows
     (4, 1, 128, "bf16", 1024, [700]),                 # window >= n: the whole causal attention matrix
     (32, 8, 128, "bf16", 129, [1111, 300]),           # 516 rows: just past the streaming kernels' limit
+    (8, 2, 128, "bf16", 300, [0, 900, 0, 1]),         # empty sequences and a one-token sequence in a wide batch
+    (8, 2, 128, "bf16", 40, [0, 333]),                # 160 rows (the smallest wide window) with an empty sequence
 ]
 
 
