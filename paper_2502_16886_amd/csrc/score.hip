@@ -38,7 +38,7 @@ __device__ __forceinline__ void load_k_half(uint4* f, const unsigned char* kunit
 // pass 1: per-row (reference exponent, sum) over this workgroup's span of keys
 // ---------------------------------------------------------------------------------------------
 template <typename T, int D, int RT_T>
-__global__ __launch_bounds__(kBlockThreads) void score_stats_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(kBlockThreads, 2) void score_stats_kernel(ScoreArgs a) {
   using S = Shape<T, D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const Unit u = load_unit(a, blockIdx.y);
@@ -200,7 +200,7 @@ __global__ __launch_bounds__(kBlockThreads) void score_lse_offsets_kernel(ScoreA
 // pass 2: column sums of the normalised probabilities
 // ---------------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(kBlockThreads) void score_reduce_kernel(ScoreArgs a) {
+__global__ __launch_bounds__(kBlockThreads, 2) void score_reduce_kernel(ScoreArgs a) {
   using S = Shape<T, D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const Unit u = load_unit(a, blockIdx.y);
