@@ -412,22 +412,26 @@ def main():
         except Exception:
             cores = os.cpu_count() or 1
         t = time.perf_counter()
-        outs = []
-        for L in host_layers:
-            outs.append(O.oracle_compress_layer(L.f64("q_win"), L.f64("k"), L.k, L.v, L.cu_seqlens, cfg.n_q_heads,
-                                                cfg.n_kv_heads, cfg.window, n_sink=cfg.n_sink,
-                                                T=H.threshold_as_float32(cfg.threshold), rank_mode=O.RANK_POSITION,
-                                                form="cumsum"))
-        dt = (time.perf_counter() - t) / len(host_layers)
-        out = outs[0]
+        out = None
+        passes = 0
+        while passes == 0 or (time.perf_counter() - t < 10.0 and passes < 8 * len(host_layers)):
+            L = host_layers[passes % len(host_layers)]   # the layers in turn, again from the first until ~10 s are spent
+            res = O.oracle_compress_layer(L.f64("q_win"), L.f64("k"), L.k, L.v, L.cu_seqlens, cfg.n_q_heads,
+                                          cfg.n_kv_heads, cfg.window, n_sink=cfg.n_sink,
+                                          T=H.threshold_as_float32(cfg.threshold), rank_mode=O.RANK_POSITION,
+                                          form="cumsum")
+            if out is None:
+                out = res                                # layer 0's result doubles as a parity check below
+            passes += 1
+        dt = (time.perf_counter() - t) / passes
         # the run doubles as a last parity check of the benchmarked launch configuration
         dl = dls[B.RANK_POSITION][0]
         dl.compress(None)
         gpu = dl.results()
         agree = bool(np.array_equal(gpu["kept"], out["kept"]))
         cpu = {"value": round(N / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"{len(host_layers)} layers of the same workload ({N} tokens, all {cfg.n_kv_heads} KV heads "
-                         f"each, upcast to float64 included), float64 numpy, {dt:.2f} s per layer",
+               "sample": f"{passes} layer-passes over {len(host_layers)} layers of the same workload ({N} tokens, all "
+                         f"{cfg.n_kv_heads} KV heads each, upcast to float64 included), float64 numpy, {dt:.2f} s per layer-pass",
                "kept_counts_match_gpu": agree}
 
     decode = None
