@@ -3,9 +3,8 @@
 // Grid (row blocks, units).  Workgroup (x, u) moves output rows [x * ROWS, ...) of unit u;
 // workgroups past the unit's kept count leave at once.  ROWS = 16 with one row per thread step for
 // a handful of units (the most workgroups in flight); with many units (a ragged batch, all layers
-// of a model in one call) a workgroup first has to add up the kept counts of the units before it,
-// and moves 32 rows, two independent loads per thread in flight, to spread that cost (measured on
-// the ragged 8-sequence batch: 94 us with 16 rows, 82 us with 32, 105 us with 64).  A row of d elements is moved as
+// of a model in one call) a workgroup moves 32 rows, two independent loads per thread in flight
+// (measured on the ragged 8-sequence batch: 81 us with 16 rows, 73 us with 32, 76 us with 64).  A row of d elements is moved as
 // 16-byte pieces by row_bytes / 16 neighbouring lanes, so loads and stores of a row are fully
 // coalesced, and every thread keeps several independent 16-byte loads in flight.
 //
@@ -15,8 +14,10 @@
 //   kSrcPaddedIdx     the per-unit padded list the select kernel wrote
 //   kSrcPackedIdx     a packed list plus offsets supplied by the caller
 // In the first two cases the unit's output offset is the sum of the kept counts of the units
-// before it (ragged layout) or unit * pad_rows (padded layout, Sec. 3.3 "Running at Scale");
-// workgroup x == 0 of each unit also publishes it (and the grand total).
+// before it (ragged layout) or unit * pad_rows (padded layout, Sec. 3.3 "Running at Scale").  With
+// up to 16 units every workgroup adds the counts up itself and workgroup x == 0 of each unit
+// publishes the offset (and the grand total); with more, a one-workgroup scan kernel writes the
+// offsets first.
 #include "kernels.h"
 
 namespace rfkv {
@@ -47,19 +48,10 @@ __device__ __forceinline__ void nt_store(uint4* p, const uint4& v) {
   cu32x4 t = {v.x, v.y, v.z, v.w};
   __builtin_nontemporal_store(t, reinterpret_cast<cu32x4*>(p));
 }
-constexpr int kUniformPrefixUnits = 16;    // up to here every thread sums the earlier kept counts itself
-
-__device__ __forceinline__ int64_t block_sum_i64(int64_t v, int64_t* sh /*[4]*/) {
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return sh[0] + sh[1] + sh[2] + sh[3];
-}
+constexpr int kUniformPrefixUnits = 16;    // up to here every workgroup sums the earlier kept counts itself
 
 template <int kRowsPerBlock, int kUnroll>
 __global__ __launch_bounds__(kBlockThreads) void compact_kernel(CompactArgs a) {
-  __shared__ int64_t sh_sum[4];
   const int unit = blockIdx.y;
   const int b = unit / a.n_kv_heads, h = unit - b * a.n_kv_heads;
   const int s0 = a.cu[b];
@@ -78,21 +70,15 @@ __global__ __launch_bounds__(kBlockThreads) void compact_kernel(CompactArgs a) {
       a.offsets_out[unit] = off;
       if (unit == a.units - 1) a.offsets_out[a.units] = (int64_t)a.units * a.pad_rows;
     }
+  } else if (a.offsets_ready) {
+    off = a.offsets_out[unit];                           // written by compact_offsets_kernel just before
   } else {
-    if (unit <= kUniformPrefixUnits) {
-      // uniform loop: scalar loads, no LDS, no barrier
-      off = 0;
-      for (int u = 0; u < unit; ++u) {
-        const int bu = u / a.n_kv_heads;
-        off += min(max(a.kept[u], 0), a.cu[bu + 1] - a.cu[bu]);
-      }
-    } else {
-      int64_t part = 0;
-      for (int u = threadIdx.x; u < unit; u += kBlockThreads) {
-        const int bu = u / a.n_kv_heads;
-        part += min(max(a.kept[u], 0), a.cu[bu + 1] - a.cu[bu]);
-      }
-      off = block_sum_i64(part, sh_sum);
+    // a handful of units (launch_compact guarantees it): every workgroup adds up the kept counts of
+    // the units before it in a uniform loop (scalar loads, no LDS, no barrier)
+    off = 0;
+    for (int u = 0; u < unit; ++u) {
+      const int bu = u / a.n_kv_heads;
+      off += min(max(a.kept[u], 0), a.cu[bu + 1] - a.cu[bu]);
     }
     if (blockIdx.x == 0 && threadIdx.x == 0 && a.offsets_out) {
       a.offsets_out[unit] = off;
@@ -149,11 +135,53 @@ __global__ __launch_bounds__(kBlockThreads) void compact_kernel(CompactArgs a) {
   }
 }
 
+// Ragged output offsets for many units: the exclusive scan of the kept counts, once, by one
+// workgroup, instead of every compaction workgroup adding up the counts of the units before it.
+__global__ __launch_bounds__(1024) void compact_offsets_kernel(CompactArgs a) {
+  __shared__ int64_t sh_wave[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int64_t carry = 0;
+  for (int base = 0; base < a.units; base += 1024) {
+    const int u = base + tid;
+    int64_t v = 0;
+    if (u < a.units) {
+      const int bu = u / a.n_kv_heads;
+      v = min(max(a.kept[u], 0), a.cu[bu + 1] - a.cu[bu]);
+    }
+    int64_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int64_t o = __shfl_up(inc, d);
+      if (lane >= d) inc += o;
+    }
+    __syncthreads();
+    if (lane == 63) sh_wave[wave] = inc;
+    __syncthreads();
+    int64_t before = carry, total = 0;
+    for (int w = 0; w < 16; ++w) {
+      if (w < wave) before += sh_wave[w];
+      total += sh_wave[w];
+    }
+    if (u < a.units) a.offsets_out[u] = before + inc - v;
+    carry += total;
+  }
+  if (tid == 0) a.offsets_out[a.units] = carry;
+}
+
 }  // namespace
 
 // Strides arrive in bytes here (the C-ABI layer converts from elements).
-hipError_t launch_compact(const Geometry& g, const CompactArgs& a, hipStream_t stream) {
+hipError_t launch_compact(const Geometry& g, const CompactArgs& a_in, hipStream_t stream) {
   if (g.units == 0) return hipSuccess;
+  CompactArgs a = a_in;
+  a.offsets_ready = 0;
+  if (g.units > kUniformPrefixUnits && a.source != kSrcPackedIdx && a.pad_rows == 0) {
+    if (!a.offsets_out) return hipErrorInvalidValue;     // the C ABI requires out_offsets
+    hipLaunchKernelGGL(compact_offsets_kernel, dim3(1), dim3(1024), 0, stream, a);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    a.offsets_ready = 1;
+  }
   if (g.units <= kUniformPrefixUnits) {
     const int xblocks = max(1, (g.max_seqlen + RFKV_COMPACT_ROWS - 1) / RFKV_COMPACT_ROWS);
     hipLaunchKernelGGL((compact_kernel<RFKV_COMPACT_ROWS, RFKV_COMPACT_UNROLL>), dim3(xblocks, g.units),

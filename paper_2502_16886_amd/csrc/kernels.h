@@ -96,6 +96,7 @@ struct CompactArgs {
   int64_t capacity_rows;
   int64_t pad_rows;             // > 0: padded layout, unit u's rows start at u * pad_rows (not kSrcPackedIdx)
   int32_t n_kv_heads, units, row_bytes, source;
+  int32_t offsets_ready;        // set by launch_compact: offsets_out already holds the exclusive scan (many units)
 };
 
 // Attention of new queries over the compacted cache (offsets != null) or over the full cache
