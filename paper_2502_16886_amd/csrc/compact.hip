@@ -4,9 +4,10 @@
 // workgroups past the unit's kept count leave at once.  ROWS = 16 with one row per thread step for
 // a handful of units (the most workgroups in flight); with many units (a ragged batch, all layers
 // of a model in one call) a workgroup moves 32 rows, two independent loads per thread in flight
-// (measured on the ragged 8-sequence batch: 81 us with 16 rows, 73 us with 32, 76 us with 64).  A row of d elements is moved as
-// 16-byte pieces by row_bytes / 16 neighbouring lanes, so loads and stores of a row are fully
-// coalesced, and every thread keeps several independent 16-byte loads in flight.
+// (measured on the ragged 8-sequence batch: 81 us with 16 rows, 73 us with 32, 76 us with 64).
+// A row of d elements is moved as 16-byte pieces by row_bytes / 16 neighbouring lanes, so loads and
+// stores of a row are fully coalesced, and every thread keeps several independent 16-byte loads in
+// flight.
 //
 // Where the source position of output row t comes from:
 //   kSrcPositionDesc  position ranking keeps two slabs, [0, sinks) and [n - (kept - sinks), n):
