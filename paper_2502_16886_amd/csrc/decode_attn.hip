@@ -497,40 +497,42 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeArgs a) {
   const float2* ml = a.part_ml + pbase + row;
   const float* po = a.part_o + (pbase + row) * D + qd * 4;
   const int64_t ml_step = a.rows_pad, po_step = (int64_t)a.rows_pad * D;
+  // one pass over the items, eight at a time (their loads issued together: a round trip per batch,
+  // not per item), with a running reference exponent like the attention kernel's own
   float M = -__builtin_inff();
-  for (int s = 0; s < nsp; ++s) M = fmaxf(M, ml[s * ml_step].x);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float den = 0.f;
-  if (M != -__builtin_inff()) {
-    // four items at a time, their loads issued together
-    int s = 0;
-    for (; s + 4 <= nsp; s += 4) {
-      float2 m4[4];
-      float4 o4[4];
+  constexpr int kBatch = 8;
+  for (int s0 = 0; s0 < nsp; s0 += kBatch) {
+    float2 m8[kBatch];
+    float4 o8[kBatch];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        m4[j] = ml[(s + j) * ml_step];
-        o4[j] = *reinterpret_cast<const float4*>(po + (s + j) * po_step);
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const float w = fast_exp2(m4[j].x - M);
-        acc.x += w * o4[j].x;
-        acc.y += w * o4[j].y;
-        acc.z += w * o4[j].z;
-        acc.w += w * o4[j].w;
-        den += w * m4[j].y;
-      }
+    for (int j = 0; j < kBatch; ++j) {
+      const int sj = min(s0 + j, nsp - 1);
+      m8[j] = ml[sj * ml_step];
+      o8[j] = *reinterpret_cast<const float4*>(po + sj * po_step);
+      if (s0 + j >= nsp) m8[j] = make_float2(-__builtin_inff(), 0.f);
     }
-    for (; s < nsp; ++s) {
-      const float2 m1 = ml[s * ml_step];
-      const float w = fast_exp2(m1.x - M);
-      const float4 o4 = *reinterpret_cast<const float4*>(po + s * po_step);
-      acc.x += w * o4.x;
-      acc.y += w * o4.y;
-      acc.z += w * o4.z;
-      acc.w += w * o4.w;
-      den += w * m1.y;
+    float Mn = M;
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) Mn = fmaxf(Mn, m8[j].x);
+    if (Mn != -__builtin_inff()) {
+      const float keep = fast_exp2(M - Mn);              // 0 while nothing has been seen yet
+      acc.x *= keep;
+      acc.y *= keep;
+      acc.z *= keep;
+      acc.w *= keep;
+      den *= keep;
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const float w = fast_exp2(m8[j].x - Mn);         // an item without visible keys has m = -inf: weight 0
+        acc.x += w * o8[j].x;
+        acc.y += w * o8[j].y;
+        acc.z += w * o8[j].z;
+        acc.w += w * o8[j].w;
+        den += w * m8[j].y;
+      }
+      M = Mn;
     }
   }
   const float inv = den > 0.f ? 1.f / den : 0.f;          // a unit without visible keys gives zeros
