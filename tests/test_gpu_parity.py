@@ -87,6 +87,27 @@ def test_thresholds_and_min_keep(mode):
     assert np.all(gpu["kept"][:2] >= 100) and np.all(gpu["kept"][2:] == 90)
 
 
+@pytest.mark.parametrize("m", [0, 1, 33, 70, 200, 5000])
+def test_sink_counts(m):
+    """n_sink (the paper's m, positions ranked first) other than 4: none, one, more than a tile, more
+    than a wavefront, more than the sequence; thresholds that put the cut among the sinks and past them."""
+    cfg = small_cfg("bf16", 8, 2, 128, 16, batch=2)
+    layer = W.make_layer(0, 9, cfg=cfg, lengths=[1200, 150])
+    for T in (0.01, 0.3, 0.9):
+        for mode in MODES:
+            dl = H.DeviceLayer(layer, rank_mode=mode, threshold=T, n_sink=m)
+            dl.compress()
+            H.compare_layer(layer, dl.results(), mode, threshold=T, n_sink=m)
+    # the per-layer cut takes the same sink paths
+    T32 = H.threshold_as_float32(0.3)
+    dl = H.DeviceLayer(layer, threshold=0.3, n_sink=m, granularity=B.PER_LAYER)
+    dl.compress()
+    gpu = dl.results()
+    kept, offs, idx = O.oracle_select_layer(gpu["scores"].astype(np.float64), layer.cu_seqlens, O.RANK_POSITION, m, T32, 0,
+                                            form="cumsum")
+    assert np.array_equal(gpu["kept"], kept) and np.array_equal(gpu["idx"], idx)
+
+
 def test_large_logits_do_not_overflow():
     # logits of magnitude ~80: the running reference exponent must keep exp2 in range
     cfg = small_cfg("fp32", 4, 2, 64, 4, q_shared=0.0, x_sink=(0.0, 0.0), spike_frac=0.0)
