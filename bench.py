@@ -148,11 +148,13 @@ def time_wide_window(np, H, B, W, window=328, reps=12):
             "stats_TFLOPs": round(flop / (k["score_stats"] * 1e-3) / 1e12, 1)}
 
 
-def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, reps=6):
+def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, reps=6, lse_per_layer=None):
     """The post-prefill pass over the whole model in ONE call: the caches of `n_layers` layers (the
     paper keeps the first two layers whole, Sec. 3.3 "Retaining Bottom Layers", so 30 of 32) laid out
     [layer, token, head, d] are a batch of `n_layers` sequences to the library, one launch of every
-    kernel instead of one per layer.  The generated layer buffers repeat to fill the 30."""
+    kernel instead of one per layer.  The generated layer buffers repeat to fill the 30.  With
+    `lse_per_layer` (the window rows' log-sum-exp of every generated layer) the same call is also timed
+    through rfkv_compress_layer_lse."""
     if len({len(l.cu_seqlens) for l in host_layers}) != 1 or len(host_layers[0].cu_seqlens) != 2:
         return None
     pick = [host_layers[i % len(host_layers)] for i in range(n_layers)]
@@ -166,14 +168,22 @@ def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, reps=6):
     for _ in range(2):
         dl.compress(None)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(reps):
-        dl.compress(None)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / reps
+    def timed(lse):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dl.compress(None, lse_win=lse)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            dl.compress(None, lse_win=lse)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    ms = timed(None)
     kept = int(dl.buf.out_offsets[-1])
+    ms_lse = None
+    if lse_per_layer is not None:
+        ms_lse = timed(torch.cat([lse_per_layer[i % len(host_layers)] for i in range(n_layers)]).contiguous())
+        assert int(dl.buf.out_offsets[-1]) > 0
     e = 2 if cfg.dtype == "bf16" else 4
     wrows = n_layers * min(cfg.window, n)
     alg = algorithmic_bytes(n_layers * n, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows, kept,
@@ -183,7 +193,11 @@ def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, reps=6):
     return {"layers_per_call": n_layers, "retained_fraction": round(kept / (n_layers * n * cfg.n_kv_heads), 4),
             "ms_per_call": round(ms, 4), "ms_per_layer": round(ms / n_layers, 5),
             "tokens_per_s_per_layer_pass": round(n / (ms / n_layers * 1e-3), 1),
-            "pipeline_frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+            "pipeline_frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "with_prefill_lse": None if ms_lse is None else {
+                "ms_per_layer": round(ms_lse / n_layers, 5),
+                "tokens_per_s_per_layer_pass": round(n / (ms_lse / n_layers * 1e-3), 1),
+                "pipeline_frac": round((alg + 4 * wrows * cfg.n_q_heads) / (ms_lse * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}}
 
 
 def main():
@@ -440,7 +454,8 @@ def main():
 
     all_layers = None
     if args.all_layers:
-        all_layers = time_all_layers(torch, np, H, B, W, host_layers, cfg, args.all_layers)
+        all_layers = time_all_layers(torch, np, H, B, W, host_layers, cfg, args.all_layers,
+                                     lse_per_layer=[x.lse for x in dls[LSE]] if args.prefill_lse else None)
 
     wide = None
     if args.wide:
