@@ -61,7 +61,10 @@ enum {
                                  /* up to 10 % of n): bf16 with head_dim 64 or 128, fp32 with 64; */
                                  /* (window * G / 128) * (longest sequence / 512) * units must    */
                                  /* stay below 2^30, else RFKV_UNSUPPORTED                        */
-  RFKV_MAX_UNITS = 65535         /* B * n_kv_heads                                                */
+  RFKV_MAX_UNITS = 65535,        /* B * n_kv_heads                                                */
+  RFKV_MAX_STRIDE_TOK = 1 << 22  /* largest k_stride_tok / v_stride_tok (elements), else          */
+                                 /* RFKV_UNSUPPORTED: the tile loaders of the scoring and         */
+                                 /* attention kernels add up to 127 token strides in 32 bits      */
 };
 
 /*

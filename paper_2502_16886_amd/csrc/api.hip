@@ -105,6 +105,9 @@ rfkv_status check_strides(const rfkv_params* p, bool need_q, bool need_k, bool n
   if (need_q && !ok(p->q_stride_row, p->q_stride_head)) return RFKV_INVALID_ARG;
   if (need_k && !ok(p->k_stride_tok, p->k_stride_head)) return RFKV_INVALID_ARG;
   if (need_v && !ok(p->v_stride_tok, p->v_stride_head)) return RFKV_INVALID_ARG;
+  // the tile loaders add up to 127 token strides in 32-bit arithmetic
+  if (need_k && p->k_stride_tok > RFKV_MAX_STRIDE_TOK) return RFKV_UNSUPPORTED;
+  if (need_v && p->v_stride_tok > RFKV_MAX_STRIDE_TOK) return RFKV_UNSUPPORTED;
   return RFKV_OK;
 }
 

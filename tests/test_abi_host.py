@@ -111,6 +111,7 @@ def test_unsupported_problems(lib):
     assert score(good(dtype=B.DTYPE_FP32, window=256)) == B.RFKV_UNSUPPORTED  # wide window: 256-byte rows at most
     assert score(good(dtype=B.DTYPE_FP32, window=128)) == B.RFKV_UNSUPPORTED  # fp32 queries do not fit in LDS
     assert score(good(batch=10000), cu_h=np.zeros(10001, dtype=np.int32)) == B.RFKV_UNSUPPORTED
+    assert score(good(k_stride_tok=(1 << 22) + 8)) == B.RFKV_UNSUPPORTED      # above RFKV_MAX_STRIDE_TOK
     # a wide window over very many units: more work items than the kernels' 32-bit grids index
     cu = np.concatenate([[0], np.cumsum(np.r_[600000, np.full(7999, 1)])]).astype(np.int32)
     assert score(good(batch=8000, window=16384), cu_h=cu) == B.RFKV_UNSUPPORTED       # 512 x 37 x 64000 items
@@ -170,3 +171,4 @@ def test_decode_attention_host_checks(lib):
     assert masked(good(), cu_d=None) == B.RFKV_INVALID_ARG
     assert masked(good(k_stride_tok=100)) == B.RFKV_INVALID_ARG
     assert masked(good(), wsb=16) == B.RFKV_WORKSPACE_TOO_SMALL
+    assert masked(good(v_stride_tok=(1 << 22) + 8)) == B.RFKV_UNSUPPORTED     # above RFKV_MAX_STRIDE_TOK
