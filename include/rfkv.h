@@ -174,8 +174,10 @@ RFKV_API rfkv_status rfkv_compact(const rfkv_params* params, const void* k, cons
  * One layer of Alg. 1's loop body: score -> rank -> budget rule -> compaction, enqueued
  * back to back with no host synchronisation.  Arguments as above; `scores_opt` may be NULL
  * (scores then live in the workspace only) and `idx_opt` may be NULL (indices not reported).
- * Layers the caller wants to leave uncompressed (the paper keeps the first two, Sec. 3.3
- * "Retaining Bottom Layers") are simply not passed to the library.
+ * Layers that keep their whole cache (the paper keeps the first two, Sec. 3.3 "Retaining Bottom
+ * Layers") are either not passed to the library at all, or passed with threshold <= 0 and
+ * scores_opt NULL: nothing is scored then (q_win may be NULL), every position is kept, and the
+ * call only re-lays the cache out into the same ragged per-unit form as the other layers'.
  */
 RFKV_API rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, const void* k,
                                 const void* v, const int32_t* cu_seqlens_host,

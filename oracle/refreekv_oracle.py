@@ -368,6 +368,25 @@ def oracle_compress_layer(q_win_f64, k_f64, k_raw, v_raw, cu_seqlens, n_q_heads,
     return dict(scores=scores, kept=kept, out_offsets=offs, idx=idx, k_out=k_out, v_out=v_out)
 
 
+def oracle_compress_model(layers, n_q_heads, n_kv_heads, window, n_frozen=2, **kw):
+    """Alg. 1's loop over layers with Sec. 3.3 "Retaining Bottom Layers": the first n_frozen
+    layers are not pruned (every position of every head is retained, in order), the others go
+    through oracle_compress_layer.  `layers`: per layer a tuple (q_win_f64, k_f64, k_raw, v_raw,
+    cu_seqlens).  Returns the per-layer result dicts (scores None for the retained layers)."""
+    out = []
+    for li, (q_win, k_f64, k_raw, v_raw, cu) in enumerate(layers):
+        if li >= n_frozen:
+            out.append(oracle_compress_layer(q_win, k_f64, k_raw, v_raw, cu, n_q_heads, n_kv_heads, window, **kw))
+            continue
+        lens = np.diff(np.asarray(cu, dtype=np.int64))
+        kept = np.repeat(lens, n_kv_heads)
+        offs = np.concatenate([[0], np.cumsum(kept)]).astype(np.int64)
+        idx = np.concatenate([np.arange(n, dtype=np.int64) for n in kept]) if len(kept) else np.zeros(0, np.int64)
+        k_out, v_out = oracle_compact(k_raw, v_raw, cu, kept, offs, idx)
+        out.append(dict(scores=None, kept=kept, out_offsets=offs, idx=idx, k_out=k_out, v_out=v_out))
+    return out
+
+
 # ----------------------------------------------------------------------------
 # helpers for the invariants the tests use
 # ----------------------------------------------------------------------------

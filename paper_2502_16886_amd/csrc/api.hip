@@ -493,10 +493,14 @@ static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_
     return RFKV_OUTPUT_TOO_SMALL;
   if (params->batch == 0) return RFKV_OK;
   if (!aligned16(ws)) return RFKV_INVALID_ARG;
-  if (total > 0 && (!aligned16(q_win) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)))
-    return RFKV_INVALID_ARG;
+  // A layer that keeps its whole cache (T <= 0 keeps everything, Sec. 3.3 "Retaining Bottom Layers") and
+  // whose scores nobody asked for needs no scoring pass: the call is the re-layout copy alone.
+  const bool keep_whole = !(params->threshold > 0.f) && !scores_opt;
+  if (total > 0 && (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))) return RFKV_INVALID_ARG;
+  if (total > 0 && !keep_whole && !aligned16(q_win)) return RFKV_INVALID_ARG;
   if (scores_opt && !aligned16(scores_opt)) return RFKV_INVALID_ARG;
-  if (with_lse && total > 0 && (!lse_win || (reinterpret_cast<uintptr_t>(lse_win) & 3u))) return RFKV_INVALID_ARG;
+  if (with_lse && !keep_whole && total > 0 && (!lse_win || (reinterpret_cast<uintptr_t>(lse_win) & 3u)))
+    return RFKV_INVALID_ARG;
   const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
   if ((st = check_wide_grid(g)) != RFKV_OK) return st;
   const Workspace w = carve_workspace(g, ws);
@@ -504,7 +508,8 @@ static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* scores = scores_opt ? scores_opt : w.scores;
   hipError_t e = hipSuccess;
-  if (total > 0) e = run_score(params, g, w, q_win, with_lse ? lse_win : nullptr, k, cu_seqlens_dev, scores, s, marks);
+  if (total > 0 && !keep_whole)
+    e = run_score(params, g, w, q_win, with_lse ? lse_win : nullptr, k, cu_seqlens_dev, scores, s, marks);
   if (e != hipSuccess) return device_status(e);
   e = run_select(params, g, w, scores, cu_seqlens_dev, kept, false, s);
   if (e != hipSuccess) return device_status(e);

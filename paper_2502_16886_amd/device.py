@@ -56,9 +56,17 @@ class DeviceLayer:
             assert kv_layout == "token_major"          # [N, Hkv, d]
         self.buf = B.alloc_layer_buffers(self.params, self.N, self.max_len)
 
-    def compress(self, stream=None, lse_win=None):
-        """One fused pass; with `lse_win` (device float32 [window rows, Hq]) through rfkv_compress_layer_lse."""
+    def compress(self, stream=None, lse_win=None, keep_whole=False):
+        """One fused pass; with `lse_win` (device float32 [window rows, Hq]) through rfkv_compress_layer_lse.
+        `keep_whole`: the layer keeps its whole cache (threshold 0, no scores asked for, no queries
+        handed over): the library scores nothing and only re-lays the cache out per unit."""
         b = self.buf
+        if keep_whole:
+            p = B.RfkvParams.from_buffer_copy(self.params)
+            p.threshold = 0.0
+            return B.rfkv_compress_layer(p, None, self.k, self.v, self.cu_host, self.cu_dev, None, b.kept,
+                                         b.out_offsets, b.idx, b.k_out, b.v_out, b.capacity_rows, b.ws, b.ws_bytes,
+                                         stream)
         if lse_win is not None:
             return B.rfkv_compress_layer_lse(self.params, self.q, lse_win, self.k, self.v, self.cu_host, self.cu_dev,
                                              b.scores, b.kept, b.out_offsets, b.idx, b.k_out, b.v_out,
@@ -76,6 +84,14 @@ class DeviceLayer:
         return dict(scores=b.scores.cpu().numpy(), kept=b.kept.cpu().numpy().astype(np.int64), out_offsets=offs,
                     idx=b.idx[:total].cpu().numpy().astype(np.int64),
                     k_out=to_host_bits(b.k_out[:total], self.dtype), v_out=to_host_bits(b.v_out[:total], self.dtype))
+
+
+def compress_model(layers, n_frozen: int = 2, stream=None) -> None:
+    """Alg. 1's loop over the layers of a prefilled model with Sec. 3.3 "Retaining Bottom Layers":
+    the first `n_frozen` layers keep their whole cache, every other layer is compressed.  `layers`:
+    DeviceLayer objects in layer order; each one's buffers hold its result afterwards."""
+    for i, dl in enumerate(layers):
+        dl.compress(stream, keep_whole=i < n_frozen)
 
 
 def threshold_as_float32(T: float) -> float:

@@ -98,6 +98,8 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert layer(good(), ko=None) == B.RFKV_INVALID_ARG
     assert layer(good(), cap=-1) == B.RFKV_INVALID_ARG
     assert layer(good(v_stride_head=64)) == B.RFKV_INVALID_ARG
+    assert layer(good(), q=None) == B.RFKV_INVALID_ARG                      # queries are needed to score ...
+    assert layer(good(threshold=0.0), q=None, k=None) == B.RFKV_INVALID_ARG  # ... and K and V always
     st = B.rfkv_compact(good(), FAKE, FAKE, CU, FAKE, FAKE, FAKE, None, FAKE, FAKE, 10, stream=0, check=False)
     assert st == B.RFKV_INVALID_ARG
     st = B.rfkv_select(good(), FAKE, CU, FAKE, None, FAKE, FAKE, FAKE, 1 << 40, stream=0, check=False)

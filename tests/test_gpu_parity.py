@@ -108,6 +108,32 @@ def test_sink_counts(m):
     assert np.array_equal(gpu["kept"], kept) and np.array_equal(gpu["idx"], idx)
 
 
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("kv_layout", ["token_major", "head_major"])
+def test_model_loop_keeps_the_bottom_layers_whole(mode, kv_layout):
+    """Sec. 3.3 "Retaining Bottom Layers": compress_model leaves the first two layers unpruned (the
+    library is handed no queries for them and scores nothing: it only re-lays the cache out per
+    unit) and compresses the rest."""
+    cfg = small_cfg("bf16", 8, 2, 128, 32, batch=3)
+    host = [W.make_layer(1, li, cfg=cfg, lengths=[700, 33, 1500]) for li in range(4)]
+    dls = [H.DeviceLayer(l, rank_mode=mode, kv_layout=kv_layout) for l in host]
+    for dl in dls:                                        # stale contents must not survive
+        dl.buf.kept.fill_(-7)
+        dl.buf.k_out.fill_(1.0)
+    H.compress_model(dls, n_frozen=2)
+    ref = O.oracle_compress_model([(l.f64("q_win"), l.f64("k"), l.k, l.v, l.cu_seqlens) for l in host], cfg.n_q_heads,
+                                  cfg.n_kv_heads, cfg.window, n_frozen=2, n_sink=cfg.n_sink,
+                                  T=H.threshold_as_float32(cfg.threshold), rank_mode=mode, form="cumsum")
+    for li, (dl, layer) in enumerate(zip(dls, host)):
+        gpu = dl.results()
+        if li < 2:
+            for key in ("kept", "out_offsets", "idx", "k_out", "v_out"):
+                assert np.array_equal(gpu[key], ref[li][key]), (li, key)
+        else:
+            H.compare_layer(layer, gpu, mode)
+            assert gpu["kept"].sum() < ref[0]["kept"].sum()
+
+
 def test_large_logits_do_not_overflow():
     # logits of magnitude ~80: the running reference exponent must keep exp2 in range
     cfg = small_cfg("fp32", 4, 2, 64, 4, q_shared=0.0, x_sink=(0.0, 0.0), spike_frac=0.0)

@@ -223,6 +223,35 @@ def test_full_budget_reproduces_cache_exactly():
                 o += n
 
 
+def test_model_loop_retains_the_bottom_layers_whole():
+    # Sec. 3.3 "Retaining Bottom Layers": the first two layers are not pruned, the others are;
+    # a retained layer holds every row of every head in order, whatever its attention looks like
+    layers = []
+    for li in range(4):
+        q, k, v, cu, Hq, Hkv, d, w = _random_batch(30 + li, [23, 6, 31])
+        k[cu[:-1]] *= 6.0                                    # a heavy first key: the rule would prune a lot
+        layers.append((q, k, k.astype(np.float32), v.astype(np.float32), cu))
+    res = O.oracle_compress_model(layers, Hq, Hkv, w, n_frozen=2, T=0.2)
+    lens = np.repeat(np.diff(cu), Hkv)
+    for li, (r, (q, k, k32, v32, _)) in enumerate(zip(res, layers)):
+        alone = O.oracle_compress_layer(q, k, k32, v32, cu, Hq, Hkv, w, T=0.2)
+        if li < 2:
+            assert np.array_equal(r["kept"], lens) and alone["kept"].sum() < lens.sum()
+            o = 0
+            for b in range(len(cu) - 1):
+                for h in range(Hkv):
+                    n = cu[b + 1] - cu[b]
+                    assert np.array_equal(r["idx"][o:o + n], np.arange(n))
+                    assert np.array_equal(r["k_out"][o:o + n].view(np.uint32), k32[cu[b]:cu[b + 1], h].view(np.uint32))
+                    assert np.array_equal(r["v_out"][o:o + n].view(np.uint32), v32[cu[b]:cu[b + 1], h].view(np.uint32))
+                    o += n
+        else:
+            for key in ("kept", "out_offsets", "idx", "k_out", "v_out"):
+                assert np.array_equal(r[key], alone[key])
+    # n_frozen = 0 prunes every layer
+    assert O.oracle_compress_model(layers[:1], Hq, Hkv, w, n_frozen=0, T=0.2)[0]["kept"].sum() < lens.sum()
+
+
 @pytest.mark.parametrize("mode", [POS, SCO])
 def test_attention_over_compacted_cache_equals_masked_full_attention(mode):
     q, k, v, cu, Hq, Hkv, d, w = _random_batch(21, [64, 9, 40])
