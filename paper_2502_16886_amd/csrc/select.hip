@@ -30,10 +30,26 @@ struct Pred {
   double total;     // P_n as a double
   double T;
   int min_keep;
+  double lo = 0.0, hi = -1.0;   // set_total: masses below lo certainly fail the rule, above hi certainly meet it
+  // Away from the boundary the squared form P > (1 - T)^2 P_n decides (the margin of 1e-9 covers the
+  // rounding of both forms many times over); only next to it is the paper's form evaluated.
+  __device__ void set_total(double t) {
+    total = t;
+    if (T < 1.0) {
+      const double thr = (1.0 - T) * (1.0 - T) * t;
+      lo = thr * (1.0 - 1e-9);
+      hi = thr * (1.0 + 1e-9);
+    }
+  }
   // Q(i, P): has the ranked prefix of i elements and mass P reached the stopping condition?
   __device__ bool operator()(int64_t count, uint64_t mass) const {
     if (count <= 0 || count < min_keep) return false;      // a prefix has at least one element
-    return 1.0 - sqrt((double)mass / total) < T;
+    const double m = (double)mass;
+    if (hi >= lo) {
+      if (m > hi) return true;
+      if (m < lo) return false;
+    }
+    return 1.0 - sqrt(m / total) < T;
   }
 };
 
@@ -255,7 +271,7 @@ __device__ __forceinline__ int score_rank(const float* s, int n, double inv, flo
     block_exclusive_scan2(ex_c, ex_m, sh.scan, &tot_c, &tot_m);
     if (pass == 0) {
       // the first histogram holds every position: its mass is P_n exactly
-      pred.total = (double)tot_m;
+      pred.set_total((double)tot_m);
       if (!pred(n, tot_m)) {                       // min_keep >= n (or no mass): keep everything
         if (idx_pad)
           for (int i = tid; i < n; i += kT) idx_pad[i] = i;
