@@ -74,7 +74,9 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
   if ((int)(blockIdx.x >> 3) >= chunk || w >= items) return;
   const int by = w / kblocks;
   const Unit u = load_unit(a, by);
-  const int kb0 = (w - by * kblocks) * kWideKeys;
+  // the key blocks of a unit back to front: the last ones, whose stages are masked per element and take
+  // longest, are dispatched first
+  const int kb0 = (kblocks - 1 - (w - by * kblocks)) * kWideKeys;
   if (kb0 >= u.n) return;                              // uniform for the whole workgroup
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -107,6 +109,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
   for (int kt = 0; kt < kWideKT; ++kt) rmin[kt] = a.group * (t0[kt] + col - base_pos);
   const int rows_blind = max(0, a.group * (kb0 - base_pos));                  // rows below see none of the block's keys
   const int wave_rmax = a.group * (t0[kWideKT - 1] + 31 - base_pos);          // rows from here on see all of the wavefront's keys
+  const int wave_blind = a.group * (t0[0] - base_pos);                        // rows below see none of the wavefront's keys
   const int stage_begin = rows_blind / (kWideStage * 32);
   const int stage_end = (u.row_tiles + kWideStage - 1) / kWideStage;          // <= rows_pad / 128
 
@@ -187,6 +190,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     if (s + 1 < stage_end) issue_stage(s + 1);
+    if ((s + 1) * (kWideStage * 32) <= wave_blind) continue;       // no row of this stage sees any of the wavefront's keys
     if (s * (kWideStage * 32) < wave_rmax) stage_compute(s, std::true_type{});
     else stage_compute(s, std::false_type{});
   }
