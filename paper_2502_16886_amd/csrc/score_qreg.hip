@@ -207,15 +207,29 @@ __global__ __launch_bounds__(256, 2) void score_stream_kernel(ScoreArgs a) {
             if (col < kSpillRows) *reinterpret_cast<float4*>(lrow + q * 8) = v;
           }
         }
-        float tmax = kNegInf;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
-        const float mnew = fmaxf(mc[rt], tmax * c);
+        // The reference exponent only has to keep 2^x in range, not to be the maximum: once every row of
+        // the wavefront has one, a tile is summed against it as it stands, and only a tile that would
+        // push a sum towards overflow (a logit more than 60 binary orders above the reference) or a row
+        // that has seen no key yet takes the path that looks for the tile's maximum first.
         float sum = 0.f;
+        bool plain = __all(mc[rt] > -1e29f);                // uniform over the wavefront
+        if (plain) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sum += fast_exp2(__builtin_fmaf(acc[i], c, -mnew));
-        l[rt] = l[rt] * fast_exp2(mc[rt] - mnew) + sum;
-        mc[rt] = mnew;
+          for (int i = 0; i < 16; ++i) sum += fast_exp2(__builtin_fmaf(acc[i], c, -mc[rt]));
+          plain = __all(sum < 0x1p60f);                      // false for inf and NaN as well
+          if (plain) l[rt] += sum;
+        }
+        if (!plain) {
+          float tmax = kNegInf;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, acc[i]);
+          const float mnew = fmaxf(mc[rt], tmax * c);
+          sum = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sum += fast_exp2(__builtin_fmaf(acc[i], c, -mnew));
+          l[rt] = l[rt] * fast_exp2(mc[rt] - mnew) + sum;
+          mc[rt] = mnew;
+        }
       } else {
         // accumulator i of this lane: row rt*32 + (i/4)*8 + hi*4 + i%4, key tile0 + col
         float4 bv[4];

@@ -150,6 +150,27 @@ def test_large_logits_do_not_overflow():
     assert nbad == 0
 
 
+@pytest.mark.parametrize("window", [32, 200])
+def test_logit_far_above_the_running_reference(window):
+    """A key in the middle of a span whose logits lie ~100 binary orders above everything before it:
+    the statistics pass sums a tile against the reference exponent it already has and must notice
+    that this tile does not fit (both the streaming kernels and the wide-window row blocks)."""
+    cfg = small_cfg("bf16", 8, 2, 128, window, x_sink=(0.0, 0.0), spike_frac=0.0)
+    layer = W.make_layer(1, 3, cfg=cfg, lengths=[2600])
+    q = layer.f64("q_win").reshape(-1, 2, 4, 128)
+    k = layer.f64("k")
+    for h in range(2):
+        qbar = q[:, h].mean(axis=(0, 1))
+        for pos in (700, 1911):
+            k[pos, h] = qbar * (90.0 * np.sqrt(128.0) / (qbar @ qbar))
+    import torch
+    layer.k = torch.from_numpy(k).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    logits = np.einsum("rd,nd->rn", q[:, 0, 0], layer.f64("k")[:, 0]) / np.sqrt(128.0)
+    assert logits[:, 700].min() - np.delete(logits, (700, 1911), axis=1).max() > 60 * np.log(2.0)
+    for mode in MODES:
+        run_and_compare(layer, mode)
+
+
 def test_all_equal_scores_tie_break_lowest_index():
     # feed rfkv_select directly: equal scores -> score ranking keeps positions 0..kept-1
     import torch
