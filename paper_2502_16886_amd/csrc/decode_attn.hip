@@ -406,21 +406,38 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
           if (!((keep_bits >> kk) & 1u)) x[i] = kNegInf;
         }
       }
-      float tmax = x[0];
-#pragma unroll
-      for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, x[i]);
-      tmax = fmaxf(tmax, other_half(tmax)) * c;                 // c > 0: scaling commutes with the maximum
-      const float m_new = fmaxf(m_run[rt], tmax);
-      const float m_use = m_new == kNegInf ? 0.f : m_new;          // nothing visible yet: every term is 0
-      alpha[rt] = fast_exp2(m_run[rt] - m_use);
+      // The reference exponent only has to keep 2^x in range: once every row of the wavefront has
+      // one, the tile is taken against it as it stands; the tile's maximum is looked for (and the
+      // accumulators rescaled) only when a sum nears overflow or a row has seen no key yet.
       float p[16], sum = 0.f;
+      alpha[rt] = 1.f;
+      bool plain = __all(m_run[rt] > kNegInf);                     // uniform over the wavefront
+      if (plain) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        p[i] = fast_exp2(__builtin_fmaf(x[i], c, -m_use));
-        sum += p[i];
+        for (int i = 0; i < 16; ++i) {
+          p[i] = fast_exp2(__builtin_fmaf(x[i], c, -m_run[rt]));
+          sum += p[i];
+        }
+        plain = __all(sum < 0x1p60f);                              // false for inf and NaN as well
+        if (plain) l_run[rt] += sum;
       }
-      l_run[rt] = l_run[rt] * alpha[rt] + sum;
-      m_run[rt] = m_new;
+      if (!plain) {
+        float tmax = x[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, x[i]);
+        tmax = fmaxf(tmax, other_half(tmax)) * c;               // c > 0: scaling commutes with the maximum
+        const float m_new = fmaxf(m_run[rt], tmax);
+        const float m_use = m_new == kNegInf ? 0.f : m_new;        // nothing visible yet: every term is 0
+        alpha[rt] = fast_exp2(m_run[rt] - m_use);
+        sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          p[i] = fast_exp2(__builtin_fmaf(x[i], c, -m_use));
+          sum += p[i];
+        }
+        l_run[rt] = l_run[rt] * alpha[rt] + sum;
+        m_run[rt] = m_new;
+      }
       rescale = rescale || alpha[rt] != 1.f;
       pf[rt][0] = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
       pf[rt][1] = make_uint4(pack_bf16(p[8], p[9]), pack_bf16(p[10], p[11]), pack_bf16(p[12], p[13]),

@@ -107,6 +107,38 @@ def test_decode_small_shapes(case, rank_mode):
     _check(got_m, ref, bound, "masked")
 
 
+@pytest.mark.parametrize("n_new", [8, 64])
+def test_decode_key_far_above_the_running_reference(n_new):
+    """A key deep in the cache whose logits lie ~100 binary orders above everything before it (and one
+    far below, for symmetry): the kernel takes a tile against the reference exponent its rows already
+    have and must notice when the tile does not fit.  T = 0: the whole cache is kept, so the planted
+    keys are attended to wherever the cut would have fallen."""
+    import torch
+    cfg = W.Config("t", 1, 8, 2, 128, 16, "bf16", batch=1, context=3000, threshold=0.0)
+    layer = W.make_layer(7, 4, cfg=cfg, lengths=(3000,))
+    qn = W.make_new_queries(7, 4, n_new=n_new, cfg=cfg, lengths=(3000,))
+    qf = W.to_f64(qn, "bf16")                               # [B, n_new, Hq, d]
+    k = layer.f64("k")
+    for h in range(2):
+        qbar = qf[0, :, 4 * h:4 * h + 4].mean(axis=(0, 1))
+        k[1700, h] = qbar * (90.0 * np.sqrt(128.0) / (qbar @ qbar))
+        k[2300, h] = -k[1700, h]
+    layer.k = torch.from_numpy(k).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    logits = np.einsum("rd,nd->rn", qf[0, :, 0], layer.f64("k")[:, 0]) / np.sqrt(128.0)
+    assert logits[:, 1700].min() - np.delete(logits, 1700, axis=1).max() > 60 * np.log(2.0)
+    dl = H.DeviceLayer(layer)
+    dl.compress()
+    res = dl.results()
+    assert int(res["kept"].min()) == 3000
+    got = _run_decode(dl, qn, n_new)
+    k_c, v_c = W.to_f64(res["k_out"], "bf16"), W.to_f64(res["v_out"], "bf16")
+    ref = O.oracle_decode_attention(qf, k_c, v_c, res["out_offsets"], 8, 2)
+    assert np.isfinite(got).all()
+    _check(got, ref, _bound(qf, k_c, v_c, res["out_offsets"], 8, 2, masked=False), "compacted")
+    got_m = _run_masked(dl, qn, n_new, _keep_mask(layer, res))
+    _check(got_m, ref, _bound(qf, k_c, v_c, res["out_offsets"], 8, 2, masked=False), "masked")
+
+
 def test_decode_empty_sequences_and_zero_queries():
     cfg = W.Config("t", 1, 8, 2, 128, 16, "bf16", batch=3, context=64)
     lens = (0, 40, 0)
