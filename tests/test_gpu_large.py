@@ -4,7 +4,8 @@ behind it so that a sequence start lies beyond 2^31 elements too.  The inputs ar
 torch's seeded generator (a generator outside both paths) and the very same bits are downloaded for
 the oracle.  Checked: one KV head's scores of the long sequence and the whole short sequence against
 the float64 oracle, Eq. 2's mass identity on every head, the selection stage-exact on every unit (both
-rankings) and the compacted rows bit for bit (gathered again with torch indexing on the device)."""
+rankings), the compacted rows bit for bit (gathered again with torch indexing on the device), and decode
+attention over that compacted cache for three units against the oracle."""
 import os
 import sys
 
@@ -77,6 +78,29 @@ def test_more_than_2g_elements(mode):
                                             form="cumsum")
     assert np.array_equal(kept, kept_o) and np.array_equal(offs, offs_o) and np.array_equal(idx, idx_o)
     assert 0 < kept.min() and kept[:HKV].max() <= LENS[0]
+
+    # the consumer over the same cache: 8 new queries, one KV head of the long sequence and the short
+    # sequence against the oracle (rows of the compacted cache beyond 2^31 elements)
+    if mode == B.RANK_POSITION:
+        n_new = 8
+        qn = (0.6 * torch.randn((2, n_new, HKV, G, D), generator=gen, device="cuda") + shared[None, 0]).reshape(
+            2, n_new, HQ, D).to(torch.bfloat16).contiguous()
+        out = torch.full((2, n_new, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
+        dws_bytes = B.rfkv_decode_workspace_bytes(p, n_new, max(LENS))
+        dws = torch.empty(dws_bytes, dtype=torch.uint8, device="cuda")
+        B.rfkv_decode_attention(p, qn, n_new, buf.k_out, buf.v_out, cu, buf.out_offsets, out, dws, dws_bytes)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all()
+        for u in (h, HKV + 2, 2 * HKV - 1):                  # units of both sequences; the last one ends the cache
+            b, hh = divmod(u, HKV)
+            o0, o1 = int(offs[u]), int(offs[u + 1])
+            k_u, v_u = bf16_to_f64(buf.k_out[o0:o1]), bf16_to_f64(buf.v_out[o0:o1])
+            q_u = bf16_to_f64(qn[b:b + 1, :, hh * G:(hh + 1) * G])
+            ref_o = O.oracle_decode_attention(q_u, k_u, v_u, np.array([0, o1 - o0]), G, 1)
+            bound = 2.0 ** -8 * O.oracle_decode_attention(q_u, k_u, np.abs(v_u), np.array([0, o1 - o0]), G, 1)
+            err = np.abs(got[b:b + 1, :, hh * G:(hh + 1) * G] - ref_o)
+            assert np.all(err <= 1.05 * bound + 1e-5), (u, float(err.max()))
 
     # compaction: the rows at those positions, bit for bit (gathered again by torch on the device)
     idx_dev = torch.from_numpy(idx).cuda()
