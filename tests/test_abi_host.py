@@ -174,3 +174,48 @@ def test_decode_attention_host_checks(lib):
     assert masked(good(k_stride_tok=100)) == B.RFKV_INVALID_ARG
     assert masked(good(), wsb=16) == B.RFKV_WORKSPACE_TOO_SMALL
     assert masked(good(v_stride_tok=(1 << 22) + 8)) == B.RFKV_UNSUPPORTED     # above RFKV_MAX_STRIDE_TOK
+
+
+C_PROGRAM = r"""
+#include "rfkv.h"
+#include <stdio.h>
+#include <string.h>
+int main(void) {
+  rfkv_params p;
+  memset(&p, 0, sizeof p);
+  p.batch = 1; p.n_q_heads = 32; p.n_kv_heads = 8; p.head_dim = 128; p.window = 32; p.n_sink = 4;
+  p.threshold = 0.01f; p.rank_mode = RFKV_RANK_POSITION; p.dtype = RFKV_DTYPE_BF16;
+  p.k_stride_tok = p.v_stride_tok = 8 * 128; p.k_stride_head = p.v_stride_head = 128;
+  p.q_stride_row = 32 * 128; p.q_stride_head = 128;
+  if (sizeof p != 104) return 1;
+  if (rfkv_version() < 100) return 2;
+  if (rfkv_workspace_bytes(&p, 32768, 32768) == 0) return 3;
+  if (strcmp(rfkv_status_string(RFKV_OK), "ok") != 0) return 4;
+  /* a null parameter block is rejected on the host, before anything touches a device */
+  if (rfkv_score(0, 0, 0, 0, 0, 0, 0, 0, 0) != RFKV_INVALID_ARG) return 5;
+  printf("%d\n", (int)rfkv_version());
+  return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_the_library_links_from_c(lib, tmp_path):
+    """include/rfkv.h compiles as strict C99 (and as C++), and a C program linked against the shared
+    library reaches the host-side entry points.  No device call is made."""
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no C compiler")
+    src = tmp_path / "abi.c"
+    src.write_text(C_PROGRAM)
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", f"-I{inc}", str(src)],
+                   check=True)
+    subprocess.run(["g++", "-std=c++11", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", f"-I{inc}",
+                    str(src)], check=True)
+    exe = tmp_path / "abi"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", f"-I{inc}", str(src), "-o", str(exe), B.LIB_PATH, f"-Wl,-rpath,{libdir}",
+                    "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, timeout=120)
+    assert int(out.stdout.strip()) == B.rfkv_version()
