@@ -205,7 +205,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--layers", type=int, default=8, help="distinct layer buffers to rotate over")
+    ap.add_argument("--layers", type=int, default=40, help="distinct layer buffers to rotate over (one graph holds them all)")
+    ap.add_argument("--gen-layers", type=int, default=8, help="layers generated on the host (the buffers repeat them)")
     ap.add_argument("--config", default="H", help="workload id in paper_2502_16886_amd.workloads.CONFIGS")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kv-layout", default="head_major", choices=["head_major", "token_major"],
@@ -246,9 +247,11 @@ def main():
     e = 2 if cfg.dtype == "bf16" else 4
 
     t0 = time.time()
-    host_layers = [W.make_layer(cfg_id, li) for li in range(args.layers)]
-    dls = {B.RANK_POSITION: [H.DeviceLayer(l, rank_mode=B.RANK_POSITION, kv_layout=args.kv_layout)
-                              for l in host_layers]}
+    # `layers` device buffers to rotate over; at most `gen_layers` of them are generated on the host, the
+    # rest are further uploads of the same layers in turn (their own buffers, inputs and outputs)
+    host_layers = [W.make_layer(cfg_id, li) for li in range(min(args.layers, args.gen_layers))]
+    dls = {B.RANK_POSITION: [H.DeviceLayer(host_layers[i % len(host_layers)], rank_mode=B.RANK_POSITION,
+                                           kv_layout=args.kv_layout) for i in range(args.layers)]}
     # score ranking shares the inputs, with its own outputs
     dls[B.RANK_SCORE] = []
     for dl in dls[B.RANK_POSITION]:
