@@ -30,25 +30,8 @@ def oracle_layer(layer: W.Layer, rank_mode, threshold=None, min_keep=0, n_sink=N
         scores = O.oracle_score(layer.f64("q_win"), layer.f64("k"), layer.cu_seqlens, c.n_q_heads, c.n_kv_heads,
                                 c.window)
     kept, offs, idx = O.oracle_select(scores, layer.cu_seqlens, rank_mode, m, T, min_keep, form="cumsum")
-    k_out, v_out = gather_rows(layer, kept, offs, idx)
+    k_out, v_out = O.oracle_compact(layer.k, layer.v, layer.cu_seqlens, kept, offs, idx)
     return dict(scores=scores, kept=kept, out_offsets=offs, idx=idx, k_out=k_out, v_out=v_out)
-
-
-def gather_rows(layer: W.Layer, kept, offs, idx):
-    """Vectorised form of the oracle's row gather (same result as O.oracle_compact, which the CPU
-    tests pin; this one is only faster on the large configurations)."""
-    Hkv = layer.cfg.n_kv_heads
-    cu = layer.cu_seqlens
-    total = int(offs[-1])
-    k_out = np.empty((total, layer.cfg.head_dim), dtype=layer.k.dtype)
-    v_out = np.empty_like(k_out)
-    for u in range(len(kept)):
-        b, h = divmod(u, Hkv)
-        o, c = int(offs[u]), int(kept[u])
-        rows = int(cu[b]) + idx[o:o + c]
-        k_out[o:o + c] = layer.k[rows, h]
-        v_out[o:o + c] = layer.v[rows, h]
-    return k_out, v_out
 
 
 def score_errors(gpu_scores: np.ndarray, ref_scores: np.ndarray):
@@ -140,5 +123,7 @@ def compare_layer(layer: W.Layer, gpu: dict, rank_mode, threshold=None, min_keep
                     cut_score = np.sort(su)[::-1][max(rk, 1) - 1]
                     assert np.all(np.abs(su[diff] - cut_score) <= 2e-3 * cut_score + 1e-30), \
                         f"unit {u}: sets differ away from the cut"
-    return dict(units=n_units, robust=n_robust, exact=n_exact, max_rel_score_err=rel, worst_shift=worst_shift,
+    return dict(units=n_units, robust=int(n_robust), exact=int(n_exact), robust_frac=round(n_robust / max(1, n_units), 4),
+                not_robust_frac=round(1.0 - n_robust / max(1, n_units), 4), max_rel_score_err=rel,
+                worst_shift=worst_shift,
                 retained=float(gpu["kept"].sum()) / max(1, layer.cfg.n_kv_heads * int(layer.cu_seqlens[-1])))

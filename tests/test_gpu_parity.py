@@ -259,6 +259,10 @@ def test_repeat_runs_are_bit_identical_and_capacity_is_respected():
 # (config, layers, K/V storage): the headline shape runs in the storage the benchmark times
 FULL_CASES = [(1, [0, 13, 31], "token_major"), (2, [5], "head_major"), (3, [2], "token_major"),
               ("H", [0], "head_major"), (4, [1], "head_major"), ("K1", [0, 7], "head_major")]
+# Units of a layer whose retained set may differ from the oracle's (they are never cut-robust ones, and
+# compare_layer bounds how far they may move): none on configs 1, 2, 3 and the headline, one on the
+# 131072-token config and on k = 1, where single razor-edge units exist among the 32 layers.
+MAY_DIFFER = {1: 0, 2: 0, 3: 0, "H": 0, 4: 1, "K1": 1}
 
 
 @pytest.mark.parametrize("cfg_id,layers,kv_layout", FULL_CASES)
@@ -277,4 +281,7 @@ def test_full_size_configs(cfg_id, layers, kv_layout):
             gpu = dl.results()
             rep = H.compare_layer(layer, gpu, mode, ref=ref)
             print(f"\n  cfg={cfg_id} layer={li} mode={mode} {rep}", flush=True)
+            # most units of the score ranking are not cut-robust at these lengths (one step of the rule is
+            # ~1e-9 of the mass), so the bit-exact comparison must not hinge on that class alone
+            assert rep["exact"] >= rep["units"] - MAY_DIFFER[cfg_id], rep
             del dl, gpu
