@@ -103,8 +103,8 @@ def time_decode_attention(torch, np, H, B, W, cfg_id=4, n_new=64, reps=20):
         return e0.elapsed_time(e1) / reps
 
     b = dl.buf
-    t_c = timed(lambda: B.rfkv_decode_attention(dl.params, q, n_new, b.k_out, b.v_out, dl.cu_host, b.out_offsets, out,
-                                                ws, ws_bytes))
+    t_c = timed(lambda: B.rfkv_decode_attention(dl.params, q, n_new, b.k_out, b.v_out, dl.cu_host, b.out_offsets, None,
+                                                out, ws, ws_bytes))
     t_m = timed(lambda: B.rfkv_masked_attention(dl.params, q, n_new, dl.k, dl.v, dl.cu_host, dl.cu_dev, mask, out, ws,
                                                 ws_bytes))
     flop_per_key = 4 * n_new * (cfg.n_q_heads // Hkv) * d          # QK^T and PV, multiply-add = 2

@@ -145,13 +145,17 @@ RFKV_API rfkv_status rfkv_score(const rfkv_params* params, const void* q_win, co
  * s[r] the score at rank r and P_i = sum_{r <= i} s[r]^2, F^2 = P_n:
  *   i* = min { i : 1 - sqrt(P_i) / F < T }   (n if there is none or F = 0),
  *   kept = min(n, max(i*, min_keep)),
- * and the retained set is ranks 1..kept.  P is accumulated exactly (integer fixed point scaled by
- * F^2, resolution 2^-60), so the result does not depend on reduction order.
+ * and the retained set is ranks 1..kept.  Both rankings are deterministic (two runs give the same
+ * bits): the position ranking adds fp64 masses in a fixed order, the score ranking accumulates P
+ * exactly (integer fixed point scaled by F^2, resolution 2^-60), so no reduction order enters.
  *   scores       device, float [Hkv, N] as written by rfkv_score
  *   kept         device, int32 [B * Hkv]
  *   out_offsets  device, int64 [B * Hkv + 1], exclusive prefix sum of kept
- *   idx          device, int32, capacity N * Hkv: retained positions relative to their sequence
- *                start, ascending, unit u at idx[out_offsets[u] .. out_offsets[u+1])
+ *   idx          device, int32: retained positions relative to their sequence start, ascending,
+ *                unit u at idx[out_offsets[u] .. out_offsets[u] + kept[u]).  Capacity the caller must
+ *                provide: N * Hkv entries with the ragged layout, B * Hkv * out_pad_rows entries with
+ *                the padded one (out_pad_rows > 0; never less than N * Hkv, since a slot holds the
+ *                longest sequence); nothing is written beyond that
  */
 RFKV_API rfkv_status rfkv_select(const rfkv_params* params, const float* scores,
                         const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
@@ -173,7 +177,9 @@ RFKV_API rfkv_status rfkv_compact(const rfkv_params* params, const void* k, cons
 /*
  * One layer of Alg. 1's loop body: score -> rank -> budget rule -> compaction, enqueued
  * back to back with no host synchronisation.  Arguments as above; `scores_opt` may be NULL
- * (scores then live in the workspace only) and `idx_opt` may be NULL (indices not reported).
+ * (scores then live in the workspace only) and `idx_opt` may be NULL (indices not reported);
+ * otherwise idx_opt has the capacity rfkv_select asks for, and like the K / V rows its entries at
+ * or beyond out_capacity_rows are not written.
  * Layers that keep their whole cache (the paper keeps the first two, Sec. 3.3 "Retaining Bottom
  * Layers") are either not passed to the library at all, or passed with threshold <= 0 and
  * scores_opt NULL: nothing is scored then (q_win may be NULL), every position is kept, and the
@@ -184,21 +190,6 @@ RFKV_API rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* 
                                 const int32_t* cu_seqlens_dev, float* scores_opt, int32_t* kept,
                                 int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
                                 int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream);
-
-/*
- * Measurement aid (not part of the paper's method): rfkv_compress_layer with a HIP event recorded
- * on `stream` after each kernel.  Synchronises the stream before returning and fills
- * kernel_ms_host[RFKV_NUM_KERNELS] (host memory) with the elapsed milliseconds between
- * consecutive events, in launch order: score statistics, statistics merge, score reduction,
- * selection, compaction.  Outputs are identical to rfkv_compress_layer's.
- */
-enum { RFKV_NUM_KERNELS = 5 };
-RFKV_API rfkv_status rfkv_compress_layer_timed(const rfkv_params* params, const void* q_win, const void* k,
-                                const void* v, const int32_t* cu_seqlens_host,
-                                const int32_t* cu_seqlens_dev, float* scores_opt, int32_t* kept,
-                                int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
-                                int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream,
-                                float* kernel_ms_host);
 
 /*
  * Scoring and the fused pass when the prefill already has the window rows' softmax normalisers.
@@ -233,6 +224,10 @@ RFKV_API rfkv_status rfkv_compress_layer_lse(const rfkv_params* params, const vo
  *   q_new        device, bf16 [B, n_new, Hq, d] contiguous
  *   k_c, v_c     device, bf16 [rows, d] contiguous as written by rfkv_compact / rfkv_compress_layer
  *   out_offsets  device, int64 [B * Hkv + 1] as written by rfkv_select / rfkv_compress_layer
+ *   kept_opt     device, int32 [B * Hkv] as written by the same call, or NULL.  With the ragged layout
+ *                a unit's rows are out_offsets[u] .. out_offsets[u + 1] and kept_opt adds nothing; with
+ *                the padded layout (out_pad_rows > 0) only the first kept[u] rows of a unit's slot hold
+ *                data, so kept_opt is required (RFKV_INVALID_ARG without it) and bounds every unit
  *   out          device, float [B, n_new, Hq, d]; a unit with no rows gives zeros
  *   ws           device scratch of at least rfkv_decode_workspace_bytes(...)
  * cu_seqlens_host bounds the unit lengths (kept_u <= n_b) for the launch geometry; the kept
@@ -243,8 +238,8 @@ enum { RFKV_MAX_DECODE_ROWS = 256 };
 RFKV_API size_t rfkv_decode_workspace_bytes(const rfkv_params* params, int32_t n_new, int32_t max_seqlen);
 RFKV_API rfkv_status rfkv_decode_attention(const rfkv_params* params, const void* q_new, int32_t n_new,
                                   const void* k_c, const void* v_c, const int32_t* cu_seqlens_host,
-                                  const int64_t* out_offsets, float* out, void* ws, size_t ws_bytes,
-                                  void* stream);
+                                  const int64_t* out_offsets, const int32_t* kept_opt, float* out, void* ws,
+                                  size_t ws_bytes, void* stream);
 
 /*
  * The same attention over the uncompressed cache with the evicted positions masked to -inf: the

@@ -25,8 +25,7 @@ DTYPE_BF16 = 1
 PER_HEAD = 0
 PER_LAYER = 1
 
-# RFKV_LIBRARY points the binding at another build of the same library (kernel tuning variants)
-LIB_PATH = os.environ.get("RFKV_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "librfkv.so")
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "librfkv.so")
 
 
 class RfkvParams(ctypes.Structure):
@@ -92,7 +91,7 @@ def load_library() -> ctypes.CDLL:
     lib.rfkv_decode_workspace_bytes.restype = sz
     lib.rfkv_decode_workspace_bytes.argtypes = [P, i32, i32]
     lib.rfkv_decode_attention.restype = ctypes.c_int
-    lib.rfkv_decode_attention.argtypes = [P, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.rfkv_decode_attention.argtypes = [P, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.rfkv_masked_attention.restype = ctypes.c_int
     lib.rfkv_masked_attention.argtypes = [P, vp, i32, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     _lib = lib
@@ -208,11 +207,11 @@ def rfkv_decode_workspace_bytes(params, n_new: int, max_seqlen: int) -> int:
     return int(load_library().rfkv_decode_workspace_bytes(ctypes.byref(params), int(n_new), int(max_seqlen)))
 
 
-def rfkv_decode_attention(params, q_new, n_new, k_c, v_c, cu_host, out_offsets, out, ws, ws_bytes, stream=None,
-                          check=True) -> int:
+def rfkv_decode_attention(params, q_new, n_new, k_c, v_c, cu_host, out_offsets, kept_opt, out, ws, ws_bytes,
+                          stream=None, check=True) -> int:
     st = load_library().rfkv_decode_attention(ctypes.byref(params), _ptr(q_new), int(n_new), _ptr(k_c), _ptr(v_c),
-                                              _ptr(cu_host), _ptr(out_offsets), _ptr(out), _ptr(ws), int(ws_bytes),
-                                              _stream(stream))
+                                              _ptr(cu_host), _ptr(out_offsets), _ptr(kept_opt), _ptr(out), _ptr(ws),
+                                              int(ws_bytes), _stream(stream))
     return _check(st, "rfkv_decode_attention", check)
 
 

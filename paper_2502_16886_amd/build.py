@@ -23,15 +23,14 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = False, extra_flags=(), out_path: str | None = None, csrc_dir: str | None = None) -> str:
-    """Compile every source for gfx950 and link the shared library.  Always recompiles.
-    `extra_flags` / `out_path` build a tuning variant (e.g. -DRFKV_COMPACT_ROWS=32) elsewhere."""
-    objdir = os.path.join(PKG_DIR, "_build") if out_path is None else out_path + ".obj"
+def build(verbose: bool = False) -> str:
+    """Compile every source for gfx950 and link the shared library.  Always recompiles."""
+    objdir = os.path.join(PKG_DIR, "_build")
     os.makedirs(objdir, exist_ok=True)
     procs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc(), *HIP_FLAGS, *extra_flags, "-c", os.path.join(csrc_dir or CSRC, src), "-o", obj]
+        cmd = [hipcc(), *HIP_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, obj, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -44,7 +43,7 @@ def build(verbose: bool = False, extra_flags=(), out_path: str | None = None, cs
         if verbose and out.strip():
             print(out)
         objs.append(obj)
-    lib_path = out_path or LIB_PATH
+    lib_path = LIB_PATH
     tmp = lib_path + ".tmp"
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

@@ -1,6 +1,7 @@
 // C-ABI layer of librfkv: host-side validation, launch geometry, workspace carving and the
 // kernel launch sequences.  The contract of every entry point is documented in include/rfkv.h.
 #include "../../include/rfkv.h"
+#include "../../include/rfkv_bench.h"
 
 #include <cmath>
 #include <cstring>
@@ -58,15 +59,13 @@ int32_t choose_span(int64_t total_tokens, int32_t n_kv_heads, int max_iters) {
 // streaming kernels cannot hold, and, where their 256-byte row limit allows, every window of more
 // than 128 score rows: from 5 to 8 row tiles they already beat the streaming kernels, which would
 // have to re-read part of the queries from LDS for every key tile.
-#ifndef RFKV_WIDE_ABOVE
-#define RFKV_WIDE_ABOVE 128
-#endif
+constexpr int kWideAbove = 128;
 bool wide_window(const rfkv_params* p) {
   const int64_t rows = (int64_t)p->window * (p->n_q_heads / p->n_kv_heads);
   const int64_t rows32 = (rows + 31) / 32 * 32;
   const int eb = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
   if (rows32 > RFKV_MAX_SCORE_ROWS) return true;
-  return rows32 > RFKV_WIDE_ABOVE && p->head_dim * eb <= 256;
+  return rows32 > kWideAbove && p->head_dim * eb <= 256;
 }
 
 rfkv_status check_params(const rfkv_params* p) {
@@ -334,6 +333,8 @@ rfkv_status rfkv_select(const rfkv_params* params, const float* scores, const in
   c.idx_pad = w.idx_pad;
   c.offsets_out = out_offsets;
   c.idx_out = idx;
+  // the documented capacity of idx: every position of every head, or every slot of the padded layout
+  c.idx_capacity = params->out_pad_rows > 0 ? (int64_t)g.units * params->out_pad_rows : total * params->n_kv_heads;
   return device_status(launch_compact(g, c, s));
 }
 
@@ -405,8 +406,8 @@ static rfkv_status decode_check(const rfkv_params* p, int32_t n_new) {
 
 static rfkv_status decode_impl(const rfkv_params* params, const void* q_new, int32_t n_new, const void* k,
                                const void* v, const int32_t* cu_host, const int32_t* cu_dev,
-                               const int64_t* out_offsets, const uint8_t* keep_mask, bool masked, float* out,
-                               void* ws, size_t ws_bytes, void* stream) {
+                               const int64_t* out_offsets, const int32_t* kept, const uint8_t* keep_mask, bool masked,
+                               float* out, void* ws, size_t ws_bytes, void* stream) {
   rfkv_status st = decode_check(params, n_new);
   if (st != RFKV_OK) return st;
   if (!cu_host || cu_host[0] != 0) return RFKV_INVALID_ARG;
@@ -421,8 +422,8 @@ static rfkv_status decode_impl(const rfkv_params* params, const void* q_new, int
   if (masked) {
     if (!cu_dev || !keep_mask) return RFKV_INVALID_ARG;
     if ((st = check_strides(params, false, true, true)) != RFKV_OK) return st;
-  } else if (!out_offsets) {
-    return RFKV_INVALID_ARG;
+  } else if (!out_offsets || (params->out_pad_rows > 0 && !kept)) {
+    return RFKV_INVALID_ARG;       // a padded cache is only described by its kept counts
   }
   if (max_len > 0 && (!aligned16(k) || !aligned16(v))) return RFKV_INVALID_ARG;
   DecodeArgs a{};
@@ -448,6 +449,7 @@ static rfkv_status decode_impl(const rfkv_params* params, const void* q_new, int
     a.v_stride_head = params->v_stride_head;
   } else {
     a.offsets = out_offsets;
+    a.kept = kept;
     a.k_stride_tok = a.v_stride_tok = params->head_dim;
     a.k_stride_head = a.v_stride_head = 0;
   }
@@ -464,16 +466,16 @@ size_t rfkv_decode_workspace_bytes(const rfkv_params* params, int32_t n_new, int
 
 rfkv_status rfkv_decode_attention(const rfkv_params* params, const void* q_new, int32_t n_new, const void* k_c,
                                   const void* v_c, const int32_t* cu_seqlens_host, const int64_t* out_offsets,
-                                  float* out, void* ws, size_t ws_bytes, void* stream) {
-  return decode_impl(params, q_new, n_new, k_c, v_c, cu_seqlens_host, nullptr, out_offsets, nullptr, false, out, ws,
-                     ws_bytes, stream);
+                                  const int32_t* kept_opt, float* out, void* ws, size_t ws_bytes, void* stream) {
+  return decode_impl(params, q_new, n_new, k_c, v_c, cu_seqlens_host, nullptr, out_offsets, kept_opt, nullptr, false,
+                     out, ws, ws_bytes, stream);
 }
 
 rfkv_status rfkv_masked_attention(const rfkv_params* params, const void* q_new, int32_t n_new, const void* k,
                                   const void* v, const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
                                   const uint8_t* keep_mask, float* out, void* ws, size_t ws_bytes, void* stream) {
-  return decode_impl(params, q_new, n_new, k, v, cu_seqlens_host, cu_seqlens_dev, nullptr, keep_mask, true, out, ws,
-                     ws_bytes, stream);
+  return decode_impl(params, q_new, n_new, k, v, cu_seqlens_host, cu_seqlens_dev, nullptr, nullptr, keep_mask, true,
+                     out, ws, ws_bytes, stream);
 }
 
 static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_win, const float* lse_win,
@@ -525,6 +527,7 @@ static rfkv_status compress_layer_impl(const rfkv_params* params, const void* q_
   c.offsets_out = out_offsets;
   c.idx_out = idx_opt;
   c.capacity_rows = out_capacity_rows;
+  c.idx_capacity = out_capacity_rows;
   e = launch_compact(g, c, s);
   if (marks && e == hipSuccess) marks->after(kKernelCompact);
   return device_status(e);

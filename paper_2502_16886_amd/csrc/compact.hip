@@ -24,18 +24,8 @@
 namespace rfkv {
 namespace {
 
-#ifndef RFKV_COMPACT_ROWS
-#define RFKV_COMPACT_ROWS 16
-#endif
-#ifndef RFKV_COMPACT_UNROLL
-#define RFKV_COMPACT_UNROLL 1
-#endif
-#ifndef RFKV_COMPACT_ROWS_MANY
-#define RFKV_COMPACT_ROWS_MANY 32
-#endif
-#ifndef RFKV_COMPACT_UNROLL_MANY
-#define RFKV_COMPACT_UNROLL_MANY 2
-#endif
+constexpr int kRowsFew = 16, kUnrollFew = 1;      // a handful of units
+constexpr int kRowsMany = 32, kUnrollMany = 2;    // many units
 // The rows are read once and written once: non-temporal accesses keep them from displacing what the
 // other kernels of the pass (and of the layers running beside it) re-use from the L2 and the
 // Infinity Cache.  The copy itself runs at the same rate; the scoring pass next to it gets faster
@@ -97,7 +87,7 @@ __global__ __launch_bounds__(kBlockThreads) void compact_kernel(CompactArgs a) {
   const int row1 = min(kept, row0 + kRowsPerBlock);
   if (a.idx_out) {
     for (int t = row0 + threadIdx.x; t < row1; t += kBlockThreads)
-      a.idx_out[off + t] = idx ? idx[t] : (t < sinks ? t : n - kept + t);
+      if (off + t < a.idx_capacity) a.idx_out[off + t] = idx ? idx[t] : (t < sinks ? t : n - kept + t);
   }
   if (!a.k_out) return;
 
@@ -184,12 +174,12 @@ hipError_t launch_compact(const Geometry& g, const CompactArgs& a_in, hipStream_
     a.offsets_ready = 1;
   }
   if (g.units <= kUniformPrefixUnits) {
-    const int xblocks = max(1, (g.max_seqlen + RFKV_COMPACT_ROWS - 1) / RFKV_COMPACT_ROWS);
-    hipLaunchKernelGGL((compact_kernel<RFKV_COMPACT_ROWS, RFKV_COMPACT_UNROLL>), dim3(xblocks, g.units),
+    const int xblocks = max(1, (g.max_seqlen + kRowsFew - 1) / kRowsFew);
+    hipLaunchKernelGGL((compact_kernel<kRowsFew, kUnrollFew>), dim3(xblocks, g.units),
                        dim3(kBlockThreads), 0, stream, a);
   } else {
-    const int xblocks = max(1, (g.max_seqlen + RFKV_COMPACT_ROWS_MANY - 1) / RFKV_COMPACT_ROWS_MANY);
-    hipLaunchKernelGGL((compact_kernel<RFKV_COMPACT_ROWS_MANY, RFKV_COMPACT_UNROLL_MANY>), dim3(xblocks, g.units),
+    const int xblocks = max(1, (g.max_seqlen + kRowsMany - 1) / kRowsMany);
+    hipLaunchKernelGGL((compact_kernel<kRowsMany, kUnrollMany>), dim3(xblocks, g.units),
                        dim3(kBlockThreads), 0, stream, a);
   }
   return hipGetLastError();

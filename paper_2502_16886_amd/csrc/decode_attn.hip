@@ -26,25 +26,16 @@
 // Tunables of the 256-row decode workgroup (rows per wavefront / 32, 32-key tiles per stage).
 // Measured on config 4 (64 new queries, attention + merge): 4 wavefronts x 64 rows, 1 tile per stage
 // 276 us; 8 x 32 rows, 1 tile 208 us; 8 x 32 rows, 2 tiles 193 us; 4 x 64 rows, 2 tiles 254 us.
-#ifndef RFKV_DECODE_RTW
-#define RFKV_DECODE_RTW 1
-#endif
-#ifndef RFKV_DECODE_KT
-#define RFKV_DECODE_KT 2
-#endif
-#ifndef RFKV_DECODE_KT_SMALL
-#define RFKV_DECODE_KT_SMALL 1
-#endif
-
 namespace rfkv {
 namespace {
 
+constexpr int kDecodeRtw = 1;          // 32-row tiles per wavefront of the 256-row workgroup
+constexpr int kDecodeKt = 2;           // 32-key tiles per stage, 256-row workgroup
+constexpr int kDecodeKtSmall = 1;      // 32-key tiles per stage, 128-row workgroup
+
 // Shape of a decode workgroup: W wavefronts of 32 * RTW query rows each; a pipeline stage holds
 // KT 32-key tiles of K and of V; kStagesFor stages of them are in flight / in use.
-#ifndef RFKV_DECODE_STAGES2
-#define RFKV_DECODE_STAGES2 3
-#endif
-constexpr int stages_for(int kt) { return kt == 1 ? 4 : RFKV_DECODE_STAGES2; }
+constexpr int stages_for(int kt) { return kt == 1 ? 4 : 3; }
 // tiles per stage, raised where a stage would otherwise hold fewer load instructions than wavefronts
 constexpr int kt_for(int d, int w, int kt) { return kt * (d / 16) < w ? w / (d / 16) : kt; }
 
@@ -129,6 +120,7 @@ __device__ __forceinline__ DUnit load_dunit(const DecodeArgs& a, int unit) {
   } else {
     u.row0 = a.offsets[unit];
     u.len = (int)(a.offsets[unit + 1] - u.row0);
+    if (a.kept) u.len = min(max(a.kept[unit], 0), u.len);    // padded layout: the slot's first kept rows
   }
   return u;
 }
@@ -560,7 +552,7 @@ template <int D, int RTW, int W, int KT, bool MASKED>
 hipError_t launch_attn(const DecodeArgs& a, hipStream_t stream) {
   constexpr int kStages = stages_for(KT);
   const size_t lds = 2 * kStages * KT * DShape<D>::kTileBytes + (MASKED ? kStages * W * 64 * sizeof(uint32_t) : 0);
-  const hipError_t e = allow_lds(decode_attn_kernel<D, RTW, W, KT, MASKED>, lds);
+  const hipError_t e = allow_lds<&decode_attn_kernel<D, RTW, W, KT, MASKED>>(lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_attn_kernel<D, RTW, W, KT, MASKED>), dim3(a.max_items), dim3(W * 64), lds, stream, a);
   return hipGetLastError();
@@ -571,10 +563,10 @@ hipError_t launch_typed(const DecodeArgs& a, int units, hipStream_t stream) {
   hipLaunchKernelGGL(decode_plan_kernel<MASKED>, dim3(1), dim3(1024), 0, stream, a, units);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  // up to 128 rows: 4 wavefronts of 32 rows, two workgroups per CU; up to 256: see RFKV_DECODE_* below
-  constexpr int kWBig = 256 / (32 * RFKV_DECODE_RTW);
-  if (a.rows_pad <= 128) e = launch_attn<D, 1, 4, kt_for(D, 4, RFKV_DECODE_KT_SMALL), MASKED>(a, stream);
-  else e = launch_attn<D, RFKV_DECODE_RTW, kWBig, kt_for(D, kWBig, RFKV_DECODE_KT), MASKED>(a, stream);
+  // up to 128 rows: 4 wavefronts of 32 rows, two workgroups per CU; up to 256: 8 wavefronts of 32 rows
+  constexpr int kWBig = 256 / (32 * kDecodeRtw);
+  if (a.rows_pad <= 128) e = launch_attn<D, 1, 4, kt_for(D, 4, kDecodeKtSmall), MASKED>(a, stream);
+  else e = launch_attn<D, kDecodeRtw, kWBig, kt_for(D, kWBig, kDecodeKt), MASKED>(a, stream);
   if (e != hipSuccess) return e;
   const int items = a.rows * (D / 4);
   hipLaunchKernelGGL(decode_merge_kernel<MASKED>, dim3((items + 255) / 256, units), dim3(256), 0, stream, a);

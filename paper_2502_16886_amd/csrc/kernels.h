@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace rfkv {
 
 constexpr int kBlockThreads = 256;     // 4 wavefronts per workgroup in the score / compact kernels
@@ -94,6 +96,7 @@ struct CompactArgs {
   int32_t* idx_out;             // other sources: packed indices written here (may be null)
   int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;
   int64_t capacity_rows;
+  int64_t idx_capacity;         // entries of idx_out; indices at or beyond it are not written
   int64_t pad_rows;             // > 0: padded layout, unit u's rows start at u * pad_rows (not kSrcPackedIdx)
   int32_t n_kv_heads, units, row_bytes, source;
   int32_t offsets_ready;        // set by launch_compact: offsets_out already holds the exclusive scan (many units)
@@ -106,6 +109,7 @@ struct DecodeArgs {
   const void* k;
   const void* v;
   const int64_t* offsets;   // compacted: first row of every unit, [units + 1]
+  const int32_t* kept;      // compacted, optional: rows of every unit (padded layout: fewer than its slot)
   const int32_t* cu;        // masked: cu_seqlens
   const uint8_t* mask;      // masked: [Hkv][N], non-zero = retained
   float* out;               // [B, n_new, Hq, d]
@@ -128,6 +132,25 @@ struct Marks {
   hipStream_t stream;
   void after(int kernel) const { (void)hipEventRecord(ev[kernel + 1], stream); }
 };
+
+// Raises a kernel's limit on dynamic LDS, once per device, to the most any launch of it may ask for.
+// (Setting it per launch to that launch's own size would let two host threads with different
+// problem sizes lower the limit under each other between the call and the launch.)
+template <auto Kernel>
+hipError_t allow_lds(size_t max_bytes) {
+  static std::atomic<uint64_t> done{0};                // bit d: raised on device d
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)max_bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
+// the most dynamic LDS the argument checks admit for the kernels that keep the window queries in LDS
+constexpr size_t kMaxQueryLds = 156 * 1024;
 
 hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream,
                         const Marks* marks = nullptr);

@@ -293,7 +293,7 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_reduce_kernel(ScoreArg
 template <typename T, int D, int RT_T>
 hipError_t launch_stats(const Geometry& g, const ScoreArgs& a, dim3 grid, hipStream_t stream) {
   const size_t lds = (size_t)g.rows_pad * Shape<T, D>::kLdsRowBytes;
-  hipError_t e = allow_lds(score_stats_kernel<T, D, RT_T>, lds);
+  hipError_t e = allow_lds<&score_stats_kernel<T, D, RT_T>>(kMaxQueryLds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((score_stats_kernel<T, D, RT_T>), grid, dim3(kBlockThreads), lds, stream, a);
   return hipGetLastError();
@@ -320,7 +320,7 @@ hipError_t launch_typed(const Geometry& g, const ScoreArgs& a, hipStream_t strea
   }
 
   const size_t lds = (size_t)g.rows_pad * (Shape<T, D>::kLdsRowBytes + 8);
-  e = allow_lds(score_reduce_kernel<T, D>, lds);
+  e = allow_lds<&score_reduce_kernel<T, D>>(kMaxQueryLds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((score_reduce_kernel<T, D>), grid, dim3(kBlockThreads), lds, stream, a);
   e = hipGetLastError();

@@ -83,12 +83,6 @@ __device__ __forceinline__ Unit load_unit(const ScoreArgs& a, int unit) {
   return u;
 }
 
-template <typename K>
-hipError_t allow_lds(K kernel, size_t bytes) {
-  if (bytes <= 48 * 1024) return hipSuccess;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)bytes);
-}
 
 // Window queries of the unit -> LDS, row r = t * G + g, rows beyond `rows` zero, row stride
 // kLdsRowBytes.  Loads are issued in batches of eight per thread before any of them is stored,

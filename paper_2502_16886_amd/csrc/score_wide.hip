@@ -210,7 +210,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
 template <typename T, int D>
 hipError_t launch_colsum_typed(const Geometry& g, const ScoreArgs& a, hipStream_t stream) {
   constexpr size_t lds = wide_lds_bytes<T, D>();
-  hipError_t e = allow_lds(score_colsum_wide_kernel<T, D>, lds);
+  hipError_t e = allow_lds<&score_colsum_wide_kernel<T, D>>(lds);
   if (e != hipSuccess) return e;
   const int items = (g.max_seqlen + kWideKeys - 1) / kWideKeys * g.units;
   hipLaunchKernelGGL((score_colsum_wide_kernel<T, D>), dim3((items + 7) / 8 * 8), dim3(256), lds, stream, a);

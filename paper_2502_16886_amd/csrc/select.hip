@@ -726,9 +726,8 @@ hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t str
     args.lds_floats = (int32_t)(want < kMaxLdsFloats ? want : kMaxLdsFloats);
   }
   const size_t dyn = (size_t)args.lds_floats * sizeof(float);
-  if (dyn > 32 * 1024) {                           // beyond the default limit on static + dynamic LDS
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)dyn);
+  if (dyn > 0) {
+    const hipError_t e = allow_lds<&select_kernel>((size_t)kMaxLdsFloats * sizeof(float));
     if (e != hipSuccess) return e;
   }
   hipLaunchKernelGGL(select_kernel, dim3(g.units), dim3(kT), dyn, stream, args);

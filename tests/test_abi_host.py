@@ -24,7 +24,8 @@ def lib():
 
 
 def test_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "rfkv.h")).read()
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     declared = set(re.findall(r"RFKV_API\s+[\w\s\*]+?\b(rfkv_\w+)\s*\(", header))
     assert declared == set(B.EXPORTED_SYMBOLS)
     for name in declared:
@@ -141,8 +142,8 @@ def test_binding_raises_on_error(lib):
     assert e.value.status == B.RFKV_INVALID_ARG
 
 
-def decode(p, n_new=64, q=FAKE, k=FAKE, v=FAKE, cu_h=CU, offs=FAKE, out=FAKE, ws=FAKE, wsb=1 << 40):
-    return B.rfkv_decode_attention(p, q, n_new, k, v, cu_h, offs, out, ws, wsb, stream=0, check=False)
+def decode(p, n_new=64, q=FAKE, k=FAKE, v=FAKE, cu_h=CU, offs=FAKE, kept=None, out=FAKE, ws=FAKE, wsb=1 << 40):
+    return B.rfkv_decode_attention(p, q, n_new, k, v, cu_h, offs, kept, out, ws, wsb, stream=0, check=False)
 
 
 def masked(p, n_new=64, q=FAKE, k=FAKE, v=FAKE, cu_h=CU, cu_d=FAKE, mask=FAKE, out=FAKE, ws=FAKE, wsb=1 << 40):
@@ -163,6 +164,9 @@ def test_decode_attention_host_checks(lib):
     assert decode(good(), k=None) == B.RFKV_INVALID_ARG
     assert decode(good(), v=FAKE + 4) == B.RFKV_INVALID_ARG
     assert decode(good(), offs=None) == B.RFKV_INVALID_ARG
+    # a padded cache is described by its kept counts: without them the attention would run over pad rows
+    assert decode(good(out_pad_rows=8192)) == B.RFKV_INVALID_ARG
+    assert decode(good(out_pad_rows=8192), kept=FAKE, wsb=need - 1) == B.RFKV_WORKSPACE_TOO_SMALL
     assert decode(good(), out=None) == B.RFKV_INVALID_ARG
     assert decode(good(), cu_h=None) == B.RFKV_INVALID_ARG
     assert decode(good(), cu_h=np.array([0, -5], dtype=np.int32)) == B.RFKV_INVALID_ARG

@@ -36,15 +36,15 @@ def _check(got, ref, bound, what):
     return worst
 
 
-def _run_decode(dl, q_new_bits, n_new):
+def _run_decode(dl, q_new_bits, n_new, with_kept=False):
     import torch
     c = dl.layer.cfg
     q = H.to_device(q_new_bits, c.dtype)
     out = torch.full((dl.batch, n_new, c.n_q_heads, c.head_dim), float("nan"), dtype=torch.float32, device="cuda")
     ws_bytes = B.rfkv_decode_workspace_bytes(dl.params, n_new, dl.max_len)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
-    B.rfkv_decode_attention(dl.params, q, n_new, dl.buf.k_out, dl.buf.v_out, dl.cu_host, dl.buf.out_offsets, out, ws,
-                            ws_bytes)
+    B.rfkv_decode_attention(dl.params, q, n_new, dl.buf.k_out, dl.buf.v_out, dl.cu_host, dl.buf.out_offsets,
+                            dl.buf.kept if with_kept else None, out, ws, ws_bytes)
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
@@ -139,6 +139,40 @@ def test_decode_key_far_above_the_running_reference(n_new):
     _check(got_m, ref, _bound(qf, k_c, v_c, res["out_offsets"], 8, 2, masked=False), "masked")
 
 
+def test_decode_over_the_padded_layout():
+    """Padded output (Sec. 3.3 "Running at Scale"): every unit owns a slot of out_pad_rows rows of which
+    the first kept[u] hold data.  The attention must stop at kept[u] (the pad rows are poisoned with
+    NaN here) and equal the oracle's attention over the same rows taken slot by slot."""
+    import torch
+    lens, n_new, pad = (700, 33, 1500), 16, 1536
+    cfg = W.Config("t", 1, 8, 2, 128, 16, "bf16", batch=len(lens), context=max(lens), threshold=0.05)
+    layer = W.make_layer(7, 2, cfg=cfg, lengths=lens)
+    qn = W.make_new_queries(7, 2, n_new=n_new, cfg=cfg, lengths=lens)
+    dl = H.DeviceLayer(layer, out_pad_rows=pad)
+    dl.buf.k_out.fill_(float("nan"))
+    dl.buf.v_out.fill_(float("nan"))
+    dl.compress()
+    res = dl.results()
+    units = len(res["kept"])
+    assert np.array_equal(res["out_offsets"], np.arange(units + 1) * pad) and res["kept"].max() < pad
+    got = _run_decode(dl, qn, n_new, with_kept=True)
+    assert np.isfinite(got).all()
+    # the oracle's ragged form of the same cache: the first kept[u] rows of every slot, packed
+    rows = np.concatenate([np.arange(u * pad, u * pad + int(res["kept"][u])) for u in range(units)])
+    offs = np.concatenate([[0], np.cumsum(res["kept"])])
+    qf = W.to_f64(qn, "bf16")
+    k_c, v_c = W.to_f64(res["k_out"][rows], "bf16"), W.to_f64(res["v_out"][rows], "bf16")
+    ref = O.oracle_decode_attention(qf, k_c, v_c, offs, 8, 2)
+    _check(got, ref, _bound(qf, k_c, v_c, offs, 8, 2, masked=False), "padded")
+    # without the kept counts the call is refused
+    out = torch.empty((len(lens), n_new, 8, 128), dtype=torch.float32, device="cuda")
+    ws_bytes = B.rfkv_decode_workspace_bytes(dl.params, n_new, dl.max_len)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    st = B.rfkv_decode_attention(dl.params, H.to_device(qn, "bf16"), n_new, dl.buf.k_out, dl.buf.v_out, dl.cu_host,
+                                 dl.buf.out_offsets, None, out, ws, ws_bytes, check=False)
+    assert st == B.RFKV_INVALID_ARG
+
+
 def test_decode_empty_sequences_and_zero_queries():
     cfg = W.Config("t", 1, 8, 2, 128, 16, "bf16", batch=3, context=64)
     lens = (0, 40, 0)
@@ -157,7 +191,7 @@ def test_decode_empty_sequences_and_zero_queries():
     out = torch.empty(0, device="cuda")
     ws = torch.empty(16, dtype=torch.uint8, device="cuda")
     assert B.rfkv_decode_attention(dl.params, dl.q, 0, dl.buf.k_out, dl.buf.v_out, dl.cu_host, dl.buf.out_offsets,
-                                   out, ws, 16) == 0
+                                   None, out, ws, 16) == 0
 
 
 def test_decode_rejects_what_it_does_not_cover():
@@ -168,9 +202,9 @@ def test_decode_rejects_what_it_does_not_cover():
     assert B.rfkv_decode_workspace_bytes(p, 65, 100) == 0           # 65 * 4 rows > 256
     cu = np.array([0, 100], np.int32)
     t = torch.empty(4096, dtype=torch.uint8, device="cuda")
-    st = B.rfkv_decode_attention(p, t, 65, t, t, cu, t, t, t, 4096, check=False)
+    st = B.rfkv_decode_attention(p, t, 65, t, t, cu, t, None, t, t, 4096, check=False)
     assert st == B.RFKV_UNSUPPORTED
-    st = B.rfkv_decode_attention(p, t, 4, t, t, cu, t, t, t, 16, check=False)
+    st = B.rfkv_decode_attention(p, t, 4, t, t, cu, t, None, t, t, 16, check=False)
     assert st == B.RFKV_WORKSPACE_TOO_SMALL
 
 

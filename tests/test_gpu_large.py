@@ -88,7 +88,7 @@ def test_more_than_2g_elements(mode):
         out = torch.full((2, n_new, HQ, D), float("nan"), dtype=torch.float32, device="cuda")
         dws_bytes = B.rfkv_decode_workspace_bytes(p, n_new, max(LENS))
         dws = torch.empty(dws_bytes, dtype=torch.uint8, device="cuda")
-        B.rfkv_decode_attention(p, qn, n_new, buf.k_out, buf.v_out, cu, buf.out_offsets, out, dws, dws_bytes)
+        B.rfkv_decode_attention(p, qn, n_new, buf.k_out, buf.v_out, cu, buf.out_offsets, None, out, dws, dws_bytes)
         torch.cuda.synchronize()
         got = out.cpu().numpy().astype(np.float64)
         assert np.isfinite(got).all()

@@ -95,6 +95,17 @@ def test_padded_layout_matches_ragged():
         p = padded.results()
         units = len(r["kept"])
         assert np.array_equal(p["kept"], r["kept"])
+        # against the oracle: its rule on the GPU's scores, its gather, laid out slot by slot; the mask is t < kept[u]
+        sel = O.oracle_select_layer if gran == B.PER_LAYER else O.oracle_select
+        okept, ooffs, oidx = sel(p["scores"].astype(np.float64), layer.cu_seqlens, O.RANK_POSITION, cfg.n_sink,
+                                 H.threshold_as_float32(cfg.threshold), 0, form="cumsum")
+        ok, ov = O.oracle_compact(layer.k, layer.v, layer.cu_seqlens, okept, ooffs, oidx)
+        assert np.array_equal(p["kept"], okept)
+        for u in range(units):
+            c, o = int(okept[u]), int(ooffs[u])
+            assert np.array_equal(p["k_out"][u * pad:u * pad + c], ok[o:o + c])
+            assert np.array_equal(p["v_out"][u * pad:u * pad + c], ov[o:o + c])
+            assert np.array_equal(p["idx"][u * pad:u * pad + c], oidx[o:o + c])
         assert np.array_equal(p["out_offsets"], np.arange(units + 1) * pad)
         for u in range(units):
             c, o = int(r["kept"][u]), int(r["out_offsets"][u])
