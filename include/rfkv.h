@@ -192,6 +192,27 @@ RFKV_API rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* 
                                 int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * rfkv_compress_layer for callers that cannot allocate device memory: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  They have no workspace to hand
+ * over, so this entry point takes none: its scratch is a fixed array of RFKV_STATIC_SCRATCH_BYTES
+ * that is part of the library's device image (each GPU the library runs on holds its own copy until
+ * the process ends).  Nothing is allocated or freed, by the library or by anything it calls.
+ *   - The device of `stream` must be the current device.
+ *   - RFKV_WORKSPACE_TOO_SMALL if the batch needs more scratch than RFKV_STATIC_SCRATCH_BYTES
+ *     (rfkv_workspace_bytes(params, N, longest sequence) bounds the need from above; a 32768-token
+ *     Llama3-8B layer needs 2.6 MB, a 131072-token one 8.5 MB).  Nothing is enqueued then.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap (different streams,
+ *     different host threads) race on it.  Order them on one stream.
+ * Arguments, outputs and every other error as rfkv_compress_layer.
+ */
+enum { RFKV_STATIC_SCRATCH_BYTES = 16 * 1024 * 1024 };
+RFKV_API rfkv_status rfkv_compress_layer_static(const rfkv_params* params, const void* q_win, const void* k,
+                                const void* v, const int32_t* cu_seqlens_host,
+                                const int32_t* cu_seqlens_dev, float* scores_opt, int32_t* kept,
+                                int64_t* out_offsets, int32_t* idx_opt, void* k_out, void* v_out,
+                                int64_t out_capacity_rows, void* stream);
+
+/*
  * Scoring and the fused pass when the prefill already has the window rows' softmax normalisers.
  * A causal attention forward pass returns, next to its output, the log-sum-exp of every query
  * row: lse[t, hq] = ln sum_{i <= pos(t)} exp(scale * q[t, hq] . k[i]).  For the window rows this is

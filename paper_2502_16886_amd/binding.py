@@ -17,6 +17,7 @@ RFKV_UNSUPPORTED = 2
 RFKV_WORKSPACE_TOO_SMALL = 3
 RFKV_OUTPUT_TOO_SMALL = 4
 RFKV_DEVICE_ERROR = 5
+STATIC_SCRATCH_BYTES = 16 * 1024 * 1024
 
 RANK_POSITION = 0
 RANK_SCORE = 1
@@ -82,6 +83,8 @@ def load_library() -> ctypes.CDLL:
     lib.rfkv_compact.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.rfkv_compress_layer.restype = ctypes.c_int
     lib.rfkv_compress_layer.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    lib.rfkv_compress_layer_static.restype = ctypes.c_int
+    lib.rfkv_compress_layer_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.rfkv_compress_layer_timed.restype = ctypes.c_int
     lib.rfkv_compress_layer_timed.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp, vp]
     lib.rfkv_score_lse.restype = ctypes.c_int
@@ -100,7 +103,7 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = ("rfkv_version", "rfkv_status_string", "rfkv_last_device_error", "rfkv_workspace_bytes",
                     "rfkv_score", "rfkv_select", "rfkv_compact", "rfkv_compress_layer",
-                    "rfkv_compress_layer_timed", "rfkv_score_lse", "rfkv_compress_layer_lse",
+                    "rfkv_compress_layer_static", "rfkv_compress_layer_timed", "rfkv_score_lse", "rfkv_compress_layer_lse",
                     "rfkv_decode_workspace_bytes", "rfkv_decode_attention", "rfkv_masked_attention")
 KERNEL_NAMES = ("score_stats", "score_merge", "score_reduce", "select", "compact")
 
@@ -181,6 +184,15 @@ def rfkv_compress_layer(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, 
                                             _ptr(idx_opt), _ptr(k_out), _ptr(v_out), int(out_capacity_rows),
                                             _ptr(ws), int(ws_bytes), _stream(stream))
     return _check(st, "rfkv_compress_layer", check)
+
+
+def rfkv_compress_layer_static(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, out_offsets, idx_opt, k_out,
+                               v_out, out_capacity_rows, stream=None, check=True) -> int:
+    st = load_library().rfkv_compress_layer_static(ctypes.byref(params), _ptr(q_win), _ptr(k), _ptr(v),
+                                                   _ptr(cu_host), _ptr(cu_dev), _ptr(scores_opt), _ptr(kept),
+                                                   _ptr(out_offsets), _ptr(idx_opt), _ptr(k_out), _ptr(v_out),
+                                                   int(out_capacity_rows), _stream(stream))
+    return _check(st, "rfkv_compress_layer_static", check)
 
 
 def rfkv_compress_layer_lse(params, q_win, lse_win, k, v, cu_host, cu_dev, scores_opt, kept, out_offsets, idx_opt,

@@ -8,9 +8,37 @@
 
 #include "kernels.h"
 
+#include <mutex>
+
+// Scratch of rfkv_compress_layer_static.  In host code this name is only a handle for
+// hipGetSymbolAddress: the device address (one per GPU) is looked up once per device and used from
+// then on wherever the array's memory is meant.
+static __device__ __align__(256) unsigned char scratch[RFKV_STATIC_SCRATCH_BYTES];
+
 namespace rfkv {
 
 static thread_local int32_t g_last_device_error = 0;
+
+// Device address of `scratch` on the current device, looked up on the first call on that device.
+static hipError_t static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptr[dev] = p;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
+}
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -539,6 +567,28 @@ rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, co
                                 int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream) {
   return compress_layer_impl(params, q_win, nullptr, false, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept,
                              out_offsets, idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, nullptr);
+}
+
+rfkv_status rfkv_compress_layer_static(const rfkv_params* params, const void* q_win, const void* k, const void* v,
+                                       const int32_t* cu_seqlens_host, const int32_t* cu_seqlens_dev,
+                                       float* scores_opt, int32_t* kept, int64_t* out_offsets, int32_t* idx_opt,
+                                       void* k_out, void* v_out, int64_t out_capacity_rows, void* stream) {
+  // the size check comes first: it needs no device, and a problem that does not fit must not get as far
+  // as looking the array up
+  rfkv_status st = check_params(params);
+  if (st != RFKV_OK) return st;
+  int64_t total;
+  int32_t max_len;
+  if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
+  if (params->batch == 0) return RFKV_OK;
+  const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
+  if (carve_workspace(g, nullptr).bytes > (size_t)RFKV_STATIC_SCRATCH_BYTES) return RFKV_WORKSPACE_TOO_SMALL;
+  void* ws = nullptr;
+  const hipError_t e = static_scratch(&ws);
+  if (e != hipSuccess) return device_status(e);
+  return compress_layer_impl(params, q_win, nullptr, false, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept,
+                             out_offsets, idx_opt, k_out, v_out, out_capacity_rows, ws, RFKV_STATIC_SCRATCH_BYTES,
+                             stream, nullptr);
 }
 
 rfkv_status rfkv_compress_layer_lse(const rfkv_params* params, const void* q_win, const float* lse_win, const void* k,

@@ -136,6 +136,21 @@ def test_empty_batches_are_no_ops(lib):
     assert score(good(batch=1), cu_h=np.array([0, 0], dtype=np.int32)) == B.RFKV_OK     # one empty sequence
 
 
+def test_static_scratch_entry_point_host_checks(lib):
+    """rfkv_compress_layer_static validates like rfkv_compress_layer and refuses, on the host, a batch
+    whose scratch would not fit its fixed array (nothing is looked up or enqueued before that)."""
+    def static(p, cu_h=CU, cap=8192 * 8):
+        return B.rfkv_compress_layer_static(p, FAKE, FAKE, FAKE, cu_h, FAKE, None, FAKE, FAKE, None, FAKE, FAKE, cap,
+                                            stream=0, check=False)
+    assert static(good(window=0)) == B.RFKV_INVALID_ARG
+    assert static(good(head_dim=96)) == B.RFKV_UNSUPPORTED
+    assert static(good(), cu_h=None) == B.RFKV_INVALID_ARG
+    n = 400000
+    assert B.rfkv_workspace_bytes(good(), n, n) > B.STATIC_SCRATCH_BYTES
+    assert static(good(), cu_h=np.array([0, n], dtype=np.int32), cap=n * 8) == B.RFKV_WORKSPACE_TOO_SMALL
+    assert static(good(batch=0), cu_h=np.array([0], dtype=np.int32)) == B.RFKV_OK
+
+
 def test_binding_raises_on_error(lib):
     with pytest.raises(B.RfkvError) as e:
         B.rfkv_score(good(window=0), FAKE, FAKE, CU, FAKE, FAKE, FAKE, 1 << 40, stream=0)
