@@ -192,6 +192,31 @@ RFKV_API rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* 
                                 int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Alg. 1's loop over the layers of a prefilled model in one call: layer l of n_layers has its own
+ * queries, cache and outputs, q_win[l], k[l], v[l], kept[l], ... (host arrays of n_layers device
+ * pointers each; scores_opt and idx_opt may be NULL as a whole), and all layers share params, the
+ * strides in it, cu_seqlens and out_capacity_rows.  The result for every layer is what
+ * rfkv_compress_layer gives for it, up to the rounding of the rows' softmax normalisers (they are
+ * folded from longer spans of keys here; scores agree to a few units in the last place).  Layers the
+ * caller wants to keep whole (the paper keeps the first two, Sec. 3.3 "Retaining Bottom Layers") are
+ * simply not passed.
+ * Having all layers at once lets the library run the steps of different layers side by side: with the
+ * position ranking, one cut per unit and up to 128 score rows per KV head, one launch works on the
+ * statistics pass of layer j, the reduction pass and the cut of layer j - 1 and the compaction of
+ * layer j - 2 (they do not depend on each other).  Other problems run layer after layer.
+ *   ws   device scratch of at least rfkv_layers_workspace_bytes(params, n_layers, N, longest sequence)
+ * Errors as rfkv_compress_layer.
+ */
+RFKV_API size_t rfkv_layers_workspace_bytes(const rfkv_params* params, int32_t n_layers, int64_t total_tokens,
+                                            int32_t max_seqlen);
+RFKV_API rfkv_status rfkv_compress_layers(const rfkv_params* params, int32_t n_layers, const void* const* q_win,
+                                const void* const* k, const void* const* v, const int32_t* cu_seqlens_host,
+                                const int32_t* cu_seqlens_dev, float* const* scores_opt, int32_t* const* kept,
+                                int64_t* const* out_offsets, int32_t* const* idx_opt, void* const* k_out,
+                                void* const* v_out, int64_t out_capacity_rows, void* ws, size_t ws_bytes,
+                                void* stream);
+
+/*
  * rfkv_compress_layer for callers that cannot allocate device memory: code running under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  They have no workspace to hand
  * over, so this entry point takes none: its scratch is a fixed array of RFKV_STATIC_SCRATCH_BYTES

@@ -83,6 +83,10 @@ def load_library() -> ctypes.CDLL:
     lib.rfkv_compact.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.rfkv_compress_layer.restype = ctypes.c_int
     lib.rfkv_compress_layer.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
+    lib.rfkv_layers_workspace_bytes.restype = sz
+    lib.rfkv_layers_workspace_bytes.argtypes = [P, i32, i64, i32]
+    lib.rfkv_compress_layers.restype = ctypes.c_int
+    lib.rfkv_compress_layers.argtypes = [P, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, sz, vp]
     lib.rfkv_compress_layer_static.restype = ctypes.c_int
     lib.rfkv_compress_layer_static.argtypes = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i64, vp]
     lib.rfkv_compress_layer_timed.restype = ctypes.c_int
@@ -103,7 +107,8 @@ def load_library() -> ctypes.CDLL:
 
 EXPORTED_SYMBOLS = ("rfkv_version", "rfkv_status_string", "rfkv_last_device_error", "rfkv_workspace_bytes",
                     "rfkv_score", "rfkv_select", "rfkv_compact", "rfkv_compress_layer",
-                    "rfkv_compress_layer_static", "rfkv_compress_layer_timed", "rfkv_score_lse", "rfkv_compress_layer_lse",
+                    "rfkv_compress_layer_static", "rfkv_layers_workspace_bytes", "rfkv_compress_layers",
+                    "rfkv_compress_layer_timed", "rfkv_score_lse", "rfkv_compress_layer_lse",
                     "rfkv_decode_workspace_bytes", "rfkv_decode_attention", "rfkv_masked_attention")
 KERNEL_NAMES = ("score_stats", "score_merge", "score_reduce", "select", "compact")
 
@@ -184,6 +189,32 @@ def rfkv_compress_layer(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, 
                                             _ptr(idx_opt), _ptr(k_out), _ptr(v_out), int(out_capacity_rows),
                                             _ptr(ws), int(ws_bytes), _stream(stream))
     return _check(st, "rfkv_compress_layer", check)
+
+
+def _ptr_array(items, n):
+    """Host array of n addresses (None for a NULL array)."""
+    if items is None:
+        return None
+    assert len(items) == n
+    arr = (ctypes.c_void_p * n)(*[_ptr(x) for x in items])
+    return arr
+
+
+def rfkv_layers_workspace_bytes(params, n_layers: int, total_tokens: int, max_seqlen: int) -> int:
+    return int(load_library().rfkv_layers_workspace_bytes(ctypes.byref(params), int(n_layers), int(total_tokens),
+                                                          int(max_seqlen)))
+
+
+def rfkv_compress_layers(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, out_offsets, idx_opt, k_out, v_out,
+                         out_capacity_rows, ws, ws_bytes, stream=None, check=True) -> int:
+    """q_win, k, ... are sequences of per-layer tensors (scores_opt / idx_opt may be None)."""
+    n = len(k)
+    arrays = [_ptr_array(x, n) for x in (q_win, k, v)]
+    outs = [_ptr_array(x, n) for x in (scores_opt, kept, out_offsets, idx_opt, k_out, v_out)]
+    st = load_library().rfkv_compress_layers(ctypes.byref(params), n, arrays[0], arrays[1], arrays[2], _ptr(cu_host),
+                                             _ptr(cu_dev), outs[0], outs[1], outs[2], outs[3], outs[4], outs[5],
+                                             int(out_capacity_rows), _ptr(ws), int(ws_bytes), _stream(stream))
+    return _check(st, "rfkv_compress_layers", check)
 
 
 def rfkv_compress_layer_static(params, q_win, k, v, cu_host, cu_dev, scores_opt, kept, out_offsets, idx_opt, k_out,

@@ -9,7 +9,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "librfkv.so")
-SOURCES = ["api.hip", "score.hip", "score_qreg.hip", "score_wide.hip", "select.hip", "compact.hip", "decode_attn.hip"]
+SOURCES = ["api.hip", "score.hip", "score_qreg.hip", "score_wide.hip", "select.hip", "compact.hip", "decode_attn.hip", "pipeline.hip"]
 
 # packed-fp32 VALU forms stay disabled for every device compilation of this library
 HIP_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-fvisibility=hidden",

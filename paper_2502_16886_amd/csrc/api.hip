@@ -57,6 +57,7 @@ Workspace carve_workspace(const Geometry& g, void* base) {
   w.scores = static_cast<float*>(take((size_t)g.total_tokens * g.n_kv_heads * sizeof(float)));
   w.tile_sq = static_cast<double*>(take((size_t)g.tiles_total * g.n_kv_heads * sizeof(double)));
   if (g.spill) w.logits = static_cast<float*>(take((size_t)g.tiles_total * 32 * kSpillRows * g.n_kv_heads * sizeof(float)));
+  w.counters = static_cast<int32_t*>(take((size_t)2 * g.units * sizeof(int32_t)));
   w.bytes = off;
   return w;
 }
@@ -205,10 +206,24 @@ float scale_times_log2e(const rfkv_params* p) {
   return (float)(s * 1.4426950408889634);
 }
 
-hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w, const void* q, const float* lse,
-                     const void* k, const int32_t* cu_dev, float* scores, hipStream_t stream,
-                     const Marks* marks = nullptr) {
+// Can the scoring pass take the position-ranking cut itself (its streaming kernels can, unit by unit, in
+// the workgroup that finishes a unit last)?  The layer pipeline needs that.
+bool select_fuses(const rfkv_params* p, const Geometry& g) {
+  return p->rank_mode == RFKV_RANK_POSITION && p->granularity == RFKV_PER_HEAD && !g.wide &&
+         score_streams(g, p->dtype == RFKV_DTYPE_BF16);
+}
+
+ScoreArgs score_args(const rfkv_params* p, const Geometry& g, const Workspace& w, const void* q, const float* lse,
+                     const void* k, const int32_t* cu_dev, float* scores, int32_t* kept_fused) {
   ScoreArgs a{};
+  a.counters = w.counters;
+  a.fuse_merge = kept_fused ? 1 : 0;                   // the layer pipeline: both hand-overs inside the launch
+  a.fuse_select = kept_fused ? 1 : 0;
+  a.n_sink = p->n_sink;
+  a.min_keep = p->min_keep;
+  a.threshold = p->threshold;
+  a.kept = kept_fused;
+  a.desc = w.desc;
   a.q = q;
   a.lse = lse;
   a.n_q_heads = g.n_q_heads;
@@ -235,7 +250,14 @@ hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w
   a.wide_items = g.wide ? (g.rows_pad / 128) * g.nspans * g.units : 0;
   a.span_colsum = g.max_seqlen;
   a.c = scale_times_log2e(p);
-  return launch_score(g, a, p->dtype == RFKV_DTYPE_BF16, stream, marks);
+  return a;
+}
+
+hipError_t run_score(const rfkv_params* p, const Geometry& g, const Workspace& w, const void* q, const float* lse,
+                     const void* k, const int32_t* cu_dev, float* scores, hipStream_t stream,
+                     const Marks* marks = nullptr, int32_t* kept_fused = nullptr) {
+  return launch_score(g, score_args(p, g, w, q, lse, k, cu_dev, scores, kept_fused), p->dtype == RFKV_DTYPE_BF16,
+                      stream, marks);
 }
 
 hipError_t run_select(const rfkv_params* p, const Geometry& g, const Workspace& w, const float* scores,
@@ -567,6 +589,155 @@ rfkv_status rfkv_compress_layer(const rfkv_params* params, const void* q_win, co
                                 int64_t out_capacity_rows, void* ws, size_t ws_bytes, void* stream) {
   return compress_layer_impl(params, q_win, nullptr, false, k, v, cu_seqlens_host, cu_seqlens_dev, scores_opt, kept,
                              out_offsets, idx_opt, k_out, v_out, out_capacity_rows, ws, ws_bytes, stream, nullptr);
+}
+
+// ---- all layers of a model in one call ---------------------------------------------------------------
+namespace rfkv {
+namespace {
+
+// Keys one scoring work item of the layer pipeline covers: about 128 items per pass and layer, so that
+// the statistics pass of one layer and the reduction pass of another fill kPipelineScoreWgs workgroups
+// with one long span each (a span's fixed costs, query fragments and the first tiles, are paid once).
+int32_t pipeline_span(int64_t total_tokens, int32_t n_kv_heads) {
+  const int64_t keys = total_tokens * n_kv_heads;
+  int64_t span = (keys / (kPipelineScoreWgs / 2) + 127) / 128 * 128;
+  if (span < 512) span = 512;
+  if (span > 16384) span = 16384;
+  return (int32_t)span;
+}
+
+Geometry pipeline_geometry(const Geometry& g) {
+  Geometry p = g;
+  p.span = pipeline_span(g.total_tokens, g.n_kv_heads);
+  p.nspans = (g.max_seqlen + p.span - 1) / p.span;
+  return p;
+}
+
+// Does this problem run as the layer pipeline?  Position ranking with one cut per unit (the scoring pass
+// takes the cut itself), the streaming kernels' shapes with two passes over K, ragged output.
+bool pipeline_covers(const rfkv_params* p, const Geometry& g, int32_t n_layers) {
+  return n_layers >= 2 && g.total_tokens > 0 && p->threshold > 0.f && p->out_pad_rows == 0 && !g.spill &&
+         g.units <= kPipelineMaxUnits && select_fuses(p, g);
+}
+
+struct LayersWorkspace {
+  int32_t* queues;        // [n_layers]              chunk counters of the copies
+  int32_t* counters;      // [n_layers][2][units]    arrival counters of the scoring passes
+  size_t zero_words;      // int32 words from `queues` on that must be zero when the pipeline starts
+  size_t layer_offset;    // first layer's scratch
+  size_t layer_bytes;     // scratch per layer
+  size_t bytes;
+};
+
+LayersWorkspace carve_layers(const Geometry& g, int32_t n_layers, void* base) {
+  LayersWorkspace w{};
+  unsigned char* b = static_cast<unsigned char*>(base);
+  const size_t head = align_up(((size_t)n_layers + (size_t)n_layers * 2 * g.units) * sizeof(int32_t), 256);
+  w.queues = reinterpret_cast<int32_t*>(b);
+  w.counters = w.queues ? w.queues + n_layers : nullptr;
+  w.zero_words = (size_t)n_layers + (size_t)n_layers * 2 * g.units;
+  w.layer_offset = head;
+  const size_t a = carve_workspace(g, nullptr).bytes, p = carve_workspace(pipeline_geometry(g), nullptr).bytes;
+  w.layer_bytes = align_up(a > p ? a : p, 256);
+  w.bytes = head + (size_t)n_layers * w.layer_bytes;
+  return w;
+}
+
+}  // namespace
+}  // namespace rfkv
+
+size_t rfkv_layers_workspace_bytes(const rfkv_params* params, int32_t n_layers, int64_t total_tokens,
+                                   int32_t max_seqlen) {
+  if (n_layers < 0 || rfkv_workspace_bytes(params, total_tokens, max_seqlen) == 0) return 0;
+  const Geometry g = make_geometry(params, total_tokens, max_seqlen);
+  return carve_layers(g, n_layers, nullptr).bytes + 256;
+}
+
+rfkv_status rfkv_compress_layers(const rfkv_params* params, int32_t n_layers, const void* const* q_win,
+                                 const void* const* k, const void* const* v, const int32_t* cu_seqlens_host,
+                                 const int32_t* cu_seqlens_dev, float* const* scores_opt, int32_t* const* kept,
+                                 int64_t* const* out_offsets, int32_t* const* idx_opt, void* const* k_out,
+                                 void* const* v_out, int64_t out_capacity_rows, void* ws, size_t ws_bytes,
+                                 void* stream) {
+  rfkv_status st = check_params(params);
+  if (st != RFKV_OK) return st;
+  if (n_layers < 0) return RFKV_INVALID_ARG;
+  if ((st = check_strides(params, true, true, true)) != RFKV_OK) return st;
+  int64_t total;
+  int32_t max_len;
+  if ((st = check_cu(params, cu_seqlens_host, cu_seqlens_dev, &total, &max_len)) != RFKV_OK) return st;
+  if (n_layers == 0) return RFKV_OK;
+  if (!q_win || !k || !v || !kept || !out_offsets || !k_out || !v_out || out_capacity_rows < 0) return RFKV_INVALID_ARG;
+  if (params->batch > 0 && !aligned16(ws)) return RFKV_INVALID_ARG;
+  const Geometry g = make_geometry(params, total, max_len, cu_seqlens_host);
+  const LayersWorkspace lw = carve_layers(g, n_layers, ws);
+  if (params->batch > 0 && ws_bytes < lw.bytes) return RFKV_WORKSPACE_TOO_SMALL;
+  auto layer_ws = [&](int l) { return static_cast<unsigned char*>(ws) + lw.layer_offset + (size_t)l * lw.layer_bytes; };
+  hipStream_t s = static_cast<hipStream_t>(stream);
+
+  if (!pipeline_covers(params, g, n_layers)) {
+    // layer after layer, each exactly as rfkv_compress_layer (which also validates the layer's pointers)
+    for (int l = 0; l < n_layers; ++l) {
+      st = compress_layer_impl(params, q_win[l], nullptr, false, k[l], v[l], cu_seqlens_host, cu_seqlens_dev,
+                               scores_opt ? scores_opt[l] : nullptr, kept[l], out_offsets[l],
+                               idx_opt ? idx_opt[l] : nullptr, k_out[l], v_out[l], out_capacity_rows, layer_ws(l),
+                               lw.layer_bytes, stream, nullptr);
+      if (st != RFKV_OK) return st;
+    }
+    return RFKV_OK;
+  }
+
+  for (int l = 0; l < n_layers; ++l) {
+    if (!kept[l] || !out_offsets[l]) return RFKV_INVALID_ARG;
+    if (!aligned16(q_win[l]) || !aligned16(k[l]) || !aligned16(v[l]) || !aligned16(k_out[l]) || !aligned16(v_out[l]))
+      return RFKV_INVALID_ARG;
+    if (scores_opt && !aligned16(scores_opt[l])) return RFKV_INVALID_ARG;
+  }
+  const Geometry gp = pipeline_geometry(g);
+  const bool bf16 = params->dtype == RFKV_DTYPE_BF16;
+  hipError_t e = launch_pipeline_prepare(lw.queues, (int64_t)lw.zero_words, s);
+  if (e != hipSuccess) return device_status(e);
+  auto score_of = [&](int l) {
+    const Workspace w = carve_workspace(gp, layer_ws(l));
+    ScoreArgs a = score_args(params, gp, w, q_win[l], nullptr, k[l], cu_seqlens_dev,
+                             scores_opt ? scores_opt[l] : w.scores, kept[l]);
+    a.counters = lw.counters + (size_t)l * 2 * g.units;
+    return a;
+  };
+  const int items = gp.nspans * g.units;
+  // launch j: statistics of layer j, reduction + cut of layer j - 1, compaction of layer j - 2
+  for (int j = 0; j < n_layers + 2; ++j) {
+    PipelineArgs p{};
+    if (j < n_layers) {
+      p.stats = score_of(j);
+      p.stats_items = items;
+    }
+    if (j >= 1 && j - 1 < n_layers) {
+      p.reduce = score_of(j - 1);
+      p.reduce_items = items;
+    }
+    if (j >= 2) {
+      const int l = j - 2;
+      const Workspace w = carve_workspace(gp, layer_ws(l));
+      CompactArgs c = compact_base(params, g, cu_seqlens_dev, kept[l]);
+      c.k = k[l];
+      c.v = v[l];
+      c.k_out = k_out[l];
+      c.v_out = v_out[l];
+      c.source = kSrcPositionDesc;
+      c.desc = w.desc;
+      c.offsets_out = out_offsets[l];
+      c.idx_out = idx_opt ? idx_opt[l] : nullptr;
+      c.capacity_rows = out_capacity_rows;
+      c.idx_capacity = out_capacity_rows;
+      p.copy = c;
+      p.copy_units = g.units;
+      p.queue = lw.queues + l;
+    }
+    e = launch_pipeline_step(gp, p, bf16, s);
+    if (e != hipSuccess) return device_status(e);
+  }
+  return RFKV_OK;
 }
 
 rfkv_status rfkv_compress_layer_static(const rfkv_params* params, const void* q_win, const void* k, const void* v,

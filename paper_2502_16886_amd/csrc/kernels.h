@@ -38,6 +38,8 @@ struct Workspace {
   float*   scores;        // [Hkv][N]                   used when the caller does not want scores
   double*  tile_sq;       // [Hkv][tiles_total]         sum of squared scores per 32-position tile
   float*   logits;        // [Hkv][kSpillRows][tiles_total * 32]  scaled logits, only when window * G <= kSpillRows
+  int32_t* counters;      // [2][units]  workgroups of a unit that have finished the statistics / the reduction pass;
+                          //             zeroed by the call's first kernel, put back to zero by each last arriver
   size_t   bytes;
 };
 
@@ -61,6 +63,20 @@ struct ScoreArgs {
   int32_t units;
   int32_t span_colsum;    // wide window: the longest sequence (keys the column-sum grid covers per unit)
   float c;                // softmax scale * log2(e)
+  // The streaming kernels can hand over between workgroups inside a launch: with `fuse_merge` the last
+  // workgroup of a unit to finish the statistics pass folds the unit's per-span statistics (no merge
+  // kernel), with `fuse_select` the last one to finish the reduction pass takes the unit's position-ranking
+  // cut (no selection kernel).  Each hand-over costs a few memory round trips (acknowledged stores, a
+  // device-scope atomic, coherent loads), about what a small dependent kernel costs, so it pays only
+  // where other work runs beside it: the layer pipeline sets both, the per-layer calls neither.
+  // counters: [2][units], zero before the launch, see Workspace.
+  int32_t* counters;
+  int32_t fuse_merge;
+  int32_t fuse_select;
+  int32_t n_sink, min_keep;
+  float threshold;
+  int32_t* kept;          // fuse_select: [units]
+  int4* desc;             // fuse_select: [units] {kept, sinks kept, -, -}
 };
 
 struct SelectArgs {
@@ -100,6 +116,21 @@ struct CompactArgs {
   int64_t pad_rows;             // > 0: padded layout, unit u's rows start at u * pad_rows (not kSrcPackedIdx)
   int32_t n_kv_heads, units, row_bytes, source;
   int32_t offsets_ready;        // set by launch_compact: offsets_out already holds the exclusive scan (many units)
+};
+
+// One launch of the layer pipeline (pipeline.hip): the statistics pass of one layer, the reduction
+// pass (with the position-ranking cut) of the layer before it and the gather-compaction of the layer
+// before that, any of which may be absent at the ends of the pipeline.
+constexpr int kPipelineGrid = 512;          // two workgroups on each of 256 CUs
+constexpr int kPipelineScoreWgs = 256;      // of which about this many start with a scoring work item
+constexpr int kPipelineMaxUnits = 512;      // units of a layer (a table of them lives in LDS)
+struct PipelineArgs {
+  ScoreArgs stats, reduce;
+  CompactArgs copy;
+  int32_t* queue;           // chunk counter of this launch's copy, zero before the launch
+  int32_t stats_items;      // spans x units of the statistics pass, 0 if absent
+  int32_t reduce_items;     // spans x units of the reduction pass, 0 if absent
+  int32_t copy_units;       // units of the layer to compact, 0 if absent
 };
 
 // Attention of new queries over the compacted cache (offsets != null) or over the full cache
@@ -154,8 +185,12 @@ constexpr size_t kMaxQueryLds = 156 * 1024;
 
 hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream,
                         const Marks* marks = nullptr);
+// does launch_score run the streaming kernels (score_qreg.hip) for this shape?
+bool score_streams(const Geometry& g, bool bf16);
 hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t stream);
 hipError_t launch_compact(const Geometry& g, const CompactArgs& a, hipStream_t stream);
+hipError_t launch_pipeline_prepare(int32_t* words, int64_t n, hipStream_t stream);
+hipError_t launch_pipeline_step(const Geometry& g, const PipelineArgs& p, bool bf16, hipStream_t stream);
 hipError_t launch_decode_attention(const DecodeArgs& a, int units, bool masked, hipStream_t stream);
 
 }  // namespace rfkv

@@ -348,6 +348,8 @@ hipError_t launch_score_offsets(const Geometry& g, const ScoreArgs& a, hipStream
   return e;
 }
 
+bool score_streams(const Geometry& g, bool bf16) { return !g.wide && score_qreg_covers(g, bf16); }
+
 hipError_t launch_score(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream, const Marks* marks) {
   if (g.units == 0 || g.nspans == 0) return hipSuccess;
   if (g.wide) return launch_score_wide(g, a, bf16, stream, marks);

@@ -16,12 +16,14 @@
 // of elements taken from the final all-equal bucket by bisection.  The retained positions are
 // then emitted in ascending order with a block-wide scan (ties: the lowest positions win).
 #include "kernels.h"
+#include "select_position.h"
 #include "tile_sum.h"
 
 namespace rfkv {
 namespace {
 
 constexpr int kT = kSelectThreads;
+constexpr int kPosThreads = 256;                   // the position ranking's workgroup, here and in the scoring pass
 constexpr int kWaves = kT / 64;
 constexpr int kBuckets = 2048;
 constexpr int kMaxLdsFloats = 32768 + 4;           // scores of one unit held in LDS by the score ranking
@@ -102,18 +104,6 @@ __device__ __forceinline__ void block_exclusive_scan2(uint64_t& x, uint64_t& y, 
   *tot_y = ty;
 }
 
-__device__ __forceinline__ double block_sum_double(double v, double* wave_tot) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d);
-  __syncthreads();
-  if (lane == 0) wave_tot[wave] = v;
-  __syncthreads();
-  double t = 0.0;
-  for (int w = 0; w < kWaves; ++w) t += wave_tot[w];      // same order in every thread
-  return t;
-}
-
 // Four consecutive scores from one 16-byte load.  `al` is the unit's score pointer moved back to
 // a 16-byte boundary (by `mis` floats), q the first of the four as an index from `al`; the
 // unit's scores are al[mis .. span).  A vector that is not wholly inside falls back to guarded
@@ -147,30 +137,6 @@ __global__ __launch_bounds__(kBlockThreads) void tile_sums_kernel(SelectArgs a) 
   const double t = tile_sum_sq(v, lane);
   if (lane == 0) a.tile_sq[(int64_t)h * a.tiles_total + tile_base + tile] = t;
 }
-
-// The stopping test 1 - sqrt(P / F^2) < T on fp64 masses.  Away from the boundary the cheap
-// squared form P > (1 - T)^2 F^2 decides; only within 1e-9 relative of it is the paper's form
-// (an fp64 divide and square root) evaluated, so sequential walks stay short.
-struct PredF {
-  double total;     // F^2
-  double T;
-  int min_keep;
-  double lo, hi;    // (1 - T)^2 F^2 shrunk / grown by 1e-9: below lo certainly false, above hi certainly true
-  __device__ PredF(double f2, double t, int mk) : total(f2), T(t), min_keep(mk) {
-    const double thr = t < 1.0 ? (1.0 - t) * (1.0 - t) * f2 : -1.0;     // T >= 1: any positive mass qualifies
-    lo = thr * (1.0 - 1e-9);
-    hi = thr * (1.0 + 1e-9);
-    if (t >= 1.0) { lo = -1.0; hi = -2.0; }                             // always take the exact path
-  }
-  __device__ bool operator()(int64_t count, double mass) const {
-    if (count <= 0 || count < min_keep) return false;
-    if (hi >= lo) {
-      if (mass > hi) return true;
-      if (mass < lo) return false;
-    }
-    return 1.0 - sqrt(mass / total) < T;
-  }
-};
 
 struct SelectShared {
   uint64_t (*scan)[2];    // [kWaves][2]
@@ -385,13 +351,13 @@ __device__ __forceinline__ int score_rank(const float* s, int n, double inv, flo
   return kept;
 }
 
+// Score ranking: one workgroup of 1024 threads per unit.
 __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
   __shared__ uint64_t sh_scan[kWaves][2];
   __shared__ double sh_dbl[kWaves];
   __shared__ uint32_t sh_cnt[kBuckets];
   __shared__ uint64_t sh_mass[kBuckets];
-  extern __shared__ __attribute__((aligned(16))) float sh_scores[];        // score ranking: a unit's scores
-  double* sh_incl = reinterpret_cast<double*>(sh_mass);                    // [kT], position ranking only
+  extern __shared__ __attribute__((aligned(16))) float sh_scores[];        // a unit's scores
   __shared__ int sh_i[8];
   __shared__ uint64_t sh_u64[2];
 
@@ -413,292 +379,63 @@ __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
   const double* tiles = a.tile_sq + (int64_t)h * a.tiles_total + tile_base;
   const int nt = (n + kTileKeys - 1) / kTileKeys;
   int32_t* idx_pad = a.idx_pad ? a.idx_pad + ((int64_t)s0 * a.n_kv_heads + (int64_t)h * n) : nullptr;
-  const int m_eff = min(max(a.n_sink, 0), n);
-  const bool by_score = a.rank_mode == 1;
   const bool keep_all = !(a.threshold > 0.f);              // T <= 0: no prefix short of everything qualifies
 
   int kept = n;
-  bool degenerate = false;
   double f2 = 0.0;
-
-  if (!by_score && !keep_all) {
-    // ---------------- position ranking: first the sinks [0, m), then the rest from the end backwards.
-    // Sink mass directly; tail mass per 32-position tile (from the scoring kernel), reversed.
-    double sink = 0.0;
-    if (m_eff <= 32) {                                     // the usual case (m = 4): every thread sums them itself
-      for (int p = 0; p < m_eff; ++p) sink += (double)s[p] * (double)s[p];
-    } else {
-      for (int p = tid; p < m_eff; p += kT) sink += (double)s[p] * (double)s[p];
-      sink = block_sum_double(sink, sh_dbl);
-    }
-    const int jm = m_eff / kTileKeys;                      // first tile holding a tail position
-    const int ntail = m_eff < n ? nt - jm : 0;
-    const int C = (ntail + kT - 1) / kT;                   // tail tiles per thread, in rank order
-    const int k0 = min(ntail, tid * C), k1 = min(ntail, k0 + C);
-    auto tile_mass = [&](int j) -> double {                // tail mass of tile j
-      if (j > jm || m_eff % kTileKeys == 0) return tiles[j];
-      double v = 0.0;                                      // the tile shared with the sinks
-      for (int p = min(n, (j + 1) * kTileKeys) - 1; p >= m_eff; --p) v += (double)s[p] * (double)s[p];
-      return v;
-    };
-    double mine = 0.0;
-    for (int k = k0; k < k1; ++k) mine += tile_mass(nt - 1 - k);
-    // inclusive scan over threads, fixed order
-    const int lane = tid & 63, wave = tid >> 6;
-    double inc = mine;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const double o = __shfl_up(inc, d);
-      if (lane >= d) inc += o;
-    }
-    __syncthreads();
-    if (lane == 63) sh_dbl[wave] = inc;
-    __syncthreads();
-    double wave_off = 0.0;
-    for (int w = 0; w < wave; ++w) wave_off += sh_dbl[w];
-    double tail_total = 0.0;
-    for (int w = 0; w < kWaves; ++w) tail_total += sh_dbl[w];
-    inc += wave_off;
-    sh_incl[tid] = inc;
-    f2 = sink + tail_total;
-    degenerate = !(f2 > 0.0) || !(f2 < 1e300);
-    if (tid == 0) {
-      sh_i[0] = n;          // result: no crossing keeps everything
-      sh_i[3] = kT;         // first thread whose chunk end satisfies the rule
-    }
-    __syncthreads();
-    if (!degenerate) {
-      const PredF pred(f2, (double)a.threshold, a.min_keep);
-      // ranks covered up to and including tail-rank tile k: sinks + positions from the end down to tile start
-      auto count_through = [&](int k) -> int { return m_eff + n - max((nt - 1 - k) * kTileKeys, m_eff); };
-      // Search one run of consecutive ranks with a wavefront: lane l takes the l-th rank of the
-      // run (position first + l * step), an inclusive fp64 prefix over lanes gives the mass through
-      // each rank, and the first lane whose prefix satisfies the rule is the cut.
-      auto wave_search = [&](int first, int step, int len, int ranks_before, double mass_before, int fallback) {
-        const int p = first + lane * step;
-        double v = 0.0;
-        if (lane < len) v = (double)s[p] * (double)s[p];
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-          const double o = __shfl_up(v, d);
-          if (lane >= d) v += o;
-        }
-        const bool ok = lane < len && pred(ranks_before + lane + 1, mass_before + v);
-        const unsigned long long mask = __ballot(ok);
-        if (lane == 0) sh_i[0] = mask ? ranks_before + __ffsll((long long)mask) : fallback;
-      };
-      if (pred(m_eff, sink)) {
-        // the cut falls inside the sinks
-        if (m_eff <= 64) {
-          if (wave == 0) wave_search(0, 1, m_eff, 0, 0.0, m_eff);
-        } else if (tid == 0) {
-          double run = 0.0;
-          int res = m_eff;
-          for (int p = 0; p < m_eff; ++p) {
-            run += (double)s[p] * (double)s[p];
-            if (pred(p + 1, run)) {
-              res = p + 1;
-              break;
-            }
-          }
-          sh_i[0] = res;
-        }
-      } else {
-        if (k1 > k0 && pred(count_through(k1 - 1), sink + inc)) atomicMin(&sh_i[3], tid);
-        __syncthreads();
-        if (sh_i[3] == tid) {
-          // the tile of this thread's chunk in which the rule is first met (the last one if rounding hides it)
-          double run = sink + (tid > 0 ? sh_incl[tid - 1] : 0.0);
-          int jstar = nt - k1;
-          for (int k = k0; k + 1 < k1; ++k) {
-            const double tm = tile_mass(nt - 1 - k);
-            if (pred(count_through(k), run + tm)) {
-              jstar = nt - 1 - k;
-              break;
-            }
-            run += tm;
-          }
-          sh_i[4] = jstar;
-          sh_dbl[0] = run;
-        }
-        __syncthreads();
-        if (sh_i[3] < kT && wave == 0) {
-          const int jt = sh_i[4];
-          const int hi_p = min(n, (jt + 1) * kTileKeys) - 1, lo_p = max(jt * kTileKeys, m_eff);
-          wave_search(hi_p, -1, hi_p - lo_p + 1, m_eff + (n - 1 - hi_p), sh_dbl[0], m_eff + (n - lo_p));
-        }
-      }
-    }
-    __syncthreads();
-    kept = degenerate ? n : sh_i[0];
-  } else if (by_score && !keep_all) {
+  if (!keep_all) {
     for (int j = tid; j < nt; j += kT) f2 += tiles[j];
-    f2 = block_sum_double(f2, sh_dbl);
-    degenerate = !(f2 > 0.0) || !(f2 < 1e300);
+    f2 = block_sum_double<kT>(f2, sh_dbl);
   }
-  const double inv = (degenerate || keep_all || !by_score) ? 0.0 : 1152921504606846976.0 / f2;      // 2^60 / F^2
-
-  if (by_score && (degenerate || keep_all)) {
+  const bool degenerate = !(f2 > 0.0) || !(f2 < 1e300);
+  if (degenerate || keep_all) {
     if (idx_pad)
       for (int i = tid; i < n; i += kT) idx_pad[i] = i;
-  } else if (by_score) {
-    // ---------------- score ranking: radix select of the cut value
+  } else {
+    // radix select of the cut value; masses are integers in units of F^2 / 2^60
     SelectShared sh{sh_scan, sh_cnt, sh_mass, sh_i, sh_u64};
-    kept = score_rank(s, n, inv, a.threshold, a.min_keep, idx_pad, sh_scores, a.lds_floats, sh);
+    kept = score_rank(s, n, 1152921504606846976.0 / f2, a.threshold, a.min_keep, idx_pad, sh_scores, a.lds_floats, sh);
   }
-
   if (tid == 0) {
     a.kept[unit] = kept;
-    a.desc[unit] = make_int4(kept, by_score ? 0 : min(kept, m_eff), 0, 0);
+    a.desc[unit] = make_int4(kept, 0, 0, 0);
   }
 }
 
-// Position ranking with one cut per (layer, sequence): the norm of Eq. 1 runs over the reduced
-// attention matrix of all KV heads of the layer (Fig. 1: eviction "per layer"; Sec. 3.3: "the
-// stopping positions of all layers"), every head keeps the same positions.  One workgroup per
-// sequence; the same search as the per-head position path of select_kernel with every mass
-// replaced by its sum over the heads (heads added in index order, fp64).
-__global__ __launch_bounds__(kT) void select_layer_kernel(SelectArgs a) {
-  __shared__ double sh_dbl[kWaves];
-  __shared__ double sh_incl[kT];
-  __shared__ int sh_i[8];
-  const int b = blockIdx.x;
+// Position ranking, one cut per unit (sequence, KV head) or, with a.per_layer, one cut per (layer,
+// sequence): the norm of Eq. 1 then runs over the reduced attention matrix of all KV heads of the
+// layer (Fig. 1: eviction "per layer"; Sec. 3.3: "the stopping positions of all layers") and every
+// head keeps the same positions.  One workgroup per unit / per sequence.
+__global__ __launch_bounds__(kPosThreads) void select_position_kernel(SelectArgs a) {
+  __shared__ PositionShared<kPosThreads> sh;
   const int H = a.n_kv_heads;
+  const int b = a.per_layer ? blockIdx.x : blockIdx.x / H;
+  const int h = a.per_layer ? 0 : blockIdx.x - b * H;
   int tile_base = 0;
   for (int bb = 0; bb < b; ++bb) tile_base += (a.cu[bb + 1] - a.cu[bb] + kTileKeys - 1) / kTileKeys;
   const int s0 = a.cu[b];
   const int n = a.cu[b + 1] - s0;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  auto publish = [&](int kept, int sinks) {
-    for (int h = tid; h < H; h += kT) {
-      a.kept[b * H + h] = kept;
-      a.desc[b * H + h] = make_int4(kept, sinks, 0, 0);
-    }
-  };
-  if (n == 0) {
-    publish(0, 0);
-    return;
-  }
-  const float* s = a.scores + s0;                          // head h: s + h * total_tokens
-  const double* tiles = a.tile_sq + tile_base;             // head h: tiles + h * tiles_total
-  const int nt = (n + kTileKeys - 1) / kTileKeys;
   const int m_eff = min(max(a.n_sink, 0), n);
-  if (!(a.threshold > 0.f)) {                              // T <= 0: no prefix short of everything qualifies
-    publish(n, m_eff);
-    return;
+  const float* s = a.scores + (int64_t)h * a.total_tokens + s0;
+  const double* tiles = a.tile_sq + (int64_t)h * a.tiles_total + tile_base;
+  int kept = 0;
+  if (n > 0) {
+    if (a.per_layer)
+      kept = position_cut<kPosThreads>(LayerMass{s, tiles, a.total_tokens, a.tiles_total, H}, n, m_eff, a.threshold,
+                                       a.min_keep, &sh);
+    else
+      kept = position_cut<kPosThreads>(HeadMass{s, tiles}, n, m_eff, a.threshold, a.min_keep, &sh);
   }
-  auto pos_mass = [&](int p) -> double {                   // squared scores of position p, all heads
-    double v = 0.0;
-    for (int h = 0; h < H; ++h) {
-      const double x = (double)s[(int64_t)h * a.total_tokens + p];
-      v += x * x;
+  const int4 d = make_int4(kept, min(kept, m_eff), 0, 0);
+  if (a.per_layer) {
+    for (int hh = threadIdx.x; hh < H; hh += kPosThreads) {
+      a.kept[b * H + hh] = kept;
+      a.desc[b * H + hh] = d;
     }
-    return v;
-  };
-  double sink = 0.0;
-  if (m_eff <= 32) {
-    for (int p = 0; p < m_eff; ++p) sink += pos_mass(p);
-  } else {
-    for (int p = tid; p < m_eff; p += kT) sink += pos_mass(p);
-    sink = block_sum_double(sink, sh_dbl);
-    __syncthreads();
+  } else if (threadIdx.x == 0) {
+    a.kept[blockIdx.x] = kept;
+    a.desc[blockIdx.x] = d;
   }
-  const int jm = m_eff / kTileKeys;                        // first tile holding a tail position
-  const int ntail = m_eff < n ? nt - jm : 0;
-  const int C = (ntail + kT - 1) / kT;                     // tail tiles per thread, in rank order
-  const int k0 = min(ntail, tid * C), k1 = min(ntail, k0 + C);
-  auto tile_mass = [&](int j) -> double {                  // tail mass of tile j, all heads
-    double v = 0.0;
-    if (j > jm || m_eff % kTileKeys == 0) {
-      for (int h = 0; h < H; ++h) v += tiles[(int64_t)h * a.tiles_total + j];
-    } else {                                               // the tile shared with the sinks
-      for (int p = min(n, (j + 1) * kTileKeys) - 1; p >= m_eff; --p) v += pos_mass(p);
-    }
-    return v;
-  };
-  double mine = 0.0;
-  for (int k = k0; k < k1; ++k) mine += tile_mass(nt - 1 - k);
-  double inc = mine;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const double o = __shfl_up(inc, d);
-    if (lane >= d) inc += o;
-  }
-  __syncthreads();
-  if (lane == 63) sh_dbl[wave] = inc;
-  __syncthreads();
-  double wave_off = 0.0, tail_total = 0.0;
-  for (int w = 0; w < kWaves; ++w) {
-    if (w < wave) wave_off += sh_dbl[w];
-    tail_total += sh_dbl[w];
-  }
-  inc += wave_off;
-  sh_incl[tid] = inc;
-  const double f2 = sink + tail_total;
-  const bool degenerate = !(f2 > 0.0) || !(f2 < 1e300);
-  if (tid == 0) {
-    sh_i[0] = n;
-    sh_i[3] = kT;
-  }
-  __syncthreads();
-  if (!degenerate) {
-    const PredF pred(f2, (double)a.threshold, a.min_keep);
-    auto count_through = [&](int k) -> int { return m_eff + n - max((nt - 1 - k) * kTileKeys, m_eff); };
-    auto wave_search = [&](int first, int step, int len, int ranks_before, double mass_before, int fallback) {
-      const int p = first + lane * step;
-      double v = lane < len ? pos_mass(p) : 0.0;
-#pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
-        const double o = __shfl_up(v, d);
-        if (lane >= d) v += o;
-      }
-      const bool ok = lane < len && pred(ranks_before + lane + 1, mass_before + v);
-      const unsigned long long mask = __ballot(ok);
-      if (lane == 0) sh_i[0] = mask ? ranks_before + __ffsll((long long)mask) : fallback;
-    };
-    if (pred(m_eff, sink)) {
-      if (m_eff <= 64) {
-        if (wave == 0) wave_search(0, 1, m_eff, 0, 0.0, m_eff);
-      } else if (tid == 0) {
-        double run = 0.0;
-        int res = m_eff;
-        for (int p = 0; p < m_eff; ++p) {
-          run += pos_mass(p);
-          if (pred(p + 1, run)) {
-            res = p + 1;
-            break;
-          }
-        }
-        sh_i[0] = res;
-      }
-    } else {
-      if (k1 > k0 && pred(count_through(k1 - 1), sink + inc)) atomicMin(&sh_i[3], tid);
-      __syncthreads();
-      if (sh_i[3] == tid) {
-        double run = sink + (tid > 0 ? sh_incl[tid - 1] : 0.0);
-        int jstar = nt - k1;
-        for (int k = k0; k + 1 < k1; ++k) {
-          const double tm = tile_mass(nt - 1 - k);
-          if (pred(count_through(k), run + tm)) {
-            jstar = nt - 1 - k;
-            break;
-          }
-          run += tm;
-        }
-        sh_i[4] = jstar;
-        sh_dbl[0] = run;
-      }
-      __syncthreads();
-      if (sh_i[3] < kT && wave == 0) {
-        const int jt = sh_i[4];
-        const int hi_p = min(n, (jt + 1) * kTileKeys) - 1, lo_p = max(jt * kTileKeys, m_eff);
-        wave_search(hi_p, -1, hi_p - lo_p + 1, m_eff + (n - 1 - hi_p), sh_dbl[0], m_eff + (n - lo_p));
-      }
-    }
-  }
-  __syncthreads();
-  const int kept = degenerate ? n : sh_i[0];
-  publish(kept, min(kept, m_eff));
 }
 
 }  // namespace
@@ -713,8 +450,8 @@ hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t str
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  if (a.per_layer) {                               // one cut per sequence over all heads (position ranking)
-    hipLaunchKernelGGL(select_layer_kernel, dim3(g.batch), dim3(kT), 0, stream, a);
+  if (a.rank_mode == 0) {                          // position ranking: one cut per unit, or per sequence over all heads
+    hipLaunchKernelGGL(select_position_kernel, dim3(a.per_layer ? g.batch : g.units), dim3(kPosThreads), 0, stream, a);
     return hipGetLastError();
   }
   // Score ranking keeps a unit's scores in LDS when the longest sequence fits (with up to three

@@ -86,6 +86,29 @@ class DeviceLayer:
                     k_out=to_host_bits(b.k_out[:total], self.dtype), v_out=to_host_bits(b.v_out[:total], self.dtype))
 
 
+class LayerSet:
+    """Several layers of one prefilled batch (same shapes, strides and sequence lengths, each with its own
+    buffers) and the scratch of one rfkv_compress_layers call over all of them."""
+
+    def __init__(self, dls):
+        import torch
+        self.dls = list(dls)
+        d0 = self.dls[0]
+        assert all(np.array_equal(d.cu_host, d0.cu_host) for d in self.dls)
+        self.ws_bytes = B.rfkv_layers_workspace_bytes(d0.params, len(self.dls), d0.N, d0.max_len)
+        self.ws = torch.empty(max(256, self.ws_bytes), dtype=torch.uint8, device="cuda")
+
+    def compress(self, stream=None, with_scores=True, with_idx=True):
+        d0 = self.dls[0]
+        bufs = [d.buf for d in self.dls]
+        return B.rfkv_compress_layers(d0.params, [d.q for d in self.dls], [d.k for d in self.dls],
+                                      [d.v for d in self.dls], d0.cu_host, d0.cu_dev,
+                                      [b.scores for b in bufs] if with_scores else None, [b.kept for b in bufs],
+                                      [b.out_offsets for b in bufs], [b.idx for b in bufs] if with_idx else None,
+                                      [b.k_out for b in bufs], [b.v_out for b in bufs], bufs[0].capacity_rows,
+                                      self.ws, self.ws_bytes, stream)
+
+
 def compress_model(layers, n_frozen: int = 2, stream=None) -> None:
     """Alg. 1's loop over the layers of a prefilled model with Sec. 3.3 "Retaining Bottom Layers":
     the first `n_frozen` layers keep their whole cache, every other layer is compressed.  `layers`:

@@ -7,7 +7,7 @@ import numpy as np
 from oracle import refreekv_oracle as O
 from paper_2502_16886_amd import binding as B
 from paper_2502_16886_amd import workloads as W
-from paper_2502_16886_amd.device import DeviceLayer, compress_model, threshold_as_float32, to_device, to_host_bits, unit_slices  # noqa: F401
+from paper_2502_16886_amd.device import DeviceLayer, LayerSet, compress_model, threshold_as_float32, to_device, to_host_bits, unit_slices  # noqa: F401
 
 # Relative error allowed on a score (bf16 or fp32 inputs, fp32 accumulation); scores below
 # `SCORE_ATOL` (far under anything that can influence a cut) are compared absolutely.

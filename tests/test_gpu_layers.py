@@ -1,0 +1,151 @@
+"""GPU parity of rfkv_compress_layers (all layers of a prefilled batch in one call; with the position
+ranking the layers' scoring passes and compactions run side by side, one launch per layer) against the
+float64 oracle, layer by layer, and against the per-layer entry point."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import rfkv_harness as H                                   # noqa: E402
+from oracle import refreekv_oracle as O                    # noqa: E402
+from paper_2502_16886_amd import binding as B              # noqa: E402
+from paper_2502_16886_amd import workloads as W            # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+
+def _poison(dl):
+    b = dl.buf
+    b.scores.fill_(float("nan"))
+    b.kept.fill_(-7)
+    b.out_offsets.fill_(-7)
+    b.idx.fill_(-7)
+    b.k_out.fill_(1.0)
+    b.v_out.fill_(1.0)
+
+
+def _run(cfg, lens, n_layers, mode=B.RANK_POSITION, kv_layout="token_major", seed=1, **kw):
+    host = [W.make_layer(seed, li, cfg=cfg, lengths=lens) for li in range(n_layers)]
+    dls = [H.DeviceLayer(l, rank_mode=mode, kv_layout=kv_layout, **kw) for l in host]
+    for dl in dls:
+        _poison(dl)
+    ls = H.LayerSet(dls)
+    ls.compress()
+    return host, dls, [dl.results() for dl in dls]
+
+
+@pytest.mark.parametrize("Hq,Hkv,d,w,dtype,lens,n_layers,kv_layout", [
+    (8, 2, 128, 32, "bf16", [777], 3, "token_major"),
+    (32, 8, 128, 32, "bf16", [1500, 333, 0, 40], 4, "head_major"),      # ragged, an empty sequence, 32 units
+    (8, 8, 64, 16, "bf16", [300, 1, 45, 1029], 2, "token_major"),       # G = 1, d = 64, a length-1 sequence
+    (8, 2, 64, 32, "fp32", [640, 33], 3, "token_major"),                # fp32
+    (8, 2, 128, 24, "bf16", [5000, 20], 5, "head_major"),               # 96 rows; several spans per unit
+    (4, 1, 128, 5, "bf16", [3, 2, 4, 70], 2, "token_major"),            # n <= m
+])
+def test_layers_small_shapes(Hq, Hkv, d, w, dtype, lens, n_layers, kv_layout):
+    cfg = W.Config("t", n_layers, Hq, Hkv, d, w, dtype, batch=len(lens), context=max(lens))
+    host, dls, got = _run(cfg, lens, n_layers, kv_layout=kv_layout)
+    for layer, g in zip(host, got):
+        rep = H.compare_layer(layer, g, B.RANK_POSITION)
+        assert rep["exact"] >= rep["units"] - 1
+    # the per-layer entry point on the same inputs: the same retained sets and rows (its scores may differ in
+    # the last place: the rows' normalisers are folded from different spans)
+    for dl, g in zip(dls, got):
+        _poison(dl)
+        dl.compress()
+        one = dl.results()
+        assert np.array_equal(one["kept"], g["kept"]) and np.array_equal(one["idx"], g["idx"])
+        assert np.array_equal(one["k_out"], g["k_out"]) and np.array_equal(one["v_out"], g["v_out"])
+        np.testing.assert_allclose(one["scores"], g["scores"], rtol=2e-6, atol=1e-30)
+
+
+@pytest.mark.parametrize("what", ["score_ranking", "per_layer_cut", "k1", "wide", "threshold0", "one_layer", "padded"])
+def test_layers_problems_that_run_layer_after_layer(what):
+    """Everything the pipeline does not cover takes the per-layer path inside the same call and must
+    give exactly the per-layer entry point's result."""
+    kw, mode, w, n_layers, Hq, Hkv = {}, B.RANK_POSITION, 32, 3, 8, 2
+    if what == "score_ranking":
+        mode = B.RANK_SCORE
+    elif what == "per_layer_cut":
+        kw["granularity"] = B.PER_LAYER
+    elif what == "k1":
+        w = 1
+    elif what == "wide":
+        Hq, Hkv = 28, 4
+    elif what == "threshold0":
+        kw["threshold"] = 0.0
+    elif what == "one_layer":
+        n_layers = 1
+    elif what == "padded":
+        kw["out_pad_rows"] = 1024
+    lens = [900, 130]
+    cfg = W.Config("t", n_layers, Hq, Hkv, 128, w, "bf16", batch=len(lens), context=max(lens))
+    host, dls, got = _run(cfg, lens, n_layers, mode=mode, **kw)
+    for dl, g in zip(dls, got):
+        _poison(dl)
+        dl.compress()
+        one = dl.results()
+        for key in ("scores", "kept", "out_offsets", "idx"):
+            assert np.array_equal(one[key], g[key]), (what, key)
+        if what != "padded":
+            assert np.array_equal(one["k_out"], g["k_out"]) and np.array_equal(one["v_out"], g["v_out"])
+
+
+def test_layers_repeat_runs_are_bit_identical_and_capacity_is_respected():
+    import torch
+    cfg = W.Config("t", 4, 32, 8, 128, 32, "bf16", batch=1, context=3000)
+    host, dls, first = _run(cfg, [3000], 4, kv_layout="head_major")
+    ls = H.LayerSet(dls)
+    for dl in dls:
+        _poison(dl)
+    ls.compress()
+    again = [dl.results() for dl in dls]
+    for a, b in zip(first, again):
+        for key in a:
+            assert np.array_equal(a[key], b[key]), key
+    # too small an output: rows past the capacity are not written, the offsets still tell the need
+    total = int(first[0]["out_offsets"][-1])
+    cap = total // 2
+    for dl in dls:
+        dl.buf.k_out.fill_(7.0)
+        dl.buf.capacity_rows = cap
+    ls.compress(with_idx=False)
+    torch.cuda.synchronize()
+    assert int(dls[0].buf.out_offsets[-1]) == total
+    assert np.array_equal(H.to_host_bits(dls[0].buf.k_out[:cap], "bf16"), first[0]["k_out"][:cap])
+    assert torch.all(dls[0].buf.k_out[cap:total].float() == 7.0)
+
+
+def test_layers_host_checks():
+    import torch
+    t = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    cu = np.array([0, 100], np.int32)
+    p = B.make_params(1, 8, 2, 128, 16, "bf16")
+    need = B.rfkv_layers_workspace_bytes(p, 3, 100, 100)
+    assert need > 3 * B.rfkv_workspace_bytes(p, 100, 100) - 1024
+    lst = [t, t, t]
+    st = B.rfkv_compress_layers(p, lst, lst, lst, cu, t, None, lst, lst, None, lst, lst, 200, t, 16, check=False)
+    assert st == B.RFKV_WORKSPACE_TOO_SMALL
+    st = B.rfkv_compress_layers(p, lst, lst, [t, None, t], cu, t, None, lst, lst, None, lst, lst, 200, t, 1 << 16,
+                                check=False)
+    assert st == B.RFKV_INVALID_ARG
+
+
+@pytest.mark.timeout(900)
+def test_layers_headline_geometry_in_full():
+    """The geometry the benchmark times: 30 layers of the 32768-token Llama3-8B-shaped layer (the paper
+    keeps the first two of 32 whole) in one call, head-major caches, every layer against the oracle."""
+    n_layers = 30
+    host = [W.make_layer("H", 2 + li) for li in range(n_layers)]
+    dls = [H.DeviceLayer(l, kv_layout="head_major") for l in host]
+    H.LayerSet(dls).compress()
+    exact = units = 0
+    for li, (layer, dl) in enumerate(zip(host, dls)):
+        rep = H.compare_layer(layer, dl.results(), B.RANK_POSITION)
+        print(f"\n  layer {2 + li}: {rep}", flush=True)
+        assert rep["exact"] >= rep["units"] - 1
+        exact += rep["exact"]
+        units += rep["units"]
+    assert exact >= units - 2
