@@ -8,8 +8,15 @@ d = 128, bf16), one 32768-token sequence, observation window 32, T = 1 %, m = 4,
 its inputs in the 256 MB Infinity Cache left there by the previous one.  Inputs are synthetic
 (paper_2502_16886_amd.workloads) and resident in HBM before timing starts.
 
-Prints one JSON line: throughput, the dominant kernel's roofline figures, the CPU oracle timed
-on the same workload, and the score-ranking and single-stream variants.
+Timing: the steps are captured into one HIP graph over all layer buffers (forked over a few streams,
+layers are independent) and the graph is replayed at least five times; every replay is bracketed by
+HIP events, `ms_per_step` is the median replay divided by the steps in it, and the spread is
+reported.  `--steps K` asks for K steps; the run rounds up to whole replays and says what it ran.
+
+Prints one JSON line: throughput, the roofline figures of the whole pass and of its dominant kernel,
+the CPU oracle timed on the same workload, and legs for the score ranking, a single stream, the
+prefill's log-sum-exp hand-over, all layers in one call, the other workload configurations, the
+decode attention over the compacted cache and the ablation's wide window.
 """
 from __future__ import annotations
 
@@ -23,6 +30,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+MIN_REPLAYS = 5
 
 
 def algorithmic_bytes(N, Hkv, d, e, Hq, wrows, kept_rows, units, score_mode):
@@ -65,8 +73,88 @@ def read_traffic(kernel, workload):
                 pass
     if "fetch_bytes_per_launch" in vals and "write_bytes_per_launch" in vals:
         return {"fetch_bytes": int(vals["fetch_bytes_per_launch"]), "write_bytes": int(vals["write_bytes_per_launch"]),
-                "total_bytes": int(vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"])}
+                "total_bytes": int(vals["fetch_bytes_per_launch"] + vals["write_bytes_per_launch"]),
+                "source": os.path.relpath(path, ROOT)}
     return None
+
+
+class Stepper:
+    """`layers` device buffers of one workload and the means to run steps over them: eagerly, on one
+    or several streams, or as replays of one HIP graph that holds one step per buffer."""
+
+    def __init__(self, torch, objs, streams):
+        self.torch = torch
+        self.objs = objs                                   # things with .compress(stream)
+        self.side = [torch.cuda.Stream() for _ in range(streams)] if streams > 1 else []
+
+    def run_steps(self, count, start=0):
+        torch, n = self.torch, len(self.objs)
+        if not self.side:
+            for i in range(count):
+                self.objs[(start + i) % n].compress(None)          # torch's current stream
+            return
+        # layer j always uses stream j % S, hence two uses of one layer's buffers stay ordered
+        cur = torch.cuda.current_stream()
+        for st in self.side:
+            st.wait_stream(cur)
+        for i in range(count):
+            j = (start + i) % n
+            with torch.cuda.stream(self.side[j % len(self.side)]):
+                self.objs[j].compress(None)
+        for st in self.side:
+            cur.wait_stream(st)
+
+    def timed(self, steps, warmup, graph=True, min_replays=MIN_REPLAYS):
+        """Per-step milliseconds: median, min and max over replays, steps run, replays, wall ms per step."""
+        import numpy as np
+        torch, n = self.torch, len(self.objs)
+        self.run_steps(max(warmup, 1))
+        torch.cuda.synchronize()
+        g = None
+        if graph:
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=None):
+                self.run_steps(n)
+            torch.cuda.synchronize()
+        replays = max(min_replays, (steps + n - 1) // n)
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(replays + 1)]
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        marks[0].record()
+        for r in range(replays):
+            if g is not None:
+                g.replay()
+            else:
+                self.run_steps(n)
+            marks[r + 1].record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t) * 1e3 / (replays * n)
+        per = np.array([marks[r].elapsed_time(marks[r + 1]) for r in range(replays)]) / n
+        return dict(ms=float(np.median(per)), ms_min=float(per.min()), ms_max=float(per.max()), steps=replays * n,
+                    replays=replays, wall_ms=wall)
+
+
+def kernel_times(np, B, dls, reps):
+    """Per-kernel durations from HIP events recorded on the launch stream between the kernels
+    (rfkv_compress_layer_timed; serial, one call at a time)."""
+    kms = np.zeros(len(B.KERNEL_NAMES))
+    for i in range(reps):
+        dl = dls[i % len(dls)]
+        b = dl.buf
+        _, ms = B.rfkv_compress_layer_timed(dl.params, dl.q, dl.k, dl.v, dl.cu_host, dl.cu_dev, b.scores, b.kept,
+                                            b.out_offsets, b.idx, b.k_out, b.v_out, b.capacity_rows, b.ws, b.ws_bytes,
+                                            None)
+        kms += np.array(ms)
+    return dict(zip(B.KERNEL_NAMES, (kms / reps).tolist()))
+
+
+def with_score_mode(H, B, dl):
+    """The same inputs and output buffers as `dl`, ranked by score."""
+    d2 = H.DeviceLayer.__new__(H.DeviceLayer)
+    d2.__dict__.update(dl.__dict__)
+    d2.params = B.RfkvParams.from_buffer_copy(dl.params)
+    d2.params.rank_mode = B.RANK_SCORE
+    return d2
 
 
 def time_decode_attention(torch, np, H, B, W, cfg_id=4, n_new=64, reps=20):
@@ -108,11 +196,13 @@ def time_decode_attention(torch, np, H, B, W, cfg_id=4, n_new=64, reps=20):
     t_m = timed(lambda: B.rfkv_masked_attention(dl.params, q, n_new, dl.k, dl.v, dl.cu_host, dl.cu_dev, mask, out, ws,
                                                 ws_bytes))
     flop_per_key = 4 * n_new * (cfg.n_q_heads // Hkv) * d          # QK^T and PV, multiply-add = 2
+    tf = flop_per_key * kept_rows / (t_c * 1e-3) / 1e12
     return {"workload": f"{cfg.name}: {N} tokens, {n_new} new queries, position ranking, T={cfg.threshold}",
             "retained_fraction": round(kept_rows / (N * Hkv), 4),
             "compacted_ms": round(t_c, 5), "masked_full_ms": round(t_m, 5), "speedup": round(t_m / t_c, 3),
             "compacted_kv_GBps": round(2 * kept_rows * d * 2 / (t_c * 1e-3) / 1e9, 1),
-            "compacted_mfma_TFLOPs": round(flop_per_key * kept_rows / (t_c * 1e-3) / 1e12, 1),
+            "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                         "frac": round(tf / 2500.0, 4), "traffic": None},
             "masked_mfma_TFLOPs": round(flop_per_key * N * Hkv / (t_m * 1e-3) / 1e12, 1)}
 
 
@@ -124,23 +214,16 @@ def time_wide_window(np, H, B, W, window=328, reps=12):
                    base.dtype, batch=1, context=base.context)
     layer = W.make_layer("H", 0, cfg=cfg)
     dl = H.DeviceLayer(layer, kv_layout="head_major")
-    b = dl.buf
-    kms = np.zeros(len(B.KERNEL_NAMES))
-    for i in range(reps + 2):
-        _, ms = B.rfkv_compress_layer_timed(dl.params, dl.q, dl.k, dl.v, dl.cu_host, dl.cu_dev, b.scores, b.kept,
-                                            b.out_offsets, b.idx, b.k_out, b.v_out, b.capacity_rows, b.ws, b.ws_bytes,
-                                            None)
-        if i >= 2:
-            kms += np.array(ms)
-    kms /= reps
+    for _ in range(2):
+        dl.compress()
+    k = kernel_times(np, B, [dl], reps)
     n, G, d, Hkv = cfg.context, cfg.n_q_heads // cfg.n_kv_heads, cfg.head_dim, cfg.n_kv_heads
     # logits a pass has to form: row t of the window sees n - w + t + 1 keys
     visible = sum(n - window + t + 1 for t in range(window)) * G * Hkv
     flop = 2.0 * visible * d
-    k = dict(zip(B.KERNEL_NAMES, kms.tolist()))
     peak = 2500.0
     return {"workload": f"{cfg.name}: {n} tokens, window {window} ({window * G} score rows per KV head), position ranking",
-            "ms_per_step": round(float(kms.sum()), 5), "kernel_ms": {a: round(v, 5) for a, v in k.items()},
+            "ms_per_step": round(float(sum(k.values())), 5), "kernel_ms": {a: round(v, 5) for a, v in k.items()},
             "flop_per_pass": flop,
             "roofline": {"bound": "mfma", "kernel": "score_reduce", "achieved": round(flop / (k["score_reduce"] * 1e-3) / 1e12, 1),
                          "peak": peak, "unit": "TFLOP/s",
@@ -148,56 +231,87 @@ def time_wide_window(np, H, B, W, window=328, reps=12):
             "stats_TFLOPs": round(flop / (k["score_stats"] * 1e-3) / 1e12, 1)}
 
 
-def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, reps=6, lse_per_layer=None):
-    """The post-prefill pass over the whole model in ONE call: the caches of `n_layers` layers (the
-    paper keeps the first two layers whole, Sec. 3.3 "Retaining Bottom Layers", so 30 of 32) laid out
-    [layer, token, head, d] are a batch of `n_layers` sequences to the library, one launch of every
-    kernel instead of one per layer.  The generated layer buffers repeat to fill the 30.  With
-    `lse_per_layer` (the window rows' log-sum-exp of every generated layer) the same call is also timed
-    through rfkv_compress_layer_lse."""
-    if len({len(l.cu_seqlens) for l in host_layers}) != 1 or len(host_layers[0].cu_seqlens) != 2:
+def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, replays=MIN_REPLAYS):
+    """The post-prefill pass over the whole model in ONE rfkv_compress_layers call on one stream:
+    `n_layers` layers (the paper keeps the first two of 32 whole, Sec. 3.3 "Retaining Bottom Layers"),
+    each with its own cache and outputs; the library runs the layers' passes side by side.  The
+    generated layers repeat to fill the 30."""
+    if len(host_layers[0].cu_seqlens) < 2:
         return None
-    pick = [host_layers[i % len(host_layers)] for i in range(n_layers)]
-    n = int(pick[0].cu_seqlens[-1])
-    merged = W.Layer(W.Config(f"{cfg.name}-x{n_layers}", cfg.layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
-                              cfg.window, cfg.dtype, batch=n_layers, context=n, threshold=cfg.threshold,
-                              n_sink=cfg.n_sink),
-                     np.concatenate([l.q_win for l in pick]), np.concatenate([l.k for l in pick]),
-                     np.concatenate([l.v for l in pick]), (np.arange(n_layers + 1) * n).astype(np.int32))
-    dl = H.DeviceLayer(merged, kv_layout="token_major")
+    dls = [H.DeviceLayer(host_layers[i % len(host_layers)], kv_layout="head_major") for i in range(n_layers)]
+    ls = H.LayerSet(dls)
     for _ in range(2):
-        dl.compress(None)
+        ls.compress(with_scores=False, with_idx=False)
     torch.cuda.synchronize()
-    def timed(lse):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        dl.compress(None, lse_win=lse)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(reps):
-            dl.compress(None, lse_win=lse)
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-    ms = timed(None)
-    kept = int(dl.buf.out_offsets[-1])
-    ms_lse = None
-    if lse_per_layer is not None:
-        ms_lse = timed(torch.cat([lse_per_layer[i % len(host_layers)] for i in range(n_layers)]).contiguous())
-        assert int(dl.buf.out_offsets[-1]) > 0
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(replays + 1)]
+    marks[0].record()
+    for r in range(replays):
+        ls.compress(with_scores=False, with_idx=False)
+        marks[r + 1].record()
+    torch.cuda.synchronize()
+    per = np.array([marks[r].elapsed_time(marks[r + 1]) for r in range(replays)])
+    ms = float(np.median(per))
+    kept = float(np.mean([int(d.buf.out_offsets[-1]) for d in dls]))
+    n = dls[0].N
     e = 2 if cfg.dtype == "bf16" else 4
-    wrows = n_layers * min(cfg.window, n)
-    alg = algorithmic_bytes(n_layers * n, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows, kept,
-                            n_layers * cfg.n_kv_heads, False)
-    del dl
+    wrows = int(np.minimum(cfg.window, np.diff(host_layers[0].cu_seqlens)).sum())
+    alg = algorithmic_bytes(n, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows, kept, dls[0].batch * cfg.n_kv_heads, False)
+    del ls, dls
     torch.cuda.empty_cache()
-    return {"layers_per_call": n_layers, "retained_fraction": round(kept / (n_layers * n * cfg.n_kv_heads), 4),
+    return {"entry_point": "rfkv_compress_layers", "layers_per_call": n_layers, "streams": 1,
+            "retained_fraction": round(kept / (n * cfg.n_kv_heads), 4),
             "ms_per_call": round(ms, 4), "ms_per_layer": round(ms / n_layers, 5),
+            "ms_per_layer_min_max": [round(float(per.min()) / n_layers, 5), round(float(per.max()) / n_layers, 5)],
             "tokens_per_s_per_layer_pass": round(n / (ms / n_layers * 1e-3), 1),
-            "pipeline_frac": round(alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "with_prefill_lse": None if ms_lse is None else {
-                "ms_per_layer": round(ms_lse / n_layers, 5),
-                "tokens_per_s_per_layer_pass": round(n / (ms_lse / n_layers * 1e-3), 1),
-                "pipeline_frac": round((alg + 4 * wrows * cfg.n_q_heads) / (ms_lse * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}}
+            "frac": round(alg / (ms / n_layers * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
+def time_config(torch, np, H, B, W, cfg_id, streams, buffers=8, gen=2):
+    """One of the other workload configurations, a few replays: position and score ranking."""
+    cfg = W.CONFIGS[cfg_id]
+    host = [W.make_layer(cfg_id, li) for li in range(gen)]
+    dls = [H.DeviceLayer(host[i % gen], kv_layout="head_major") for i in range(buffers)]
+    N = dls[0].N
+    e = 2 if cfg.dtype == "bf16" else 4
+    wrows = int(np.minimum(cfg.window, np.diff(host[0].cu_seqlens)).sum())
+    units = dls[0].batch * cfg.n_kv_heads
+    out = {"workload": f"{cfg.name}: {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, d={cfg.head_dim}, batch {dls[0].batch}, "
+                       f"{N} tokens, window {cfg.window}, {cfg.dtype}", "tokens": N}
+    for name, objs, score_mode in (("position", dls, False), ("score", [with_score_mode(H, B, d) for d in dls], True)):
+        r = Stepper(torch, objs, streams).timed(buffers, 2)
+        kept = float(np.mean([int(d.buf.out_offsets[-1]) for d in dls]))
+        alg = algorithmic_bytes(N, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows, kept, units, score_mode)
+        out[name] = {"ms_per_step": round(r["ms"], 5), "ms_min_max": [round(r["ms_min"], 5), round(r["ms_max"], 5)],
+                     "tokens_per_s": round(N / (r["ms"] * 1e-3), 1), "retained_fraction": round(kept / (N * cfg.n_kv_heads), 4),
+                     "frac": round(alg / (r["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del dls
+    torch.cuda.empty_cache()
+    return out
+
+
+def oracle_seconds(np, O, H, layer, threads=None):
+    """Best of a few oracle layer-passes (inputs already upcast), optionally with the numerical
+    libraries limited to `threads` threads."""
+    c = layer.cfg
+    q, k = layer.f64("q_win"), layer.f64("k")
+
+    def once():
+        t = time.perf_counter()
+        O.oracle_compress_layer(q, k, layer.k, layer.v, layer.cu_seqlens, c.n_q_heads, c.n_kv_heads, c.window,
+                                n_sink=c.n_sink, T=H.threshold_as_float32(c.threshold), rank_mode=O.RANK_POSITION,
+                                form="cumsum")
+        return time.perf_counter() - t
+
+    def best():
+        return min(once() for _ in range(3))
+    if threads is None:
+        return best()
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:
+        return None
+    with threadpool_limits(limits=threads):
+        return best()
 
 
 def main():
@@ -222,9 +336,11 @@ def main():
     ap.add_argument("--prefill-lse", type=int, default=1,
                     help="also time the pass when the prefill hands over the window rows' log-sum-exp (0 = skip)")
     ap.add_argument("--all-layers", type=int, default=30,
-                    help="also time this many layers compressed by one call, as a batch (0 = skip)")
+                    help="also time this many layers compressed by one rfkv_compress_layers call (0 = skip)")
     ap.add_argument("--wide", type=int, default=1,
                     help="also time the ablation's wide window (k = 1 %% of n) on the headline shape (0 = skip)")
+    ap.add_argument("--configs", default="0,1,2,3,4,K1",
+                    help="other workload configurations to time briefly, comma separated ('' = none)")
     ap.add_argument("--streams", type=int, default=4,
                     help="HIP streams the steps are spread over (layers are independent; step i runs on stream i %% S)")
     ap.add_argument("--graph", type=int, default=1, help="replay the timed steps from a HIP graph (1) or launch eagerly (0)")
@@ -250,69 +366,73 @@ def main():
     # `layers` device buffers to rotate over; at most `gen_layers` of them are generated on the host, the
     # rest are further uploads of the same layers in turn (their own buffers, inputs and outputs)
     host_layers = [W.make_layer(cfg_id, li) for li in range(min(args.layers, args.gen_layers))]
-    dls = {B.RANK_POSITION: [H.DeviceLayer(host_layers[i % len(host_layers)], rank_mode=B.RANK_POSITION,
-                                           kv_layout=args.kv_layout) for i in range(args.layers)]}
-    # score ranking shares the inputs, with its own outputs
-    dls[B.RANK_SCORE] = []
-    for dl in dls[B.RANK_POSITION]:
-        d2 = H.DeviceLayer.__new__(H.DeviceLayer)
-        d2.__dict__.update(dl.__dict__)
-        d2.params = B.RfkvParams.from_buffer_copy(dl.params)
-        d2.params.rank_mode = B.RANK_SCORE
-        d2.buf = dl.buf
-        dls[B.RANK_SCORE].append(d2)
+    pos_dls = [H.DeviceLayer(host_layers[i % len(host_layers)], rank_mode=B.RANK_POSITION, kv_layout=args.kv_layout)
+               for i in range(args.layers)]
     gen_s = time.time() - t0
-    N = dls[B.RANK_POSITION][0].N
+    N = pos_dls[0].N
     wrows = int(np.minimum(cfg.window, np.diff(host_layers[0].cu_seqlens)).sum())
-    units = dls[B.RANK_POSITION][0].batch * cfg.n_kv_heads
+    units = pos_dls[0].batch * cfg.n_kv_heads
+    shape = (N, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows)
 
-    # Layers are independent, so consecutive steps may run on different streams (all at the default
-    # priority).  Layer j always uses stream j % S, hence two uses of one layer's buffers stay ordered.
-    side = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else []
+    def kept_rows_of(dls):
+        return float(np.mean([int(dl.buf.out_offsets[-1]) for dl in dls]))
 
-    def run_steps(mode, count, start=0):
-        if not side:
-            for i in range(count):
-                dls[mode][(start + i) % args.layers].compress(None)   # torch's current stream
-            return
-        cur = torch.cuda.current_stream()
-        for st in side:
-            st.wait_stream(cur)
-        for i in range(count):
-            j = (start + i) % args.layers
-            with torch.cuda.stream(side[j % args.streams]):
-                dls[mode][j].compress(None)
-        for st in side:
-            cur.wait_stream(st)
+    # ---- headline: position ranking, graph over all buffers, several streams
+    head = Stepper(torch, pos_dls, args.streams)
+    try:
+        pos = head.timed(args.steps, args.warmup, graph=bool(args.graph))
+    except Exception as ex:          # graph capture unavailable: fall back to eager launches
+        if not args.graph:
+            raise
+        print(f"bench.py: graph replay failed ({ex}); timing eager launches", file=sys.stderr)
+        args.graph = 0
+        pos = head.timed(args.steps, args.warmup, graph=False)
+    pos["kernel_ms"] = kernel_times(np, B, pos_dls, max(args.layers, 40))
+    pos["kept_rows"] = kept_rows_of(pos_dls)
+    ms_per_step = pos["ms"]
+    value = N / (ms_per_step * 1e-3)
+    alg = algorithmic_bytes(*shape, pos["kept_rows"], units, False)
+    dom = max(pos["kernel_ms"], key=pos["kernel_ms"].get)       # dominant kernel = longest average duration
+    dom_bytes = kernel_bytes(dom, *shape, pos["kept_rows"])
+    dom_gbs = dom_bytes / (pos["kernel_ms"][dom] * 1e-3) / 1e9
+    pipe_gbs = alg / (ms_per_step * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "scope": "whole pass: algorithmic bytes of a step's kernels / step time",
+                "achieved": round(pipe_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(pipe_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": int(alg),
+                "traffic": read_traffic("step", cfg.name),
+                "dominant_kernel": {"kernel": dom, "algorithmic_bytes": int(dom_bytes),
+                                    "ms": round(pos["kernel_ms"][dom], 5), "achieved": round(dom_gbs, 1),
+                                    "kernel_frac": round(dom_gbs / HBM_PEAK_GBS, 4),
+                                    "traffic": read_traffic(dom, cfg.name)},
+                "kernel_ms": {k: round(v, 5) for k, v in pos["kernel_ms"].items()}}
 
-    def timed(mode, steps, warmup):
-        run_steps(mode, warmup)
-        torch.cuda.synchronize()
-        graph = None
-        if args.graph:
-            # one graph holds `layers` consecutive steps; replays cover the timed region
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=None):
-                run_steps(mode, args.layers)
-            torch.cuda.synchronize()
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        ev0.record()
-        if graph is not None:
-            reps = (steps + args.layers - 1) // args.layers
-            for _ in range(reps):
-                graph.replay()
-            done = reps * args.layers
-        else:
-            run_steps(mode, steps)
-            done = steps
-        ev1.record()
-        torch.cuda.synchronize()
-        wall = time.perf_counter() - t
-        return wall / done * 1e3, ev0.elapsed_time(ev1) / done, done
+    # ---- score ranking on the same inputs
+    score_mode = None
+    sdls = None
+    if args.modes == "both":
+        sdls = [with_score_mode(H, B, dl) for dl in pos_dls]
+        sco = Stepper(torch, sdls, args.streams).timed(args.layers, 2, graph=bool(args.graph))
+        kms = kernel_times(np, B, sdls, args.layers)
+        kr = kept_rows_of(sdls)
+        alg_s = algorithmic_bytes(*shape, kr, units, True)
+        score_mode = {"value": round(N / (sco["ms"] * 1e-3), 1), "ms_per_step": round(sco["ms"], 5),
+                      "ms_min_max": [round(sco["ms_min"], 5), round(sco["ms_max"], 5)],
+                      "retained_fraction": round(kr / (N * cfg.n_kv_heads), 4),
+                      "kernel_ms": {k: round(v, 5) for k, v in kms.items()},
+                      "frac": round(alg_s / (sco["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
-    LSE = "prefill_lse"
+    # ---- the same steps on one stream (no overlap between layers): per-layer latency
+    single = None
+    if args.streams > 1:
+        for dl in pos_dls:
+            dl.compress()
+        s1 = Stepper(torch, pos_dls, 1).timed(args.layers, 2, graph=bool(args.graph))
+        single = {"ms_per_step": round(s1["ms"], 5), "ms_min_max": [round(s1["ms_min"], 5), round(s1["ms_max"], 5)],
+                  "frac": round(alg / (s1["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+    # ---- the prefill hands over the window rows' log-sum-exp
+    with_lse = None
+    lse_objs = None
     if args.prefill_lse:
         # Stand-in for the prefill's attention kernel: the window rows' log-sum-exp, by torch, outside
         # every timed region.  Position ranking on the same inputs and buffers as the headline.
@@ -329,97 +449,28 @@ def main():
                     n, wp = e0 - s0, min(c.window, e0 - s0)
                     q = dl.q[q0:q0 + wp].float().view(wp, c.n_kv_heads, G, c.head_dim)
                     logits = torch.einsum("rhgd,hnd->rhgn", q, k[:, s0:e0].float()) * scale
-                    pos = torch.arange(n, device="cuda")[None, :] <= (n - wp + torch.arange(wp, device="cuda"))[:, None]
-                    logits = logits.masked_fill(~pos[:, None, None, :], float("-inf"))
+                    vis = torch.arange(n, device="cuda")[None, :] <= (n - wp + torch.arange(wp, device="cuda"))[:, None]
+                    logits = logits.masked_fill(~vis[:, None, None, :], float("-inf"))
                     parts.append(torch.logsumexp(logits, dim=-1).reshape(wp, c.n_q_heads))
                     q0 += wp
                 self.lse = torch.cat(parts).contiguous()
 
             def compress(self, stream):
                 return self.dl.compress(stream, lse_win=self.lse)
-        dls[LSE] = [WithLse(dl) for dl in dls[B.RANK_POSITION]]
-
-    results = {}
-    modes = (B.RANK_POSITION, B.RANK_SCORE) if args.modes == "both" else (B.RANK_POSITION,)
-    if args.prefill_lse:
-        modes = modes + (LSE,)
-    for mode in modes:
-        steps = args.steps if mode == B.RANK_POSITION else max(args.layers, args.steps // 4)
-        if mode == LSE:
-            wall_ms, ev_ms, done = timed(mode, max(args.layers, args.steps // 2), 2)
-            kept_rows = float(np.mean([int(dl.buf.out_offsets[-1]) for dl in dls[B.RANK_POSITION]]))
-            results[mode] = dict(wall_ms=wall_ms, ev_ms=ev_ms, steps=done, kept_rows=kept_rows,
-                                 retained=kept_rows / (N * cfg.n_kv_heads))
-            continue
-        try:
-            wall_ms, ev_ms, done = timed(mode, steps, args.warmup)
-        except Exception as ex:          # graph capture unavailable: fall back to eager launches
-            if not args.graph:
-                raise
-            print(f"bench.py: graph replay failed ({ex}); timing eager launches", file=sys.stderr)
-            args.graph = 0
-            wall_ms, ev_ms, done = timed(mode, steps, args.warmup)
-        # per-kernel durations from HIP events recorded on the launch stream between kernels
-        kms = np.zeros(len(B.KERNEL_NAMES))
-        reps = max(args.layers, min(64, steps))
-        for i in range(reps):
-            dl = dls[mode][i % args.layers]
-            b = dl.buf
-            _, ms = B.rfkv_compress_layer_timed(dl.params, dl.q, dl.k, dl.v, dl.cu_host, dl.cu_dev, b.scores, b.kept,
-                                                b.out_offsets, b.idx, b.k_out, b.v_out, b.capacity_rows, b.ws,
-                                                b.ws_bytes, None)
-            kms += np.array(ms)
-        kms /= reps
-        kept_rows = float(np.mean([int(dl.buf.out_offsets[-1]) for dl in dls[mode]]))
-        results[mode] = dict(wall_ms=wall_ms, ev_ms=ev_ms, steps=done, kernel_ms=dict(zip(B.KERNEL_NAMES, kms.tolist())),
-                             kept_rows=kept_rows, retained=kept_rows / (N * cfg.n_kv_heads))
-
-    pos = results[B.RANK_POSITION]
-    ms_per_step = pos["wall_ms"]
-    value = N / (ms_per_step * 1e-3)
-    shape = (N, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows)
-    alg = algorithmic_bytes(*shape, pos["kept_rows"], units, False)
-    # dominant kernel = the one with the longest average duration
-    dom = max(pos["kernel_ms"], key=pos["kernel_ms"].get)
-    dom_bytes = kernel_bytes(dom, *shape, pos["kept_rows"])
-    dom_gbs = dom_bytes / (pos["kernel_ms"][dom] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(dom_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(dom_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                "kernel_ms": {k: round(v, 5) for k, v in pos["kernel_ms"].items()},
-                "kernel_algorithmic_bytes": int(dom_bytes),
-                "pipeline_algorithmic_bytes": int(alg),
-                "pipeline_achieved": round(alg / (ms_per_step * 1e-3) / 1e9, 1),
-                "pipeline_frac": round(alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-
-    score_mode = None
-    if B.RANK_SCORE in results:
-        sco = results[B.RANK_SCORE]
-        alg_s = algorithmic_bytes(*shape, sco["kept_rows"], units, True)
-        score_mode = {"value": round(N / (sco["wall_ms"] * 1e-3), 1), "ms_per_step": round(sco["wall_ms"], 5),
-                      "retained_fraction": round(sco["retained"], 4),
-                      "kernel_ms": {k: round(v, 5) for k, v in sco["kernel_ms"].items()},
-                      "pipeline_frac": round(alg_s / (sco["wall_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-
-    # the same steps on one stream (no overlap between layers): per-layer latency
-    single = None
-    if args.streams > 1:
-        side.clear()
-        w1, e1, _ = timed(B.RANK_POSITION, max(args.layers, args.steps // 2), 2)
-        single = {"ms_per_step": round(w1, 5), "pipeline_frac": round(alg / (w1 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
-        if LSE in results:
-            results[LSE]["single_ms"] = timed(LSE, max(args.layers, args.steps // 2), 2)[0]
-
-    with_lse = None
-    if LSE in results:
-        r = results[LSE]
-        alg_l = algorithmic_bytes(*shape, r["kept_rows"], units, False) + 4 * wrows * cfg.n_q_heads
+        lse_objs = [WithLse(dl) for dl in pos_dls]
+        r = Stepper(torch, lse_objs, args.streams).timed(args.layers, 2, graph=bool(args.graph))
+        kr = kept_rows_of(pos_dls)
+        alg_l = algorithmic_bytes(*shape, kr, units, False) + 4 * wrows * cfg.n_q_heads
+        r1 = Stepper(torch, lse_objs, 1).timed(args.layers, 2, graph=bool(args.graph)) if args.streams > 1 else None
         with_lse = {"note": "window rows' log-sum-exp supplied by the caller (rfkv_compress_layer_lse): no statistics pass, "
                             "K read once; the lse itself comes from torch outside the timed region",
-                    "value": round(N / (r["wall_ms"] * 1e-3), 1), "ms_per_step": round(r["wall_ms"], 5),
-                    "retained_fraction": round(r["retained"], 4),
-                    "pipeline_frac": round(alg_l / (r["wall_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                    "single_stream_ms_per_step": round(r["single_ms"], 5) if "single_ms" in r else None}
+                    "value": round(N / (r["ms"] * 1e-3), 1), "ms_per_step": round(r["ms"], 5),
+                    "ms_min_max": [round(r["ms_min"], 5), round(r["ms_max"], 5)],
+                    "retained_fraction": round(kr / (N * cfg.n_kv_heads), 4),
+                    "frac": round(alg_l / (r["ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "single_stream_ms_per_step": round(r1["ms"], 5) if r1 else None}
 
+    # ---- the CPU oracle on the same workload
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import refreekv_oracle as O
@@ -442,27 +493,37 @@ def main():
             passes += 1
         dt = (time.perf_counter() - t) / passes
         # the run doubles as a last parity check of the benchmarked launch configuration
-        dl = dls[B.RANK_POSITION][0]
+        dl = pos_dls[0]
         dl.compress(None)
         gpu = dl.results()
         agree = bool(np.array_equal(gpu["kept"], out["kept"]))
+        # the small configurations with the numerical libraries held to one thread, and unrestricted
+        small = {}
+        for cid in (0, 1):
+            L = W.make_layer(cid, 0)
+            one, many = oracle_seconds(np, O, H, L, threads=1), oracle_seconds(np, O, H, L)
+            small[f"config{cid}"] = {"tokens": int(L.cu_seqlens[-1]),
+                                     "one_thread_ms_per_layer_pass": None if one is None else round(one * 1e3, 3),
+                                     "all_threads_ms_per_layer_pass": round(many * 1e3, 3)}
         cpu = {"value": round(N / dt, 1), "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                "sample": f"{passes} layer-passes over {len(host_layers)} layers of the same workload ({N} tokens, all "
                          f"{cfg.n_kv_heads} KV heads each, upcast to float64 included), float64 numpy, {dt:.2f} s per layer-pass",
-               "kept_counts_match_gpu": agree}
+               "kept_counts_match_gpu": agree, "small_configs": small}
 
-    decode = None
-    if args.decode:
-        decode = time_decode_attention(torch, np, H, B, W)
+    decode = time_decode_attention(torch, np, H, B, W) if args.decode else None
+    all_layers = time_all_layers(torch, np, H, B, W, host_layers, cfg, args.all_layers) if args.all_layers else None
+    wide = time_wide_window(np, H, B, W) if args.wide else None
 
-    all_layers = None
-    if args.all_layers:
-        all_layers = time_all_layers(torch, np, H, B, W, host_layers, cfg, args.all_layers,
-                                     lse_per_layer=[x.lse for x in dls[LSE]] if args.prefill_lse else None)
-
-    wide = None
-    if args.wide:
-        wide = time_wide_window(np, H, B, W)
+    per_config = None
+    if args.configs:
+        del head, pos_dls, lse_objs, sdls                # make room: the other configurations bring their own buffers
+        torch.cuda.empty_cache()
+        per_config = {}
+        for cid in args.configs.split(","):
+            cid = int(cid) if cid.isdigit() else cid
+            if cid == cfg_id:
+                continue
+            per_config[str(cid)] = time_config(torch, np, H, B, W, cid, args.streams)
 
     if args.calibrate_copy:
         src = torch.empty(128 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -471,21 +532,24 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    roofline["traffic"] = read_traffic(dom, cfg.name)
     line = {
         "metric": "tokens/s compressed per layer-pass at Llama3-8B shape, 32K ctx; % peak HBM BW",
         "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": pos["steps"], "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.n_q_heads}q/{cfg.n_kv_heads}kv heads, d={cfg.head_dim}, "
-                               f"batch {dls[B.RANK_POSITION][0].batch}, {N} tokens, window {cfg.window}, T={cfg.threshold}, "
+                               f"batch {units // cfg.n_kv_heads}, {N} tokens, window {cfg.window}, T={cfg.threshold}, "
                                f"m={cfg.n_sink}, position ranking, K/V {args.kv_layout}, {args.layers} rotating layer buffers",
-                   "rank_mode": "position", "retained_fraction": round(pos["retained"], 4),
-                   "launch": "hip_graph" if args.graph else "eager", "streams": args.streams, "event_ms_per_step": round(pos["ev_ms"], 5),
-                   "input_generation_s": round(gen_s, 1)},
-        "percent_peak_hbm": round(100 * roofline["pipeline_frac"], 2),
+                   "rank_mode": "position", "retained_fraction": round(pos["kept_rows"] / (N * cfg.n_kv_heads), 4),
+                   "launch": "hip_graph" if args.graph else "eager", "streams": args.streams,
+                   "steps_requested": args.steps, "steps_run": pos["steps"], "replays": pos["replays"],
+                   "timing": "median over replays of the HIP-event time of one replay / steps in it",
+                   "ms_per_step_min_max": [round(pos["ms_min"], 5), round(pos["ms_max"], 5)],
+                   "wall_ms_per_step": round(pos["wall_ms"], 5), "input_generation_s": round(gen_s, 1)},
+        "percent_peak_hbm": round(100 * roofline["frac"], 2),
         "roofline": roofline, "cpu_baseline": cpu, "score_ranking": score_mode, "single_stream": single,
-        "with_prefill_lse": with_lse, "all_layers_one_call": all_layers, "decode_attention": decode, "wide_window": wide,
+        "with_prefill_lse": with_lse, "all_layers_one_call": all_layers, "per_config": per_config,
+        "decode_attention": decode, "wide_window": wide,
     }
     print(json.dumps(line))
 
