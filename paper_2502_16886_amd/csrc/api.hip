@@ -58,6 +58,9 @@ Workspace carve_workspace(const Geometry& g, void* base) {
   w.tile_sq = static_cast<double*>(take((size_t)g.tiles_total * g.n_kv_heads * sizeof(double)));
   if (g.spill) w.logits = static_cast<float*>(take((size_t)g.tiles_total * 32 * kSpillRows * g.n_kv_heads * sizeof(float)));
   w.counters = static_cast<int32_t*>(take((size_t)2 * g.units * sizeof(int32_t)));
+  if (g.score_slices > 0) {
+    w.sel_block = static_cast<uint32_t*>(take((size_t)g.units * kSelWords * sizeof(uint32_t)));
+  }
   w.bytes = off;
   return w;
 }
@@ -175,6 +178,7 @@ Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len, con
   g.span = choose_span(g.wide ? total * (g.rows_pad / 128) / 2 : total, p->n_kv_heads, g.wide ? 64 : 16);
   g.nspans = (max_len + g.span - 1) / g.span;
   g.max_seqlen = max_len;
+  g.score_slices = score_slices(max_len, g.units);      // whatever the ranking: a workspace serves both
   g.total_tokens = total;
   g.elem_bytes = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
   // 32-position tiles per sequence; without the lengths, the bound every batch of this size obeys
@@ -224,6 +228,7 @@ ScoreArgs score_args(const rfkv_params* p, const Geometry& g, const Workspace& w
   a.threshold = p->threshold;
   a.kept = kept_fused;
   a.desc = w.desc;
+  a.sel_block = p->rank_mode == RFKV_RANK_SCORE && g.score_slices > 0 ? w.sel_block : nullptr;
   a.q = q;
   a.lse = lse;
   a.n_q_heads = g.n_q_heads;
@@ -278,6 +283,8 @@ hipError_t run_select(const rfkv_params* p, const Geometry& g, const Workspace& 
   a.rank_mode = p->rank_mode;
   a.threshold = p->threshold;
   a.per_layer = p->granularity == RFKV_PER_LAYER ? 1 : 0;
+  a.sel_block = w.sel_block;
+  a.units = g.units;
   return launch_select(g, a, stream);
 }
 

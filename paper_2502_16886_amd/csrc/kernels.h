@@ -28,7 +28,31 @@ struct Geometry {
   int64_t tiles_total;    // sum over sequences of ceil(n_b / 32) (an upper bound when sizing)
   int32_t spill;          // window * group <= kSpillRows: scoring keeps its logits instead of re-reading K
   int32_t wide;           // window * group > RFKV_MAX_SCORE_ROWS: row-blocked statistics, key-resident column sums
+  int32_t score_slices;   // score ranking: workgroups a unit is split over (0: one workgroup per unit)
 };
+
+// Score ranking of long units: a unit is split over several workgroups when the longest sequence has more
+// than kSingleWorkgroupMax positions and the batch no more than kSlicedMaxUnits units (each unit then has
+// a 24 KB histogram in the workspace).
+constexpr int kSingleWorkgroupMax = 8192;
+constexpr int kSliceMin = 2048;             // positions per slice at least (two per thread)
+constexpr int kMaxSlices = 32;
+constexpr int kSlicedMaxUnits = 1024;
+// A unit's block in the workspace: 2048 counts (uint32), 2048 integer masses (uint64), the arrival counter
+// of its workgroups and a pad word.  Every word is zero when the histogram kernel starts: the kernel that
+// runs just before it in the same call (the last scoring kernel, or the tile-sum kernel of a separate
+// rfkv_select) clears it, one workgroup per unit.
+constexpr int kSelCntWords = 2048, kSelMassWords = 4096;
+constexpr int kSelWords = kSelCntWords + kSelMassWords + 2;
+__device__ __forceinline__ void clear_select_block(uint32_t* sel_block, int unit) {
+  uint2* p2 = reinterpret_cast<uint2*>(sel_block + (int64_t)unit * kSelWords);      // 24584 bytes, 8-byte aligned
+  for (int i = threadIdx.x; i < kSelWords / 2; i += blockDim.x) p2[i] = make_uint2(0u, 0u);
+}
+inline int score_slices(int max_seqlen, int units) {
+  if (max_seqlen <= kSingleWorkgroupMax || units > kSlicedMaxUnits) return 0;
+  const int w = (max_seqlen + kSliceMin - 1) / kSliceMin;
+  return w > kMaxSlices ? kMaxSlices : w;
+}
 
 struct Workspace {
   float2*  partials;      // [units][nspans][rows_pad]  (reference exponent, sum) per span
@@ -40,6 +64,7 @@ struct Workspace {
   float*   logits;        // [Hkv][kSpillRows][tiles_total * 32]  scaled logits, only when window * G <= kSpillRows
   int32_t* counters;      // [2][units]  workgroups of a unit that have finished the statistics / the reduction pass;
                           //             zeroed by the call's first kernel, put back to zero by each last arriver
+  uint32_t* sel_block;    // [units][kSelWords]  score ranking of long units, see kSelWords
   size_t   bytes;
 };
 
@@ -77,6 +102,7 @@ struct ScoreArgs {
   float threshold;
   int32_t* kept;          // fuse_select: [units]
   int4* desc;             // fuse_select: [units] {kept, sinks kept, -, -}
+  uint32_t* sel_block;    // not null: the last scoring kernel clears every unit's block for the score ranking
 };
 
 struct SelectArgs {
@@ -93,6 +119,10 @@ struct SelectArgs {
   float threshold;
   int32_t per_layer;      // one cut per (layer, sequence) over all heads instead of one per unit
   int32_t lds_floats;     // set by launch_select: floats of dynamic LDS the select kernel may use
+  // score ranking of long units (several workgroups per unit): per unit kSelWords words (first-digit
+  // histogram, arrival counter), zero when the histogram kernel starts
+  uint32_t* sel_block;
+  int32_t units;
 };
 
 enum CompactSource { kSrcPositionDesc = 0, kSrcPaddedIdx = 1, kSrcPackedIdx = 2 };

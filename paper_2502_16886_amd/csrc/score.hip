@@ -209,6 +209,7 @@ __global__ __launch_bounds__(kBlockThreads, 2) void score_reduce_kernel(ScoreArg
   const int span_end = min(u.n, span_begin + a.span);
   const int rows32 = u.row_tiles * 32;
 
+  if (blockIdx.x == 0 && a.sel_block) clear_select_block(a.sel_block, blockIdx.y);   // for the score ranking of long units
   stage_q<T, D>(a, u, smem);
   float* bsm = reinterpret_cast<float*>(smem + rows32 * S::kLdsRowBytes);   // [rows32] exponent offsets
   int* rlast = reinterpret_cast<int*>(bsm + rows32);                        // [rows32] last visible key

@@ -82,6 +82,7 @@ __global__ __launch_bounds__(256) void score_spill_reduce_kernel(ScoreArgs a) {
     if (a.fuse_select) coherent_store(tsq_out, v);
     else *tsq_out = v;
   }
+  if (a.sel_block && blockIdx.x == 0) clear_select_block(a.sel_block, blockIdx.y);
   if (a.fuse_select && last_arrival(a.counters + a.units + blockIdx.y, (u.n + 255) / 256, &sh_flag))
     cut_unit(a, u, blockIdx.y, &sh_pos);
 }

@@ -347,6 +347,7 @@ __device__ __forceinline__ void score_stream_body(const ScoreArgs& a, int block_
     }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // no load may still be writing LDS from here on
+  if (PASS == 2 && a.sel_block && bx == 0) clear_select_block(a.sel_block, by);
   if (PASS == 2 && a.fuse_select) {
     __syncthreads();                                   // every wavefront is done with its tile buffers
     PositionShared<kStreamThreads>* sh = reinterpret_cast<PositionShared<kStreamThreads>*>(smem);

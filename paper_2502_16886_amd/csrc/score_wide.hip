@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256, 2) void score_colsum_wide_kernel(ScoreArgs a) 
   // longest, are dispatched first
   const int kb0 = (kblocks - 1 - (w - by * kblocks)) * kWideKeys;
   if (kb0 >= u.n) return;                              // uniform for the whole workgroup
+  if (kb0 == 0 && a.sel_block) clear_select_block(a.sel_block, by);     // for the score ranking of long units
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 31, hi = lane >> 5;

@@ -118,6 +118,24 @@ __device__ __forceinline__ float4 load_scores4(const float* al, int q, int mis, 
   return v;
 }
 
+// kBatch 4-vectors of scores, q[j] = qb + (j * kT + tid) * 4, all loads in flight at once: the vectors
+// that lie wholly inside the unit (all but its two ends) are loaded without a branch between them.
+template <int kBatch>
+__device__ __forceinline__ void load_scores_batch(float4* v, const float* al, int qb, int mis, int span) {
+  const int tid = threadIdx.x;
+  const int q_first = qb + tid * 4, q_last = qb + ((kBatch - 1) * kT + tid) * 4;
+  if (q_first >= mis && q_last + 4 <= span) {
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) v[j] = *reinterpret_cast<const float4*>(al + qb + (j * kT + tid) * 4);
+  } else {
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      const int q = qb + (j * kT + tid) * 4;
+      v[j] = q < span ? load_scores4(al, q, mis, span) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+}
+
 // Per-tile squared-score sums straight from a score array (used when scoring did not run in
 // the same call).  One wavefront per tile, same butterfly as the scoring kernel.
 __global__ __launch_bounds__(kBlockThreads) void tile_sums_kernel(SelectArgs a) {
@@ -130,6 +148,7 @@ __global__ __launch_bounds__(kBlockThreads) void tile_sums_kernel(SelectArgs a) 
   const int nt = (n + kTileKeys - 1) / kTileKeys;
   const int lane = threadIdx.x & 63;
   const int tile = blockIdx.x * (kBlockThreads / 64) + (threadIdx.x >> 6);
+  if (blockIdx.x == 0 && a.sel_block) clear_select_block(a.sel_block, unit);   // for the score ranking of long units
   if (tile >= nt) return;                                  // uniform per wavefront
   const float* s = a.scores + (int64_t)h * a.total_tokens + s0;
   const int pos = tile * kTileKeys + lane;
@@ -402,6 +421,344 @@ __global__ __launch_bounds__(kT) void select_kernel(SelectArgs a) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Score ranking of long units, a unit split over several workgroups.
+//
+// select_score_hist_kernel, grid (slices, units): every workgroup forms the histogram of the first
+// radix digit (count and integer mass per bucket) over its slice of the unit in LDS and adds its
+// non-empty buckets to the unit's histogram in the workspace (integer atomics: exact, so the order
+// of arrival does not matter).  The workgroup that arrives last finds the crossing bucket, collects
+// the unit's positions in that bucket (usually a small part of the unit) into LDS and finishes
+// the two remaining digits and the tie count on them alone; it leaves the cut (key, ties, kept count).
+// select_score_emit_kernel, grid (slices, units): every workgroup counts the retained positions before
+// its slice (above the cut key, and equal to it) and writes the retained positions of its slice in
+// ascending order; of the positions that tie the cut key the lowest `ties` are kept.
+// ---------------------------------------------------------------------------------------------
+
+// positions [p0, p1) of slice `slice` of `slices`: whole 1024-position blocks, so that the emit
+// kernel's chunks and the aligned 16-byte loads of both kernels coincide for every slice
+__device__ __forceinline__ void slice_range(int n, int mis, int slice, int slices, int* q0, int* q1) {
+  const int span = n + mis;                                 // floats from the aligned base
+  const int blocks = (span + kT - 1) / kT;
+  const int per = (blocks + slices - 1) / slices;
+  *q0 = min(span, slice * per * kT);
+  *q1 = min(span, (slice + 1) * per * kT);
+}
+
+__global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
+  __shared__ uint64_t sh_scan[kWaves][2];
+  __shared__ double sh_dbl[kWaves];
+  __shared__ uint32_t sh_cnt[kBuckets];
+  __shared__ uint64_t sh_mass[kBuckets];
+  extern __shared__ __attribute__((aligned(16))) float sh_cand[];           // the crossing bucket's scores
+  __shared__ int sh_i[8];
+  __shared__ uint64_t sh_u64[2];
+  __shared__ int sh_flag;
+
+  const int unit = blockIdx.y, slice = blockIdx.x, slices = gridDim.x;
+  const int b = unit / a.n_kv_heads, h = unit - b * a.n_kv_heads;
+  int tile_base = 0;
+  for (int bb = 0; bb < b; ++bb) tile_base += (a.cu[bb + 1] - a.cu[bb] + kTileKeys - 1) / kTileKeys;
+  const int s0 = a.cu[b];
+  const int n = a.cu[b + 1] - s0;
+  const int tid = threadIdx.x;
+  auto publish = [&](int kept, int ties, uint32_t key) {
+    if (tid == 0) {
+      a.kept[unit] = kept;
+      a.desc[unit] = make_int4(kept, 0, ties, (int)key);
+    }
+  };
+  if (n == 0) {
+    if (slice == 0) publish(0, -1, 0u);
+    return;
+  }
+  const float* s = a.scores + (int64_t)h * a.total_tokens + s0;
+  const double* tiles = a.tile_sq + (int64_t)h * a.tiles_total + tile_base;
+  const int nt = (n + kTileKeys - 1) / kTileKeys;
+  // F^2: every workgroup of the unit adds the tile sums in the same order and gets the same bits
+  double f2 = 0.0;
+  const bool keep_all = !(a.threshold > 0.f);
+  if (!keep_all) {
+    for (int j = tid; j < nt; j += kT) f2 += tiles[j];
+    f2 = block_sum_double<kT>(f2, sh_dbl);
+  }
+  if (keep_all || !(f2 > 0.0) || !(f2 < 1e300)) {          // uniform over the unit's workgroups: keep everything
+    if (slice == 0) publish(n, -1, 0u);                    // ties < 0: the emit kernel writes the identity
+    return;
+  }
+  const double inv = 1152921504606846976.0 / f2;            // masses are integers in units of F^2 / 2^60
+  const int mis = (int)((reinterpret_cast<uintptr_t>(s) >> 2) & 3);
+  const float* al = s - mis;
+  const int span = n + mis;
+
+  // ---- first digit over this workgroup's slice
+  for (int d = tid; d < kBuckets; d += kT) {
+    sh_cnt[d] = 0;
+    sh_mass[d] = 0;
+  }
+  __syncthreads();
+  int q0, q1;
+  slice_range(n, mis, slice, slices, &q0, &q1);
+  for (int q = q0 + tid * 4; q < q1; q += kT * 4) {
+    const float4 v = load_scores4(al, q, mis, span);
+    const float f[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int i = q + e - mis;
+      if (i >= 0 && i < n) {
+        const uint32_t d = order_key(f[e]) >> 21;
+        atomicAdd(&sh_cnt[d], 1u);
+        atomicAdd(reinterpret_cast<unsigned long long*>(&sh_mass[d]), (unsigned long long)quantise(f[e], inv));
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* g_cnt = a.sel_block + (int64_t)unit * kSelWords;
+  unsigned long long* g_mass = reinterpret_cast<unsigned long long*>(g_cnt + kSelCntWords);
+  int32_t* g_arrivals = reinterpret_cast<int32_t*>(g_cnt + kSelCntWords + kSelMassWords);
+  if (slices > 1) {
+    for (int d = tid; d < kBuckets; d += kT) {
+      const uint32_t c = sh_cnt[d];
+      if (c) {
+        atomicAdd(&g_cnt[d], c);
+        atomicAdd(&g_mass[d], (unsigned long long)sh_mass[d]);
+      }
+    }
+    if (!last_arrival(g_arrivals, slices, &sh_flag)) return;
+    // ---- the last workgroup of the unit: the whole unit's first-digit histogram
+    for (int d = tid; d < kBuckets; d += kT) {
+      sh_cnt[d] = __hip_atomic_load(&g_cnt[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      sh_mass[d] = __hip_atomic_load(&g_mass[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+  }
+  Pred pred{0.0, (double)a.threshold, a.min_keep};
+  uint32_t prefix = 0;
+  int64_t cnt_above = 0;
+  uint64_t mass_above = 0;
+  uint32_t cut_cnt = 0;
+  uint64_t cut_mass = 0;
+  int done_bits = 0;
+  // crossing bucket of the histogram in sh_cnt / sh_mass (nb buckets of `width` bits); false: keep everything
+  auto resolve = [&](int width, bool first) -> bool {
+    const int nb = 1 << width;
+    if (tid == 0) sh_i[1] = 0;
+    __syncthreads();
+    const int d_hi = nb - 1 - 2 * tid, d_lo = d_hi - 1;
+    const uint32_t c_hi = d_hi >= 0 ? sh_cnt[d_hi] : 0, c_lo = d_lo >= 0 ? sh_cnt[d_lo] : 0;
+    const uint64_t m_hi = d_hi >= 0 ? sh_mass[d_hi] : 0, m_lo = d_lo >= 0 ? sh_mass[d_lo] : 0;
+    uint64_t tot_c, tot_m, ex_c = (uint64_t)c_hi + c_lo, ex_m = m_hi + m_lo;
+    block_exclusive_scan2(ex_c, ex_m, sh_scan, &tot_c, &tot_m);
+    if (first) {
+      pred.set_total((double)tot_m);                       // the first histogram holds every position: P_n exactly
+      if (!pred(n, tot_m)) return false;                   // min_keep >= n (or no mass)
+    }
+    if (d_hi >= 0) {
+      const int64_t n0 = cnt_above + (int64_t)ex_c;
+      const uint64_t m0 = mass_above + ex_m;
+      const bool p0 = pred(n0, m0);
+      const bool p1 = pred(n0 + c_hi, m0 + m_hi);
+      if (!p0 && p1 && c_hi > 0) {
+        sh_i[1] = d_hi;
+        sh_u64[0] = (uint64_t)n0;
+        sh_u64[1] = m0;
+      } else if (d_lo >= 0 && !p1) {
+        const bool p2 = pred(n0 + c_hi + c_lo, m0 + m_hi + m_lo);
+        if (p2 && c_lo > 0) {
+          sh_i[1] = d_lo;
+          sh_u64[0] = (uint64_t)(n0 + c_hi);
+          sh_u64[1] = m0 + m_hi;
+        }
+      }
+    }
+    __syncthreads();
+    const int d_cut = sh_i[1];
+    cnt_above = (int64_t)sh_u64[0];
+    mass_above = sh_u64[1];
+    cut_cnt = sh_cnt[d_cut];
+    cut_mass = sh_mass[d_cut];
+    prefix = (prefix << width) | (uint32_t)d_cut;
+    done_bits += width;
+    __syncthreads();
+    return true;
+  };
+  if (!resolve(11, true)) {
+    publish(n, -1, 0u);
+    return;
+  }
+  // ---- the crossing bucket's scores: into LDS if they fit, else every later digit reads the unit again
+  const bool resident = (int)cut_cnt <= a.lds_floats;
+  if (tid == 0) sh_i[2] = 0;
+  __syncthreads();
+  if (resident) {
+    // every thread looks at eight 4-vectors at a time; a wavefront reserves places for all its hits with
+    // one LDS atomic (prefix over lanes), so a bucket that holds most of the unit costs no more than an
+    // almost empty one
+    constexpr int kBatch = 8;
+    const int lane = tid & 63;
+    for (int qb = 0; qb < span; qb += kT * 4 * kBatch) {
+      float4 v[kBatch];
+      load_scores_batch<kBatch>(v, al, qb, mis, span);
+      uint32_t hits = 0;                                   // bit 4 j + e: element e of vector j is in the bucket
+#pragma unroll
+      for (int j = 0; j < kBatch; ++j) {
+        const int q = qb + (j * kT + tid) * 4;
+        const float f[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = q + e - mis;
+          hits |= (uint32_t)(q < span && i >= 0 && i < n && (order_key(f[e]) >> 21) == prefix) << (4 * j + e);
+        }
+      }
+      const int mine = __popc(hits);
+      if (__ballot(mine > 0)) {
+        const int inc = wave_inclusive_scan(mine, lane);
+        int base = 0;
+        if (lane == 63) base = atomicAdd(&sh_i[2], inc);
+        base = __shfl(base, 63) + inc - mine;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+          const float f[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (hits & (1u << (4 * j + e))) sh_cand[base++] = f[e];
+        }
+      }
+    }
+    __syncthreads();
+  }
+  const int ncand = resident ? (int)cut_cnt : 0;
+  // f(score) for every position of the unit whose key starts with the digits decided so far
+  auto for_each_candidate = [&](auto f) {
+    if (resident) {
+      for (int j = tid; j < ncand; j += kT) {
+        const float x = sh_cand[j];
+        if ((order_key(x) >> (32 - done_bits)) == prefix) f(x);
+      }
+    } else {
+      for (int q = tid * 4; q < span; q += kT * 4) {
+        const float4 v = load_scores4(al, q, mis, span);
+        const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = q + e - mis;
+          if (i >= 0 && i < n && (order_key(x[e]) >> (32 - done_bits)) == prefix) f(x[e]);
+        }
+      }
+    }
+  };
+  const int shifts[2] = {10, 0}, widths[2] = {11, 10};
+  for (int lvl = 0; lvl < 2; ++lvl) {
+    const int shift = shifts[lvl], nb = 1 << widths[lvl];
+    for (int d = tid; d < kBuckets; d += kT) {
+      sh_cnt[d] = 0;
+      sh_mass[d] = 0;
+    }
+    __syncthreads();
+    for_each_candidate([&](float x) {
+      const uint32_t d = (order_key(x) >> shift) & (nb - 1);
+      atomicAdd(&sh_cnt[d], 1u);
+      atomicAdd(reinterpret_cast<unsigned long long*>(&sh_mass[d]), (unsigned long long)quantise(x, inv));
+    });
+    __syncthreads();
+    resolve(widths[lvl], false);
+  }
+  // all cut_cnt positions of the final bucket share one value: take the fewest that cross
+  const uint64_t q_each = cut_mass / (cut_cnt ? cut_cnt : 1u);
+  if (tid == 0) {
+    int lo = 1, hi = (int)cut_cnt;                         // pred is true at hi
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (pred(cnt_above + mid, mass_above + (uint64_t)mid * q_each)) hi = mid;
+      else lo = mid + 1;
+    }
+    publish((int)cnt_above + lo, lo, prefix);
+  }
+}
+
+__global__ __launch_bounds__(kT) void select_score_emit_kernel(SelectArgs a) {
+  __shared__ uint32_t sh_w[kWaves][2];
+  const int unit = blockIdx.y, slice = blockIdx.x, slices = gridDim.x;
+  const int b = unit / a.n_kv_heads, h = unit - b * a.n_kv_heads;
+  const int s0 = a.cu[b];
+  const int n = a.cu[b + 1] - s0;
+  if (n == 0 || !a.idx_pad) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* s = a.scores + (int64_t)h * a.total_tokens + s0;
+  int32_t* idx_pad = a.idx_pad + ((int64_t)s0 * a.n_kv_heads + (int64_t)h * n);
+  const int4 cut = a.desc[unit];
+  const int ties = cut.z;
+  const uint32_t key_cut = (uint32_t)cut.w;
+  const int mis = (int)((reinterpret_cast<uintptr_t>(s) >> 2) & 3);
+  const float* al = s - mis;
+  const int span = n + mis;
+  int q0, q1;
+  slice_range(n, mis, slice, slices, &q0, &q1);
+  if (ties < 0) {                                          // everything is kept
+    for (int q = q0 + tid; q < q1; q += kT)
+      if (q >= mis) idx_pad[q - mis] = q - mis;
+    return;
+  }
+  // retained positions before the slice: above the cut key, and equal to it
+  uint32_t g_before = 0, e_before = 0;
+  constexpr int kBatch = 8;
+  for (int qb = 0; qb < q0; qb += kT * 4 * kBatch) {
+    float4 v[kBatch];
+    load_scores_batch<kBatch>(v, al, qb, mis, q0);         // q0 <= span; positions from q0 on read as 0 and are skipped
+#pragma unroll
+    for (int j = 0; j < kBatch; ++j) {
+      const int q = qb + (j * kT + tid) * 4;
+      const float f[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool valid = q + e >= mis && q + e < q0;
+        const uint32_t key = order_key(f[e]);
+        g_before += valid && key > key_cut;
+        e_before += valid && key == key_cut;
+      }
+    }
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    g_before += __shfl_xor(g_before, d);
+    e_before += __shfl_xor(e_before, d);
+  }
+  if (lane == 0) {
+    sh_w[wave][0] = g_before;
+    sh_w[wave][1] = e_before;
+  }
+  __syncthreads();
+  uint32_t g_run = 0, e_run = 0;
+  for (int w = 0; w < kWaves; ++w) {
+    g_run += sh_w[w][0];
+    e_run += sh_w[w][1];
+  }
+  // the slice, 1024 positions at a time in ascending order: thread t takes position q0 + c * 1024 + t
+  for (int c0 = q0; c0 < q1; c0 += kT) {
+    const int q = c0 + tid;
+    const bool valid = q < q1 && q >= mis;
+    const uint32_t key = valid ? order_key(al[q]) : 0u;
+    const uint32_t gt = valid && key > key_cut, eq = valid && key == key_cut;
+    const uint32_t packed = (gt << 16) | eq;
+    const uint32_t inc = wave_inclusive_scan(packed, lane);
+    __syncthreads();                                       // sh_w of the round before has been read
+    if (lane == 63) sh_w[wave][0] = inc;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+    for (int w = 0; w < kWaves; ++w) {
+      const uint32_t t = sh_w[w][0];
+      if (w < wave) before += t;
+      total += t;
+    }
+    const uint32_t ex = before + inc - packed;
+    const uint32_t g = g_run + (ex >> 16), e = e_run + (ex & 0xffffu);
+    if (gt) idx_pad[g + min(e, (uint32_t)ties)] = q - mis;
+    else if (eq && e < (uint32_t)ties) idx_pad[g + e] = q - mis;
+    g_run += total >> 16;
+    e_run += total & 0xffffu;
+  }
+}
+
 // Position ranking, one cut per unit (sequence, KV head) or, with a.per_layer, one cut per (layer,
 // sequence): the norm of Eq. 1 then runs over the reduced attention matrix of all KV heads of the
 // layer (Fig. 1: eviction "per layer"; Sec. 3.3: "the stopping positions of all layers") and every
@@ -439,7 +796,6 @@ __global__ __launch_bounds__(kPosThreads) void select_position_kernel(SelectArgs
 }
 
 }  // namespace
-
 hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t stream) {
   if (g.units == 0) return hipSuccess;
   if (a.from_scores && g.max_seqlen > 0) {
@@ -454,8 +810,21 @@ hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t str
     hipLaunchKernelGGL(select_position_kernel, dim3(a.per_layer ? g.batch : g.units), dim3(kPosThreads), 0, stream, a);
     return hipGetLastError();
   }
-  // Score ranking keeps a unit's scores in LDS when the longest sequence fits (with up to three
-  // floats of alignment slack); otherwise units that fit what is there use it and the rest stream.
+  if (g.score_slices > 0) {
+    // long units: a unit split over several workgroups, then the ordered emit
+    SelectArgs args = a;
+    const int slices = g.score_slices;
+    const int64_t want = ((int64_t)g.max_seqlen + 3) / 4 * 4;
+    args.lds_floats = (int32_t)(want < kMaxLdsFloats ? want : kMaxLdsFloats);
+    const size_t dyn = (size_t)args.lds_floats * sizeof(float);
+    hipError_t e = allow_lds<&select_score_hist_kernel>((size_t)kMaxLdsFloats * sizeof(float));
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(select_score_hist_kernel, dim3(slices, g.units), dim3(kT), dyn, stream, args);
+    if (a.idx_pad) hipLaunchKernelGGL(select_score_emit_kernel, dim3(slices, g.units), dim3(kT), 0, stream, args);
+    return hipGetLastError();
+  }
+  // Short units: one workgroup per unit.  It keeps the unit's scores in LDS (with up to three floats of
+  // alignment slack).
   SelectArgs args = a;
   args.lds_floats = 0;
   if (a.rank_mode == 1 && a.threshold > 0.f) {
