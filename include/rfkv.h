@@ -91,7 +91,8 @@ typedef struct rfkv_params {
                                sequence), the norms of Eq. 1 taken over the reduced attention
                                matrix of all KV heads (Fig. 1 "per layer"; Sec. 3.3 "the stopping
                                positions of all layers"), every head keeping the same number of
-                               positions.  RFKV_PER_LAYER is built for RFKV_RANK_POSITION only.    */
+                               positions: with the position ranking the same positions, with the
+                               score ranking each head its own largest scores.                     */
   /* strides in elements; the head_dim axis is contiguous.  Token index is the packed index
      0..N-1 for K/V and the packed window-row index 0..sum_b w'_b - 1 for Q.                      */
   int64_t k_stride_tok, k_stride_head;

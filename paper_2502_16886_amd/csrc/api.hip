@@ -61,6 +61,10 @@ Workspace carve_workspace(const Geometry& g, void* base) {
   if (g.score_slices > 0) {
     w.sel_block = static_cast<uint32_t*>(take((size_t)g.units * kSelWords * sizeof(uint32_t)));
   }
+  if (g.per_layer) {
+    w.sort_keys = static_cast<uint32_t*>(take((size_t)2 * g.total_tokens * g.n_kv_heads * sizeof(uint32_t)));
+    w.sorted_scores = static_cast<float*>(take((size_t)g.total_tokens * g.n_kv_heads * sizeof(float)));
+  }
   w.bytes = off;
   return w;
 }
@@ -111,7 +115,6 @@ rfkv_status check_params(const rfkv_params* p) {
   if (p->rank_mode != RFKV_RANK_POSITION && p->rank_mode != RFKV_RANK_SCORE) return RFKV_INVALID_ARG;
   if (p->granularity != RFKV_PER_HEAD && p->granularity != RFKV_PER_LAYER) return RFKV_INVALID_ARG;
   if (p->out_pad_rows < 0) return RFKV_INVALID_ARG;
-  if (p->granularity == RFKV_PER_LAYER && p->rank_mode != RFKV_RANK_POSITION) return RFKV_UNSUPPORTED;
   if (p->dtype != RFKV_DTYPE_FP32 && p->dtype != RFKV_DTYPE_BF16) return RFKV_UNSUPPORTED;
   if (p->head_dim != 64 && p->head_dim != 128) return RFKV_UNSUPPORTED;
   const int64_t rows = (int64_t)p->window * (p->n_q_heads / p->n_kv_heads);
@@ -179,6 +182,7 @@ Geometry make_geometry(const rfkv_params* p, int64_t total, int32_t max_len, con
   g.nspans = (max_len + g.span - 1) / g.span;
   g.max_seqlen = max_len;
   g.score_slices = score_slices(max_len, g.units);      // whatever the ranking: a workspace serves both
+  g.per_layer = p->granularity == RFKV_PER_LAYER ? 1 : 0;
   g.total_tokens = total;
   g.elem_bytes = p->dtype == RFKV_DTYPE_BF16 ? 2 : 4;
   // 32-position tiles per sequence; without the lengths, the bound every batch of this size obeys
@@ -285,6 +289,8 @@ hipError_t run_select(const rfkv_params* p, const Geometry& g, const Workspace& 
   a.per_layer = p->granularity == RFKV_PER_LAYER ? 1 : 0;
   a.sel_block = w.sel_block;
   a.units = g.units;
+  a.sort_keys = w.sort_keys;
+  a.sorted_scores = w.sorted_scores;
   return launch_select(g, a, stream);
 }
 

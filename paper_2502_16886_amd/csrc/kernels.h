@@ -29,6 +29,7 @@ struct Geometry {
   int32_t spill;          // window * group <= kSpillRows: scoring keeps its logits instead of re-reading K
   int32_t wide;           // window * group > RFKV_MAX_SCORE_ROWS: row-blocked statistics, key-resident column sums
   int32_t score_slices;   // score ranking: workgroups a unit is split over (0: one workgroup per unit)
+  int32_t per_layer;      // one cut per (layer, sequence): the score ranking then needs room to sort
 };
 
 // Score ranking of long units: a unit is split over several workgroups when the longest sequence has more
@@ -65,6 +66,8 @@ struct Workspace {
   int32_t* counters;      // [2][units]  workgroups of a unit that have finished the statistics / the reduction pass;
                           //             zeroed by the call's first kernel, put back to zero by each last arriver
   uint32_t* sel_block;    // [units][kSelWords]  score ranking of long units, see kSelWords
+  uint32_t* sort_keys;    // [2 * N * Hkv]  per-layer cut with the score ranking: every unit's keys, padded to a power of two
+  float*   sorted_scores; // [Hkv][N]       ... and its scores in ascending order
   size_t   bytes;
 };
 
@@ -123,6 +126,9 @@ struct SelectArgs {
   // histogram, arrival counter), zero when the histogram kernel starts
   uint32_t* sel_block;
   int32_t units;
+  // one cut per (layer, sequence) with the score ranking: see Workspace
+  uint32_t* sort_keys;
+  float* sorted_scores;
 };
 
 enum CompactSource { kSrcPositionDesc = 0, kSrcPaddedIdx = 1, kSrcPackedIdx = 2 };

@@ -795,7 +795,130 @@ __global__ __launch_bounds__(kPosThreads) void select_position_kernel(SelectArgs
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// One cut per (layer, sequence) with the score ranking (Fig. 1 "per layer", Sec. 3.3 "the stopping
+// positions of all layers", with the ranking of Sec. 4.4): every head's row is ranked on its own and the
+// matrix masked at rank i keeps the i largest scores of EVERY head, so the mass of a ranked prefix is
+// sum_h (mass of head h's i largest).  That is a function of the rank, not of a score value shared by
+// the heads, so each head's scores are sorted (bitonic network on their order-preserving keys: chunks
+// of kSortChunk in LDS, the strides beyond a chunk in global memory), written back in ascending order,
+// and the cut is then the position ranking's search with no sinks over the sorted rows (from the end
+// backwards = descending score) with masses summed over the heads.  A head keeps its `kept` largest;
+// of the scores that tie the kept-th largest, the lowest positions.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSortChunk = 8192;                   // keys one workgroup sorts or merges in LDS (32 KB)
+
+__device__ __forceinline__ int sort_size(int n) {    // next power of two >= n
+  int p = 1;
+  while (p < n) p <<= 1;
+  return p;
+}
+__device__ __forceinline__ float key_to_score(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+struct SortUnit {
+  int unit, h, s0, n, n2;
+  uint32_t* keys;       // [n2] the unit's keys being sorted; pads (key 0) sort first
+};
+__device__ __forceinline__ SortUnit sort_unit(const SelectArgs& a, int unit) {
+  SortUnit u;
+  u.unit = unit;
+  const int b = unit / a.n_kv_heads;
+  u.h = unit - b * a.n_kv_heads;
+  u.s0 = a.cu[b];
+  u.n = a.cu[b + 1] - u.s0;
+  u.n2 = sort_size(u.n);
+  u.keys = a.sort_keys + 2 * ((int64_t)u.s0 * a.n_kv_heads + (int64_t)u.h * u.n);     // n2 <= 2 n
+  return u;
+}
+
+// compare-exchange steps (size k, strides j_hi .. 1, each below kSortChunk) on one chunk in LDS
+__device__ __forceinline__ void bitonic_lds_steps(uint32_t* sh, int chunk_base, int len, int k, int j_hi) {
+  for (int j = j_hi; j > 0; j >>= 1) {
+    __syncthreads();
+    for (int t = threadIdx.x; t < len / 2; t += kT) {
+      const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));          // the lower index of pair t
+      const int l = i | j;
+      const bool asc = ((chunk_base + i) & k) == 0;
+      const uint32_t x = sh[i], y = sh[l];
+      if ((x > y) == asc) {
+        sh[i] = y;
+        sh[l] = x;
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// mode 0: load a chunk of keys from the scores (pads first), sort it completely (sizes 2 .. chunk);
+// mode 1: for size k (> chunk), the strides below a chunk.  Grid (chunks, units).
+__global__ __launch_bounds__(kT) void sort_lds_kernel(SelectArgs a, int mode, int k) {
+  __shared__ uint32_t sh[kSortChunk];
+  const SortUnit u = sort_unit(a, blockIdx.y);
+  if (u.n == 0) return;
+  const int len = min(u.n2, kSortChunk);
+  const int base = blockIdx.x * kSortChunk;
+  if (base >= u.n2 || (mode == 1 && k > u.n2)) return;
+  if (mode == 0) {
+    const float* s = a.scores + (int64_t)u.h * a.total_tokens + u.s0;
+    const int pad = u.n2 - u.n;
+    for (int i = threadIdx.x; i < len; i += kT) sh[i] = base + i < pad ? 0u : order_key(s[base + i - pad]);
+    for (int kk = 2; kk <= len; kk <<= 1) bitonic_lds_steps(sh, base, len, kk, kk >> 1);
+  } else {
+    for (int i = threadIdx.x; i < len; i += kT) sh[i] = u.keys[base + i];
+    bitonic_lds_steps(sh, base, len, k, len >> 1);
+  }
+  for (int i = threadIdx.x; i < len; i += kT) u.keys[base + i] = sh[i];
+}
+
+// one compare-exchange step (size k, stride j >= kSortChunk) in global memory.  Grid (pairs / kT, units).
+__global__ __launch_bounds__(kT) void sort_global_kernel(SelectArgs a, int k, int j) {
+  const SortUnit u = sort_unit(a, blockIdx.y);
+  if (k > u.n2) return;
+  const int t = blockIdx.x * kT + threadIdx.x;
+  if (t >= u.n2 / 2) return;
+  const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+  const int l = i | j;
+  const bool asc = (i & k) == 0;
+  const uint32_t x = u.keys[i], y = u.keys[l];
+  if ((x > y) == asc) {
+    u.keys[i] = y;
+    u.keys[l] = x;
+  }
+}
+
+// the sorted scores of every unit, ascending, in the layout of the scores.  Grid (n / kT, units).
+__global__ __launch_bounds__(kT) void sort_store_kernel(SelectArgs a) {
+  const SortUnit u = sort_unit(a, blockIdx.y);
+  const int r = blockIdx.x * kT + threadIdx.x;
+  if (r >= u.n) return;
+  a.sorted_scores[(int64_t)u.h * a.total_tokens + u.s0 + r] = key_to_score(u.keys[u.n2 - u.n + r]);
+}
+
+// after the cut: every head's cut key (its kept-th largest score) and how many of the scores equal to
+// it are kept.  One thread per unit: bisection of the ascending row.
+__global__ __launch_bounds__(64) void layer_score_cut_keys_kernel(SelectArgs a) {
+  const SortUnit u = sort_unit(a, blockIdx.x);
+  if (threadIdx.x != 0) return;
+  const int kept = a.kept[u.unit];
+  if (u.n == 0 || kept >= u.n) {
+    a.desc[u.unit] = make_int4(kept, 0, -1, 0);            // ties < 0: the emit kernel writes the identity
+    return;
+  }
+  const uint32_t* row = u.keys + (u.n2 - u.n);
+  const uint32_t key = row[u.n - kept];                    // kept >= 1
+  int lo = u.n - kept, hi = u.n;                           // first index whose key is greater than the cut key
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (row[mid] > key) hi = mid;
+    else lo = mid + 1;
+  }
+  a.desc[u.unit] = make_int4(kept, 0, kept - (u.n - lo), (int)key);
+}
+
 }  // namespace
+
 hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t stream) {
   if (g.units == 0) return hipSuccess;
   if (a.from_scores && g.max_seqlen > 0) {
@@ -805,6 +928,34 @@ hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t str
                        stream, a);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+  }
+  if (a.per_layer && a.rank_mode == 1 && g.max_seqlen > 0) {
+    // sort every head's scores, cut over the ranks with masses summed over the heads, then each head's keys
+    int n2 = 1;
+    while (n2 < g.max_seqlen) n2 <<= 1;
+    const int chunks = (n2 + kSortChunk - 1) / kSortChunk;
+    hipLaunchKernelGGL(sort_lds_kernel, dim3(chunks, g.units), dim3(kT), 0, stream, a, 0, 0);
+    for (int k = 2 * kSortChunk; k <= n2; k <<= 1) {
+      for (int j = k >> 1; j >= kSortChunk; j >>= 1)
+        hipLaunchKernelGGL(sort_global_kernel, dim3((n2 / 2 + kT - 1) / kT, g.units), dim3(kT), 0, stream, a, k, j);
+      hipLaunchKernelGGL(sort_lds_kernel, dim3(chunks, g.units), dim3(kT), 0, stream, a, 1, k);
+    }
+    hipLaunchKernelGGL(sort_store_kernel, dim3((g.max_seqlen + kT - 1) / kT, g.units), dim3(kT), 0, stream, a);
+    SelectArgs cut = a;                            // the position search over the sorted rows: no sinks, ranks from the end
+    cut.scores = a.sorted_scores;
+    cut.n_sink = 0;
+    cut.sel_block = nullptr;
+    const int tiles = (g.max_seqlen + kTileKeys - 1) / kTileKeys;
+    const int per_block = kBlockThreads / 64;
+    hipLaunchKernelGGL(tile_sums_kernel, dim3((tiles + per_block - 1) / per_block, g.units), dim3(kBlockThreads), 0,
+                       stream, cut);
+    hipLaunchKernelGGL(select_position_kernel, dim3(g.batch), dim3(kPosThreads), 0, stream, cut);
+    hipLaunchKernelGGL(layer_score_cut_keys_kernel, dim3(g.units), dim3(64), 0, stream, a);
+    if (a.idx_pad) {
+      const int slices = g.score_slices > 0 ? g.score_slices : 1;
+      hipLaunchKernelGGL(select_score_emit_kernel, dim3(slices, g.units), dim3(kT), 0, stream, a);
+    }
+    return hipGetLastError();
   }
   if (a.rank_mode == 0) {                          // position ranking: one cut per unit, or per sequence over all heads
     hipLaunchKernelGGL(select_position_kernel, dim3(a.per_layer ? g.batch : g.units), dim3(kPosThreads), 0, stream, a);
