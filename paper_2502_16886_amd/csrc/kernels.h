@@ -33,12 +33,13 @@ struct Geometry {
 };
 
 // Score ranking of long units: a unit is split over several workgroups when the longest sequence has more
-// than kSingleWorkgroupMax positions and the batch no more than kSlicedMaxUnits units (each unit then has
-// a 24 KB histogram in the workspace).
+// than kSingleWorkgroupMax positions and the batch is small enough for the split to put idle CUs to work
+// (a batch of many units fills the chip with one workgroup per unit; each sliced unit has a 24 KB histogram
+// in the workspace).
 constexpr int kSingleWorkgroupMax = 8192;
 constexpr int kSliceMin = 2048;             // positions per slice at least (two per thread)
 constexpr int kMaxSlices = 32;
-constexpr int kSlicedMaxUnits = 1024;
+constexpr int kSliceWorkgroups = 256;       // workgroups of all units together, about one per CU
 // A unit's block in the workspace: 2048 counts (uint32), 2048 integer masses (uint64), the arrival counter
 // of its workgroups and a pad word.  Every word is zero when the histogram kernel starts: the kernel that
 // runs just before it in the same call (the last scoring kernel, or the tile-sum kernel of a separate
@@ -50,9 +51,11 @@ __device__ __forceinline__ void clear_select_block(uint32_t* sel_block, int unit
   for (int i = threadIdx.x; i < kSelWords / 2; i += blockDim.x) p2[i] = make_uint2(0u, 0u);
 }
 inline int score_slices(int max_seqlen, int units) {
-  if (max_seqlen <= kSingleWorkgroupMax || units > kSlicedMaxUnits) return 0;
-  const int w = (max_seqlen + kSliceMin - 1) / kSliceMin;
-  return w > kMaxSlices ? kMaxSlices : w;
+  if (max_seqlen <= kSingleWorkgroupMax || units <= 0) return 0;
+  int w = (max_seqlen + kSliceMin - 1) / kSliceMin;
+  if (w > kMaxSlices) w = kMaxSlices;
+  if (w > kSliceWorkgroups / units) w = kSliceWorkgroups / units;
+  return w >= 2 ? w : 0;
 }
 
 struct Workspace {

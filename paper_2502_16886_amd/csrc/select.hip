@@ -27,6 +27,8 @@ constexpr int kPosThreads = 256;                   // the position ranking's wor
 constexpr int kWaves = kT / 64;
 constexpr int kBuckets = 2048;
 constexpr int kMaxLdsFloats = 32768 + 4;           // scores of one unit held in LDS by the score ranking
+constexpr int kMaxCandidates = 8192;               // scores of a unit's crossing bucket held in LDS (sliced units)
+constexpr int kRankDirect = 128;                   // up to this many candidates are ranked pair by pair
 
 struct Pred {
   double total;     // P_n as a double
@@ -444,6 +446,12 @@ __device__ __forceinline__ void slice_range(int n, int mis, int slice, int slice
   *q0 = min(span, slice * per * kT);
   *q1 = min(span, (slice + 1) * per * kT);
 }
+// slices of a unit that hold positions (a short unit of a ragged batch fills only the first ones)
+__device__ __forceinline__ int slices_used(int n, int mis, int slices) {
+  const int blocks = (n + mis + kT - 1) / kT;
+  const int per = (blocks + slices - 1) / slices;
+  return (blocks + per - 1) / per;
+}
 
 __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
   __shared__ uint64_t sh_scan[kWaves][2];
@@ -452,10 +460,10 @@ __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
   __shared__ uint64_t sh_mass[kBuckets];
   extern __shared__ __attribute__((aligned(16))) float sh_cand[];           // the crossing bucket's scores
   __shared__ int sh_i[8];
-  __shared__ uint64_t sh_u64[2];
+  __shared__ uint64_t sh_u64[3];
   __shared__ int sh_flag;
 
-  const int unit = blockIdx.y, slice = blockIdx.x, slices = gridDim.x;
+  const int unit = blockIdx.y, slice = blockIdx.x;
   const int b = unit / a.n_kv_heads, h = unit - b * a.n_kv_heads;
   int tile_base = 0;
   for (int bb = 0; bb < b; ++bb) tile_base += (a.cu[bb + 1] - a.cu[bb] + kTileKeys - 1) / kTileKeys;
@@ -473,6 +481,11 @@ __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
     return;
   }
   const float* s = a.scores + (int64_t)h * a.total_tokens + s0;
+  const int mis = (int)((reinterpret_cast<uintptr_t>(s) >> 2) & 3);
+  const float* al = s - mis;
+  const int span = n + mis;
+  const int slices = slices_used(n, mis, gridDim.x);
+  if (slice >= slices) return;                             // nothing of the unit falls to this workgroup
   const double* tiles = a.tile_sq + (int64_t)h * a.tiles_total + tile_base;
   const int nt = (n + kTileKeys - 1) / kTileKeys;
   // F^2: every workgroup of the unit adds the tile sums in the same order and gets the same bits
@@ -487,9 +500,6 @@ __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
     return;
   }
   const double inv = 1152921504606846976.0 / f2;            // masses are integers in units of F^2 / 2^60
-  const int mis = (int)((reinterpret_cast<uintptr_t>(s) >> 2) & 3);
-  const float* al = s - mis;
-  const int span = n + mis;
 
   // ---- first digit over this workgroup's slice
   for (int d = tid; d < kBuckets; d += kT) {
@@ -498,7 +508,7 @@ __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
   }
   __syncthreads();
   int q0, q1;
-  slice_range(n, mis, slice, slices, &q0, &q1);
+  slice_range(n, mis, slice, gridDim.x, &q0, &q1);
   for (int q = q0 + tid * 4; q < q1; q += kT * 4) {
     const float4 v = load_scores4(al, q, mis, span);
     const float f[4] = {v.x, v.y, v.z, v.w};
@@ -525,7 +535,9 @@ __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
       }
     }
     if (!last_arrival(g_arrivals, slices, &sh_flag)) return;
-    // ---- the last workgroup of the unit: the whole unit's first-digit histogram
+  }
+  // ---- the last workgroup of the unit: the whole unit's first-digit histogram
+  if (slices > 1) {
     for (int d = tid; d < kBuckets; d += kT) {
       sh_cnt[d] = __hip_atomic_load(&g_cnt[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       sh_mass[d] = __hip_atomic_load(&g_mass[d], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -596,9 +608,7 @@ __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
     // almost empty one
     constexpr int kBatch = 8;
     const int lane = tid & 63;
-    for (int qb = 0; qb < span; qb += kT * 4 * kBatch) {
-      float4 v[kBatch];
-      load_scores_batch<kBatch>(v, al, qb, mis, span);
+    auto collect = [&](const float4* v, int qb) {
       uint32_t hits = 0;                                   // bit 4 j + e: element e of vector j is in the bucket
 #pragma unroll
       for (int j = 0; j < kBatch; ++j) {
@@ -624,6 +634,11 @@ __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
             if (hits & (1u << (4 * j + e))) sh_cand[base++] = f[e];
         }
       }
+    };
+    for (int qb = 0; qb < span; qb += kT * 4 * kBatch) {
+      float4 v[kBatch];
+      load_scores_batch<kBatch>(v, al, qb, mis, span);
+      collect(v, qb);
     }
     __syncthreads();
   }
@@ -647,6 +662,56 @@ __global__ __launch_bounds__(kT) void select_score_hist_kernel(SelectArgs a) {
       }
     }
   };
+  if (resident && ncand <= kRankDirect) {
+    // Few candidates (the cut often lies among the large scores, whose buckets are thin): every candidate
+    // is ranked among the others directly, count and integer mass of the larger ones and the number of
+    // equal ones, and the one score value at which the rule flips is the final bucket.  (All pairs: beyond
+    // a hundred or so candidates the two digit passes below are cheaper.)
+    uint32_t key_t = 0;
+    uint64_t q_t = 0;
+    if (tid < ncand) {
+      const float x = sh_cand[tid];
+      key_t = order_key(x);
+      q_t = quantise(x, inv);
+      sh_cnt[tid] = key_t;
+      sh_mass[tid] = q_t;
+    }
+    __syncthreads();
+    if (tid < ncand) {
+      uint32_t c = 0, e = 0;
+      uint64_t m = 0;
+#pragma unroll 8
+      for (int j = 0; j < ncand; ++j) {
+        const uint32_t key_j = sh_cnt[j];
+        const uint64_t q_j = sh_mass[j];
+        c += key_j > key_t;
+        m += key_j > key_t ? q_j : 0;
+        e += key_j == key_t;
+      }
+      const int64_t n0 = cnt_above + c;
+      const uint64_t m0 = mass_above + m;
+      if (!pred(n0, m0) && pred(n0 + e, m0 + (uint64_t)e * q_t)) {   // the same values from every equal candidate
+        sh_u64[0] = (uint64_t)n0;
+        sh_u64[1] = m0;
+        sh_u64[2] = q_t;
+        sh_i[1] = (int)key_t;
+        sh_i[3] = (int)e;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      const int64_t above = (int64_t)sh_u64[0];
+      const uint64_t m_above = sh_u64[1], q_each = sh_u64[2];
+      int lo = 1, hi = sh_i[3];                              // pred is true at hi
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (pred(above + mid, m_above + (uint64_t)mid * q_each)) hi = mid;
+        else lo = mid + 1;
+      }
+      publish((int)above + lo, lo, (uint32_t)sh_i[1]);
+    }
+    return;
+  }
   const int shifts[2] = {10, 0}, widths[2] = {11, 10};
   for (int lvl = 0; lvl < 2; ++lvl) {
     const int shift = shifts[lvl], nb = 1 << widths[lvl];
@@ -694,6 +759,7 @@ __global__ __launch_bounds__(kT) void select_score_emit_kernel(SelectArgs a) {
   const int span = n + mis;
   int q0, q1;
   slice_range(n, mis, slice, slices, &q0, &q1);
+  if (q0 >= q1) return;                                    // a short unit: nothing falls to this workgroup
   if (ties < 0) {                                          // everything is kept
     for (int q = q0 + tid; q < q1; q += kT)
       if (q >= mis) idx_pad[q - mis] = q - mis;
@@ -965,11 +1031,8 @@ hipError_t launch_select(const Geometry& g, const SelectArgs& a, hipStream_t str
     // long units: a unit split over several workgroups, then the ordered emit
     SelectArgs args = a;
     const int slices = g.score_slices;
-    const int64_t want = ((int64_t)g.max_seqlen + 3) / 4 * 4;
-    args.lds_floats = (int32_t)(want < kMaxLdsFloats ? want : kMaxLdsFloats);
+    args.lds_floats = kMaxCandidates;              // every workgroup reserves it, only a unit's last one uses it
     const size_t dyn = (size_t)args.lds_floats * sizeof(float);
-    hipError_t e = allow_lds<&select_score_hist_kernel>((size_t)kMaxLdsFloats * sizeof(float));
-    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(select_score_hist_kernel, dim3(slices, g.units), dim3(kT), dyn, stream, args);
     if (a.idx_pad) hipLaunchKernelGGL(select_score_emit_kernel, dim3(slices, g.units), dim3(kT), 0, stream, args);
     return hipGetLastError();
