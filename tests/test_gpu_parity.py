@@ -196,6 +196,47 @@ def test_all_equal_scores_tie_break_lowest_index():
     assert np.all(buf.kept.cpu().numpy() == n)
 
 
+@pytest.mark.parametrize("T", [0.02, 0.31])
+def test_score_ranking_of_long_units_in_a_ragged_batch(T):
+    """Units split over several workgroups (longer than 8192 positions) beside short and empty ones of the same
+    batch, fed straight to rfkv_select, with score patterns that send the last workgroup of a unit down
+    each of its ways: a crossing bucket of a few scores (ranked pair by pair), of thousands (two more radix
+    digits) and of more equal scores than its LDS holds (re-read from memory)."""
+    import torch
+    lens = [20000, 100, 0, 2500, 9001, 12000]
+    Hkv = 2
+    N = sum(lens)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rng = np.random.default_rng(5)
+    host = np.zeros((Hkv, N), np.float32)
+    for b, n in enumerate(lens):
+        s0 = int(cu[b])
+        if n == 0:
+            continue
+        # head 0: a few large scores over a floor of small ones; head 1: per sequence a different shape
+        host[0, s0:s0 + n] = rng.uniform(1e-6, 2e-6, n)
+        host[0, s0 + rng.choice(n, max(1, n // 50), replace=False)] = rng.uniform(0.01, 0.5, max(1, n // 50))
+        if b % 3 == 0:
+            host[1, s0:s0 + n] = rng.uniform(0.25, 0.3, n)              # thousands of scores in one bucket
+        elif b % 3 == 1:
+            host[1, s0:s0 + n] = 0.125                                  # all equal: ties, lowest positions win
+        else:
+            host[1, s0:s0 + n] = np.exp(rng.normal(-8.0, 2.0, n))       # spread over many exponents
+    p = B.make_params(len(lens), 2, Hkv, 128, 1, "bf16", threshold=T, rank_mode=B.RANK_SCORE)
+    cu_d = torch.from_numpy(cu).cuda()
+    scores = torch.from_numpy(host).cuda()
+    buf = B.alloc_layer_buffers(p, N, max(lens))
+    for _ in range(2):                                                  # the second call finds the counters reset
+        buf.kept.fill_(-7)
+        B.rfkv_select(p, scores, cu, cu_d, buf.kept, buf.out_offsets, buf.idx, buf.ws, buf.ws_bytes)
+        torch.cuda.synchronize()
+        kept, offs, idx = O.oracle_select(host.astype(np.float64), cu, O.RANK_SCORE, 4, H.threshold_as_float32(T), 0,
+                                          form="cumsum")
+        assert np.array_equal(buf.kept.cpu().numpy(), kept)
+        assert np.array_equal(buf.out_offsets.cpu().numpy(), offs)
+        assert np.array_equal(buf.idx[:int(offs[-1])].cpu().numpy(), idx)
+
+
 @pytest.mark.parametrize("mode", MODES)
 def test_staged_calls_equal_fused_call(mode):
     # rfkv_score -> rfkv_select -> rfkv_compact give what rfkv_compress_layer gives; strided
