@@ -436,6 +436,7 @@ static void decode_geometry(const rfkv_params* p, int32_t n_new, DecodeArgs* a) 
   a->group = p->n_q_heads / p->n_kv_heads;
   a->n_new = n_new;
   a->rows = n_new * a->group;
+  a->units = units;
   a->rows_pad = a->rows <= 128 ? 128 : 256;
   a->head_dim = p->head_dim;
   a->target_items = a->rows_pad <= 128 ? 512 : 256;
@@ -444,7 +445,7 @@ static void decode_geometry(const rfkv_params* p, int32_t n_new, DecodeArgs* a) 
 }
 
 struct DecodeWs {
-  size_t part_o, part_ml, items, item_begin, bytes;
+  size_t part_o, part_ml, item_begin, bytes;
 };
 static DecodeWs decode_ws(const rfkv_params* p, const DecodeArgs& a) {
   const size_t units = (size_t)p->batch * p->n_kv_heads;
@@ -452,8 +453,7 @@ static DecodeWs decode_ws(const rfkv_params* p, const DecodeArgs& a) {
   DecodeWs w;
   w.part_o = 0;
   w.part_ml = w.part_o + slots * a.head_dim * sizeof(float);
-  w.items = w.part_ml + slots * sizeof(float2);
-  w.item_begin = w.items + (size_t)a.max_items * sizeof(int4);
+  w.item_begin = w.part_ml + slots * sizeof(float2);
   w.bytes = (w.item_begin + (units + 1) * sizeof(int32_t) + 255) / 256 * 256;
   return w;
 }
@@ -501,7 +501,6 @@ static rfkv_status decode_impl(const rfkv_params* params, const void* q_new, int
   unsigned char* base = static_cast<unsigned char*>(ws);
   a.part_o = reinterpret_cast<float*>(base + w.part_o);
   a.part_ml = reinterpret_cast<float2*>(base + w.part_ml);
-  a.items = reinterpret_cast<int4*>(base + w.items);
   a.item_begin = reinterpret_cast<int32_t*>(base + w.item_begin);
   if (masked) {
     a.cu = cu_dev;

@@ -2,10 +2,10 @@
 // uncompressed cache with the evicted positions masked (the consumer of Alg. 1's compressed K / V;
 // Sec. 4.3 compares the two costs).  bf16 storage, fp32 softmax and accumulation, fp32 output.
 //
-// The kept counts differ from unit to unit and are known on the device only, so a one-workgroup
-// planning kernel first cuts every unit's keys into work items of nearly equal length (about as
-// many items as the launch has workgroups to keep every CU busy once).  One workgroup (4
-// wavefronts) then takes one item -- a contiguous range of keys of one unit (sequence, KV head) --
+// The kept counts differ from unit to unit and are known on the device only, so every workgroup first
+// cuts the units' keys into work items of nearly equal length (about as many items as the launch has
+// workgroups to keep every CU busy once; the same arithmetic in every workgroup, no kernel of its own)
+// and takes the item of its index -- a contiguous range of keys of one unit (sequence, KV head) --
 // and all M = n_new * G query rows of that KV head (row = j * G + g), 32 * RTW rows per wavefront:
 //
 //   S^T = K Q^T   32x32x16 bf16 MFMA, keys along M, rows along N: a lane owns one query row and
@@ -125,29 +125,37 @@ __device__ __forceinline__ DUnit load_dunit(const DecodeArgs& a, int unit) {
   return u;
 }
 
-// Work items: item_begin[u] .. item_begin[u + 1] are unit u's; items[i] = {unit, first key, end key, -}.
-// Keys are handed out in chunks of kChunkKeys; every item gets at most C chunks, C chosen so that
-// the items number about `a.target_items` (never more than target_items + units, the launch's grid).
+// Work items: item_begin[u] .. item_begin[u + 1] are unit u's; item i of unit u covers keys
+// [i * C * kChunkKeys, min(len, (i + 1) * C * kChunkKeys)).  Keys are handed out in chunks of kChunkKeys; every
+// item gets at most C chunks, C chosen so that the items number about `a.target_items` (never more than
+// target_items + units, the launch's grid).  Returns workgroup `bx`'s item {unit, first key, end key, -}
+// (unit < 0: the grid has more workgroups than there are items); with `write_table` also writes item_begin
+// (for the merge kernel).  Called by all NT threads of the workgroup.
 constexpr int kChunkKeys = 256;
 
-template <bool MASKED>
-__global__ __launch_bounds__(1024) void decode_plan_kernel(DecodeArgs a, int units) {
-  __shared__ long long sh_tot[16];
-  __shared__ int sh_scan[17];
+template <bool MASKED, int NT>
+__device__ __forceinline__ int4 plan_item(const DecodeArgs& a, int bx, bool write_table) {
+  constexpr int kW = NT / 64;
+  __shared__ long long sh_tot[kW];
+  __shared__ int sh_scan[kW];
+  __shared__ int4 sh_item;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int units = a.units;
   // total chunks
   long long mine = 0;
-  for (int u = tid; u < units; u += 1024) mine += (load_dunit<MASKED>(a, u).len + kChunkKeys - 1) / kChunkKeys;
+  for (int u = tid; u < units; u += NT) mine += (load_dunit<MASKED>(a, u).len + kChunkKeys - 1) / kChunkKeys;
 #pragma unroll
   for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d);
   if (lane == 0) sh_tot[wave] = mine;
+  if (tid == 0) sh_item = make_int4(-1, 0, 0, 0);
   __syncthreads();
   long long total = 0;
-  for (int w = 0; w < 16; ++w) total += sh_tot[w];
+#pragma unroll
+  for (int w = 0; w < kW; ++w) total += sh_tot[w];
   const int C = (int)max(1ll, (total + a.target_items - 1) / a.target_items);
-  // items per unit, exclusive prefix over units in batches of 1024
+  // items per unit, exclusive prefix over units in batches of NT
   int carry = 0;
-  for (int base = 0; base < units; base += 1024) {
+  for (int base = 0; base < units; base += NT) {
     const int u = base + tid;
     int len = 0, cnt = 0;
     if (u < units) {
@@ -165,21 +173,24 @@ __global__ __launch_bounds__(1024) void decode_plan_kernel(DecodeArgs a, int uni
     if (lane == 63) sh_scan[wave] = inc;
     __syncthreads();
     int off = carry, tot = 0;
-    for (int w = 0; w < 16; ++w) {
+#pragma unroll
+    for (int w = 0; w < kW; ++w) {
       if (w < wave) off += sh_scan[w];
       tot += sh_scan[w];
     }
     const int first = off + inc - cnt;
     if (u < units) {
-      a.item_begin[u] = first;
-      for (int i = 0; i < cnt; ++i)
-        a.items[first + i] = make_int4(u, i * C * kChunkKeys, min(len, (i + 1) * C * kChunkKeys), 0);
+      if (write_table) a.item_begin[u] = first;
+      if (bx >= first && bx < first + cnt) {
+        const int i = bx - first;
+        sh_item = make_int4(u, i * C * kChunkKeys, min(len, (i + 1) * C * kChunkKeys), 0);
+      }
     }
     carry += tot;
   }
-  if (tid == 0) a.item_begin[units] = carry;
-  // unused grid slots
-  for (int i = carry + tid; i < a.max_items; i += 1024) a.items[i] = make_int4(-1, 0, 0, 0);
+  if (write_table && tid == 0) a.item_begin[units] = carry;
+  __syncthreads();
+  return sh_item;
 }
 
 template <int D, int RTW, int W, int KT, bool MASKED>
@@ -198,7 +209,7 @@ __global__ __launch_bounds__(W * 64, (W == 4 && RTW == 1) ? 2 : 1) void decode_a
   unsigned char* vsm = dsm + kStages * kStageBytes;
   uint32_t* msm = reinterpret_cast<uint32_t*>(dsm + 2 * kStages * kStageBytes);
   const int bx = blockIdx.x;
-  const int4 item = a.items[bx];
+  const int4 item = plan_item<MASKED, W * 64>(a, bx, bx == 0);
   const int unit = item.x;
   if (unit < 0) return;                                  // uniform for the whole workgroup
   const DUnit u = load_dunit<MASKED>(a, unit);
@@ -560,9 +571,7 @@ hipError_t launch_attn(const DecodeArgs& a, hipStream_t stream) {
 
 template <int D, bool MASKED>
 hipError_t launch_typed(const DecodeArgs& a, int units, hipStream_t stream) {
-  hipLaunchKernelGGL(decode_plan_kernel<MASKED>, dim3(1), dim3(1024), 0, stream, a, units);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
   // up to 128 rows: 4 wavefronts of 32 rows, two workgroups per CU; up to 256: 8 wavefronts of 32 rows
   constexpr int kWBig = 256 / (32 * kDecodeRtw);
   if (a.rows_pad <= 128) e = launch_attn<D, 1, 4, kt_for(D, 4, kDecodeKtSmall), MASKED>(a, stream);

@@ -185,11 +185,10 @@ struct DecodeArgs {
   float* out;               // [B, n_new, Hq, d]
   float* part_o;            // [max_items][rows_pad][d]  unnormalised partial outputs, one slot per work item
   float2* part_ml;          // [max_items][rows_pad]     (reference exponent, sum)
-  int4* items;              // [max_items]  {unit, first key, end key, -}; unit < 0: unused slot
-  int32_t* item_begin;      // [units + 1]  first item of every unit
+  int32_t* item_begin;      // [units + 1]  first item of every unit (written by the attention kernel's first workgroup)
   int64_t k_stride_tok, k_stride_head, v_stride_tok, v_stride_head;   // elements
   int64_t total_tokens;
-  int32_t n_q_heads, n_kv_heads, group, n_new, rows, rows_pad, head_dim;
+  int32_t n_q_heads, n_kv_heads, group, n_new, rows, rows_pad, head_dim, units;
   int32_t target_items;     // items the planner aims for (workgroups that fit the chip at once)
   int32_t max_items;        // target_items + units: the grid and the number of partial slots
   float c;                  // softmax scale * log2(e)
