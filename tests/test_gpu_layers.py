@@ -133,6 +133,42 @@ def test_layers_host_checks():
     assert st == B.RFKV_INVALID_ARG
 
 
+def test_layers_call_replays_from_a_hip_graph():
+    """The whole call captured into a HIP graph (its counters are cleared by a fill kernel, not a memset, and
+    nothing synchronises): three replays with poisoned outputs and eager work of the program in between give
+    the eager call's bits every time."""
+    import torch
+    cfg = W.Config("t", 4, 32, 8, 128, 32, "bf16", batch=2, context=6000)
+    lens = [6000, 1300]
+    host = [W.make_layer(3, li, cfg=cfg, lengths=lens) for li in range(4)]
+    dls = [H.DeviceLayer(l, kv_layout="head_major") for l in host]
+    ls = H.LayerSet(dls)
+    ls.compress()
+    eager = [dl.results() for dl in dls]
+    rep = H.compare_layer(host[2], eager[2], B.RANK_POSITION)
+    assert rep["exact"] >= rep["units"] - 1
+    stream = torch.cuda.Stream()                           # default priority
+    with torch.cuda.stream(stream):
+        ls.compress(stream)                                # warm on the capture stream
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        ls.compress(torch.cuda.current_stream())
+    torch.cuda.synchronize()
+    keys = ("scores", "kept", "out_offsets", "idx", "k_out", "v_out")
+    for replay in range(3):
+        for dl in dls:
+            _poison(dl)
+        torch.cuda.synchronize()
+        graph.replay()
+        for j, dl in enumerate(dls):
+            got = dl.results()                             # synchronises
+            for key in keys:
+                assert np.array_equal(got[key], eager[j][key]), (replay, j, key)
+        dls[replay].compress()                             # an eager per-layer call between the replays
+        torch.cuda.synchronize()
+
+
 @pytest.mark.timeout(900)
 def test_layers_headline_geometry_in_full():
     """The geometry the benchmark times: 30 layers of the 32768-token Llama3-8B-shaped layer (the paper
