@@ -173,7 +173,12 @@ __device__ __forceinline__ int position_cut(const Mass& mass, int n, int m_eff, 
     return v;
   };
   double mine = 0.0;
-  for (int k = k0; k < k1; k += 8) {                       // eight loads in flight, added in rank order
+  double head[8];                                          // the chunk's first eight tile masses, kept for the walk below
+#pragma unroll
+  for (int j = 0; j < 8; ++j) head[j] = k0 + j < k1 ? tile_mass(nt - 1 - (k0 + j)) : 0.0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) mine += head[j];
+  for (int k = k0 + 8; k < k1; k += 8) {                   // eight loads in flight, added in rank order
     double v[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = k + j < k1 ? tile_mass(nt - 1 - (k + j)) : 0.0;
@@ -244,15 +249,31 @@ __device__ __forceinline__ int position_cut(const Mass& mass, int n, int m_eff, 
       __syncthreads();
       if (sh->i[3] == tid) {
         // the tile of this thread's chunk in which the rule is first met (the last one if rounding hides it)
+        // (the first eight masses are still in registers: up to 8 * kThreads tiles, 65536 positions at 256
+        // threads, the walk costs no further trip to memory)
         double run = sink + (tid > 0 ? sh->incl[tid - 1] : 0.0);
         int jstar = nt - k1;
-        for (int k = k0; k + 1 < k1; ++k) {
+        bool found = false;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int k = k0 + j;
+          if (!found && k + 1 < k1) {
+            if (pred(count_through(k), run + head[j])) {
+              jstar = nt - 1 - k;
+              found = true;
+            } else {
+              run += head[j];
+            }
+          }
+        }
+        for (int k = k0 + 8; !found && k + 1 < k1; ++k) {
           const double tm = tile_mass(nt - 1 - k);
           if (pred(count_through(k), run + tm)) {
             jstar = nt - 1 - k;
-            break;
+            found = true;
+          } else {
+            run += tm;
           }
-          run += tm;
         }
         sh->i[4] = jstar;
         sh->dbl[0] = run;
