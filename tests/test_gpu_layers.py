@@ -93,6 +93,25 @@ def test_layers_problems_that_run_layer_after_layer(what):
             assert np.array_equal(one["k_out"], g["k_out"]) and np.array_equal(one["v_out"], g["v_out"])
 
 
+@pytest.mark.parametrize("batch", [128, 129])
+def test_layers_at_the_pipeline_limit_of_units(batch):
+    """512 units (128 sequences x 4 KV heads) are the most the pipeline's copy table holds; one sequence more and
+    the call runs layer after layer.  Both against the oracle, sequence lengths from 1 to a few tiles."""
+    rng = np.random.default_rng(batch)
+    lens = [int(x) for x in rng.integers(1, 200, batch)]
+    lens[5] = 0
+    cfg = W.Config("t", 3, 8, 4, 64, 8, "bf16", batch=batch, context=max(lens))
+    host, dls, got = _run(cfg, lens, 3)
+    for layer, g in zip(host, got):
+        rep = H.compare_layer(layer, g, B.RANK_POSITION)
+        assert rep["exact"] >= rep["units"] - 2, rep
+    _poison(dls[1])
+    dls[1].compress()
+    one = dls[1].results()
+    for key in ("kept", "out_offsets", "idx", "k_out", "v_out"):
+        assert np.array_equal(one[key], got[1][key]), key
+
+
 def test_layers_repeat_runs_are_bit_identical_and_capacity_is_respected():
     import torch
     cfg = W.Config("t", 4, 32, 8, 128, 32, "bf16", batch=1, context=3000)
