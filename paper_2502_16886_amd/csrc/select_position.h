@@ -129,17 +129,29 @@ struct LayerMass {
   const double* tiles;     // head h: tiles + h * tiles_total
   int64_t total_tokens, tiles_total;
   int heads;
+  // Eight heads' loads are issued together and without a branch between them (a load behind a branch is
+  // waited for on the spot: a trip to memory per head), a head past the last reads the last head's word
+  // and counts as zero; then they are added in index order.
   __device__ double pos(int p) const {
     double v = 0.0;
-    for (int h = 0; h < heads; ++h) {
-      const double x = (double)coherent_load(s + (int64_t)h * total_tokens + p);
-      v += x * x;
+    for (int h0 = 0; h0 < heads; h0 += 8) {
+      float x[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[j] = coherent_load(s + (int64_t)min(h0 + j, heads - 1) * total_tokens + p);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v += h0 + j < heads ? (double)x[j] * (double)x[j] : 0.0;
     }
     return v;
   }
   __device__ double tile(int j) const {
     double v = 0.0;
-    for (int h = 0; h < heads; ++h) v += coherent_load(tiles + (int64_t)h * tiles_total + j);
+    for (int h0 = 0; h0 < heads; h0 += 8) {
+      double x[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) x[i] = coherent_load(tiles + (int64_t)min(h0 + i, heads - 1) * tiles_total + j);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v += h0 + i < heads ? x[i] : 0.0;
+    }
     return v;
   }
 };
@@ -156,7 +168,13 @@ __device__ __forceinline__ int position_cut(const Mass& mass, int n, int m_eff, 
   // Sink mass directly; tail mass per 32-position tile (from the scoring kernel), reversed.
   double sink = 0.0;
   if (m_eff <= 32) {                                       // the usual case (m = 4): every thread sums them itself
-    for (int p = 0; p < m_eff; ++p) sink += mass.pos(p);
+    for (int p0 = 0; p0 < m_eff; p0 += 4) {                // four positions' loads in flight, added in order
+      double x[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) x[j] = mass.pos(min(p0 + j, m_eff - 1));
+#pragma unroll
+      for (int j = 0; j < 4; ++j) sink += p0 + j < m_eff ? x[j] : 0.0;
+    }
   } else {
     for (int p = tid; p < m_eff; p += kThreads) sink += mass.pos(p);
     sink = block_sum_double<kThreads>(sink, sh->dbl);
@@ -172,16 +190,29 @@ __device__ __forceinline__ int position_cut(const Mass& mass, int n, int m_eff, 
     for (int p = min(n, (j + 1) * kTileKeys) - 1; p >= m_eff; --p) v += mass.pos(p);
     return v;
   };
+  // Tail masses of the tiles of ranks k .. k + 7 of this thread's chunk: eight loads in flight with no branch
+  // between them (ranks past the chunk read a tile of the chunk and count as zero); the one tile of the unit
+  // that the sinks share is put right afterwards.
+  auto tile_masses = [&](double* v, int k) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = mass.tile(nt - 1 - min(k + j, max(k1 - 1, 0)));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int jt = nt - 1 - (k + j);
+      if (k + j >= k1) v[j] = 0.0;
+      else if (jt == jm && m_eff % kTileKeys != 0) v[j] = tile_mass(jt);
+    }
+  };
   double mine = 0.0;
   double head[8];                                          // the chunk's first eight tile masses, kept for the walk below
 #pragma unroll
-  for (int j = 0; j < 8; ++j) head[j] = k0 + j < k1 ? tile_mass(nt - 1 - (k0 + j)) : 0.0;
+  for (int j = 0; j < 8; ++j) head[j] = 0.0;
+  if (k0 < k1) tile_masses(head, k0);
 #pragma unroll
   for (int j = 0; j < 8; ++j) mine += head[j];
-  for (int k = k0 + 8; k < k1; k += 8) {                   // eight loads in flight, added in rank order
+  for (int k = k0 + 8; k < k1; k += 8) {                   // added in rank order
     double v[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = k + j < k1 ? tile_mass(nt - 1 - (k + j)) : 0.0;
+    tile_masses(v, k);
 #pragma unroll
     for (int j = 0; j < 8; ++j) mine += v[j];
   }
