@@ -756,7 +756,6 @@ __global__ __launch_bounds__(kT) void select_score_emit_kernel(SelectArgs a) {
   const uint32_t key_cut = (uint32_t)cut.w;
   const int mis = (int)((reinterpret_cast<uintptr_t>(s) >> 2) & 3);
   const float* al = s - mis;
-  const int span = n + mis;
   int q0, q1;
   slice_range(n, mis, slice, slices, &q0, &q1);
   if (q0 >= q1) return;                                    // a short unit: nothing falls to this workgroup
