@@ -41,6 +41,8 @@ def _run(cfg, lens, n_layers, mode=B.RANK_POSITION, kv_layout="token_major", see
     (32, 8, 128, 32, "bf16", [1500, 333, 0, 40], 4, "head_major"),      # ragged, an empty sequence, 32 units
     (8, 8, 64, 16, "bf16", [300, 1, 45, 1029], 2, "token_major"),       # G = 1, d = 64, a length-1 sequence
     (8, 2, 64, 32, "fp32", [640, 33], 3, "token_major"),                # fp32
+    (8, 2, 128, 8, "fp32", [513, 64], 3, "head_major"),                 # fp32 d = 128: 512-byte rows, one workgroup per CU
+    (8, 2, 128, 16, "fp32", [300], 2, "token_major"),                   # fp32 d = 128, two row tiles
     (8, 2, 128, 24, "bf16", [5000, 20], 5, "head_major"),               # 96 rows; several spans per unit
     (4, 1, 128, 5, "bf16", [3, 2, 4, 70], 2, "token_major"),            # n <= m
 ])
