@@ -258,12 +258,44 @@ def time_all_layers(torch, np, H, B, W, host_layers, cfg, n_layers=30, replays=M
     alg = algorithmic_bytes(n, cfg.n_kv_heads, cfg.head_dim, e, cfg.n_q_heads, wrows, kept, dls[0].batch * cfg.n_kv_heads, False)
     del ls, dls
     torch.cuda.empty_cache()
-    return {"entry_point": "rfkv_compress_layers", "layers_per_call": n_layers, "streams": 1,
+    as_batch = time_layers_as_batch(torch, np, H, W, host_layers, cfg, n_layers, replays, alg)
+    return {"entry_point": "rfkv_compress_layers", "layers_per_call": n_layers, "streams": 1, "as_batch": as_batch,
             "retained_fraction": round(kept / (n * cfg.n_kv_heads), 4),
             "ms_per_call": round(ms, 4), "ms_per_layer": round(ms / n_layers, 5),
             "ms_per_layer_min_max": [round(float(per.min()) / n_layers, 5), round(float(per.max()) / n_layers, 5)],
             "tokens_per_s_per_layer_pass": round(n / (ms / n_layers * 1e-3), 1),
             "frac": round(alg / (ms / n_layers * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
+
+def time_layers_as_batch(torch, np, H, W, host_layers, cfg, n_layers, replays, alg_per_layer):
+    """The same layers once more, as a batch: a layer is to rfkv_compress_layer what a sequence is, so caches
+    that sit in one allocation ([layer, token, head, d]) are compressed by ONE call of the per-layer entry
+    point with one launch of each kernel over all layers (no ramp, launch gap or tail per layer)."""
+    src = [host_layers[i % len(host_layers)] for i in range(n_layers)]
+    n = int(src[0].cu_seqlens[-1])
+    cat = W.Layer(cfg=cfg, q_win=np.concatenate([l.q_win for l in src]), k=np.concatenate([l.k for l in src]),
+                  v=np.concatenate([l.v for l in src]),
+                  cu_seqlens=np.concatenate([[0], np.cumsum(np.concatenate([np.diff(l.cu_seqlens) for l in src]))]).astype(np.int32))
+    dl = H.DeviceLayer(cat, kv_layout="token_major")       # [layer * token, head, d]
+    del cat
+    for _ in range(2):
+        dl.compress()
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(replays + 1)]
+    marks[0].record()
+    for r in range(replays):
+        dl.compress()
+        marks[r + 1].record()
+    torch.cuda.synchronize()
+    per = np.array([marks[r].elapsed_time(marks[r + 1]) for r in range(replays)]) / n_layers
+    ms = float(np.median(per))
+    out = {"entry_point": "rfkv_compress_layer, the layers as a batch of sequences in one allocation", "streams": 1,
+           "ms_per_layer": round(ms, 5), "ms_per_layer_min_max": [round(float(per.min()), 5), round(float(per.max()), 5)],
+           "tokens_per_s_per_layer_pass": round(n / (ms * 1e-3), 1),
+           "frac": round(alg_per_layer / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    del dl
+    torch.cuda.empty_cache()
+    return out
 
 
 def time_config(torch, np, H, B, W, cfg_id, streams, buffers=8, gen=2):
