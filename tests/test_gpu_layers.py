@@ -126,6 +126,15 @@ def test_layers_repeat_runs_are_bit_identical_and_capacity_is_respected():
     for a, b in zip(first, again):
         for key in a:
             assert np.array_equal(a[key], b[key]), key
+    # without the optional outputs (scores, index lists), as the benchmark calls it: the same cache
+    for dl in dls:
+        _poison(dl)
+    ls.compress(with_scores=False, with_idx=False)
+    for a, dl in zip(first, dls):
+        b = dl.results()
+        for key in ("kept", "out_offsets", "k_out", "v_out"):
+            assert np.array_equal(a[key], b[key]), key
+        assert np.all(np.isnan(b["scores"])) and np.all(b["idx"] == -7)       # left alone
     # too small an output: rows past the capacity are not written, the offsets still tell the need
     total = int(first[0]["out_offsets"][-1])
     cap = total // 2
