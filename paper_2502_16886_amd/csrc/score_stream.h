@@ -32,12 +32,14 @@ __device__ __forceinline__ void merge_unit_statistics(const ScoreArgs& a, const 
     sum[j] = 0.f;
   }
   for (int s = sub; s < nsp; s += 32) {
+    // all J loads in flight, no branch between them (a load behind a branch is waited for on the spot); rows
+    // that do not exist read an existing row's word and are replaced
     float2 v[J];
 #pragma unroll
-    for (int j = 0; j < J; ++j) {
-      const int r = j * 8 + rr;
-      v[j] = r < u.rows ? coherent_load(p + (int64_t)s * a.rows_pad + r) : make_float2(-1e30f, 0.f);
-    }
+    for (int j = 0; j < J; ++j) v[j] = coherent_load(p + (int64_t)s * a.rows_pad + min(j * 8 + rr, u.rows - 1));
+#pragma unroll
+    for (int j = 0; j < J; ++j)
+      if (j * 8 + rr >= u.rows) v[j] = make_float2(-1e30f, 0.f);
 #pragma unroll
     for (int j = 0; j < J; ++j) {
       const float nm = fmaxf(m[j], v[j].x);
