@@ -36,26 +36,12 @@ __global__ __launch_bounds__(256, 2) void score_stream_kernel(ScoreArgs a) {
   score_stream_body<T, D, RT_T, PASS, WIDE>(a, blockIdx.x, blockIdx.y, lds);
 }
 
-// First kernel of a call: the arrival counters start at zero.
-__global__ __launch_bounds__(256) void score_prepare_kernel(int32_t* counters, int n) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < n) counters[i] = 0;
-}
-
 // Scores from kept logits (PASS 3): one thread per key.  x_r = q_r . k (unscaled), c = scale * log2 e,
 // b_r = reference + log2(sum * G) from the merge: score = sum_r 2^(x_r c - b_r) / (rows that see the key).
 __global__ __launch_bounds__(256) void score_spill_reduce_kernel(ScoreArgs a) {
-  __shared__ PositionShared<kStreamThreads> sh_pos;
-  __shared__ int sh_flag;
   const Unit u = load_unit(a, blockIdx.y);
   const int key0 = blockIdx.x * 256;
-  if (key0 >= u.n) {                                   // uniform for the whole workgroup
-    if (a.fuse_select && u.n == 0 && blockIdx.x == 0 && threadIdx.x == 0) {
-      a.kept[blockIdx.y] = 0;
-      a.desc[blockIdx.y] = make_int4(0, 0, 0, 0);
-    }
-    return;
-  }
+  if (key0 >= u.n) return;                             // uniform for the whole workgroup
   const int key = key0 + threadIdx.x;
   float sum = 0.f;
   if (key < u.n) {
@@ -69,22 +55,16 @@ __global__ __launch_bounds__(256) void score_spill_reduce_kernel(ScoreArgs a) {
   }
   const float score = key < u.n ? sum / (float)min(u.wp, u.n - key) : 0.f;
   float* score_out = a.scores + (int64_t)u.h * a.total_tokens + u.s0 + key;
-  if (key < u.n) {
-    if (a.fuse_select) coherent_store(score_out, score);
-    else *score_out = score;
-  }
+  if (key < u.n) *score_out = score;
   // per-tile squared sums: the butterfly of tile_sum_sq, in both halves of the wavefront at once
   double v = (double)score * (double)score;
 #pragma unroll
   for (int d = 16; d >= 1; d >>= 1) v += __shfl_xor(v, d);
   if ((threadIdx.x & 31) == 0 && key < u.n) {
     double* tsq_out = a.tile_sq + (int64_t)u.h * a.tiles_total + u.tile_base + (key >> 5);
-    if (a.fuse_select) coherent_store(tsq_out, v);
-    else *tsq_out = v;
+    *tsq_out = v;
   }
   if (a.sel_block && blockIdx.x == 0) clear_select_block(a.sel_block, blockIdx.y);
-  if (a.fuse_select && last_arrival(a.counters + a.units + blockIdx.y, (u.n + 255) / 256, &sh_flag))
-    cut_unit(a, u, blockIdx.y, &sh_pos);
 }
 
 template <typename T, int D>
@@ -149,11 +129,6 @@ bool score_qreg_covers(const Geometry& g, bool bf16) {
 
 hipError_t launch_score_qreg(const Geometry& g, const ScoreArgs& a, bool bf16, hipStream_t stream,
                              const Marks* marks) {
-  if (a.fuse_merge || a.fuse_select) {                 // arrival counters start at zero
-    hipLaunchKernelGGL(score_prepare_kernel, dim3((2 * g.units + 255) / 256), dim3(256), 0, stream, a.counters, 2 * g.units);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
   if (bf16) {
     if (g.head_dim == 64) return launch_stream_rt<Bf16, 64>(g, a, stream, marks);
     return launch_stream_rt<Bf16, 128>(g, a, stream, marks);
