@@ -316,7 +316,7 @@ using namespace rfkv;
 
 extern "C" {
 
-int32_t rfkv_version(void) { return 100; }
+int32_t rfkv_version(void) { return 200; }
 
 const char* rfkv_status_string(rfkv_status status) {
   switch (status) {
